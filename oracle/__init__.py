@@ -1,0 +1,172 @@
+"""CPU oracle of the sparse decode step -- TEST INFRASTRUCTURE, not product code.
+
+Thin ctypes access to ``sv_oracle.c`` (plain C, double precision; the three
+steps of the paper's section 3.2 written out as their definitions).  Only
+``tests/``, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this package; the HIP library and its Python binding never do, and
+this package imports nothing from them.
+
+Arrays are numpy, contiguous, ``[B, Hkv, N, D]`` for K/V and ``[B, Hq, D]``
+for q; dtype float16 or float32 decides how the C code widens the bits.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sv_oracle.c")
+_LIB = os.path.join(_HERE, "libsv_oracle.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile sv_oracle.c with gcc (OpenMP over independent (batch, head) units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, ip, dp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+        i, d = ctypes.c_int, ctypes.c_double
+        lib.svo_half_to_double.restype = ctypes.c_double
+        lib.svo_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.svo_score_visual.restype = i
+        lib.svo_score_visual.argtypes = [i, i, i, i, i, i, d, vp, vp, ip, dp]
+        lib.svo_topk_select.restype = i
+        lib.svo_topk_select.argtypes = [i, i, i, i, dp, ip, ip, ip]
+        lib.svo_sparse_decode_attn.restype = i
+        lib.svo_sparse_decode_attn.argtypes = [i, i, i, i, i, i, i, i, d, vp, vp, vp, vp, vp,
+                                               ip, ip, ip, dp, dp, dp]
+        lib.svo_decode_step.restype = i
+        lib.svo_decode_step.argtypes = [i, i, i, i, i, i, i, i, d, vp, vp, vp, vp, vp,
+                                        ip, ip, dp, ip, ip, dp, dp, dp]
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float16:
+        return 0
+    if a.dtype == np.float32:
+        return 1
+    raise TypeError(f"oracle inputs must be float16 or float32, got {a.dtype}")
+
+
+def _c(a: np.ndarray, dtype=None) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _lens(x, B: int) -> Optional[np.ndarray]:
+    if x is None:
+        return None
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    assert x.shape == (B,)
+    return x
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().svo_half_to_double(int(bits)))
+
+
+def default_scale(D: int) -> float:
+    return 1.0 / float(np.sqrt(np.float64(D)))
+
+
+def score_visual(q, k_vis, vis_len=None, scale: Optional[float] = None) -> np.ndarray:
+    """Step 1: float64 scores [B, Hkv, Nv]; -inf beyond vis_len."""
+    q, k_vis = _c(q), _c(k_vis)
+    B, Hq, D = q.shape
+    _, Hkv, Nv, _ = k_vis.shape
+    assert k_vis.shape == (B, Hkv, Nv, D) and q.dtype == k_vis.dtype
+    vl = _lens(vis_len, B)
+    s = np.empty((B, Hkv, Nv), dtype=np.float64)
+    rc = _load().svo_score_visual(B, Hq, Hkv, D, Nv, _dtype_code(q),
+                                  default_scale(D) if scale is None else scale,
+                                  _ptr(q), _ptr(k_vis), _ptr(vl), _ptr(s))
+    if rc:
+        raise ValueError(f"svo_score_visual failed: {rc}")
+    return s
+
+
+def topk_select(scores, k: int, vis_len=None):
+    """Step 2: (idx [B,Hkv,k] int32 ascending, -1 padded; count [B,Hkv] int32)."""
+    s = _c(scores, np.float64)
+    B, Hkv, Nv = s.shape
+    vl = _lens(vis_len, B)
+    idx = np.full((B, Hkv, max(k, 0)), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    rc = _load().svo_topk_select(B, Hkv, Nv, k, _ptr(s), _ptr(vl), _ptr(idx), _ptr(cnt))
+    if rc:
+        raise ValueError(f"svo_topk_select failed: {rc}")
+    return idx, cnt
+
+
+def sparse_decode_attn(q, k_vis, v_vis, k_txt, v_txt, idx, count, txt_len=None,
+                       scale: Optional[float] = None):
+    """Step 3: (out [B,Hq,D] f64, lse [B,Hq] f64, wsum [B,Hq] f64)."""
+    q, k_vis, v_vis, k_txt, v_txt = map(_c, (q, k_vis, v_vis, k_txt, v_txt))
+    B, Hq, D = q.shape
+    _, Hkv, Nv, _ = k_vis.shape
+    Nt = k_txt.shape[2]
+    assert v_vis.shape == k_vis.shape and v_txt.shape == k_txt.shape
+    assert k_txt.shape == (B, Hkv, Nt, D)
+    assert len({a.dtype for a in (q, k_vis, v_vis, k_txt, v_txt)}) == 1
+    idx = _c(idx, np.int32)
+    count = _c(count, np.int32)
+    k = idx.shape[2]
+    assert idx.shape == (B, Hkv, k) and count.shape == (B, Hkv)
+    tl = _lens(txt_len, B)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    wsum = np.empty((B, Hq), dtype=np.float64)
+    rc = _load().svo_sparse_decode_attn(B, Hq, Hkv, D, Nv, Nt, k, _dtype_code(q),
+                                        default_scale(D) if scale is None else scale,
+                                        _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
+                                        _ptr(tl), _ptr(idx), _ptr(count),
+                                        _ptr(out), _ptr(lse), _ptr(wsum))
+    if rc:
+        raise ValueError(f"svo_sparse_decode_attn failed: {rc}")
+    return out, lse, wsum
+
+
+def decode_step(q, k_vis, v_vis, k_txt, v_txt, k: int, vis_len=None, txt_len=None,
+                scale: Optional[float] = None) -> dict:
+    """Steps 1-3 chained.  Returns dict(scores, idx, count, out, lse, wsum)."""
+    q, k_vis, v_vis, k_txt, v_txt = map(_c, (q, k_vis, v_vis, k_txt, v_txt))
+    B, Hq, D = q.shape
+    _, Hkv, Nv, _ = k_vis.shape
+    Nt = k_txt.shape[2]
+    assert v_vis.shape == k_vis.shape and v_txt.shape == k_txt.shape
+    assert len({a.dtype for a in (q, k_vis, v_vis, k_txt, v_txt)}) == 1
+    vl, tl = _lens(vis_len, B), _lens(txt_len, B)
+    scores = np.empty((B, Hkv, Nv), dtype=np.float64)
+    idx = np.full((B, Hkv, max(k, 0)), -1, dtype=np.int32)
+    cnt = np.zeros((B, Hkv), dtype=np.int32)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    wsum = np.empty((B, Hq), dtype=np.float64)
+    rc = _load().svo_decode_step(B, Hq, Hkv, D, Nv, Nt, k, _dtype_code(q),
+                                 default_scale(D) if scale is None else scale,
+                                 _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
+                                 _ptr(vl), _ptr(tl), _ptr(scores), _ptr(idx), _ptr(cnt),
+                                 _ptr(out), _ptr(lse), _ptr(wsum))
+    if rc:
+        raise ValueError(f"svo_decode_step failed: {rc}")
+    return dict(scores=scores, idx=idx, count=cnt, out=out, lse=lse, wsum=wsum)
