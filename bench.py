@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse decode step (score -> top-k -> sparse attention) on one MI355X.
+
+One "step" is one sv_decode_step over the whole workload: for the long-video config
+that is all 28 independent layers folded into the batch dimension (one launch per
+stage).  Inputs are synthetic, seeded, and resident in HBM before timing starts.
+
+Prints ONE JSON line.  Besides the step latency it carries
+  roofline      the scoring kernel (it moves ~88 % of the step's algorithmic bytes):
+                bytes of visual K per launch / its mean duration measured with HIP
+                events on the launch stream, against the 8 TB/s HBM peak;
+  cpu_baseline  the CPU oracle (plain C, fp64, OpenMP over independent units) timed on
+                a bounded sample of the same inputs on this host's cores;
+  parity        index-set rule statistics (boundary tie counts) and output error of the
+                GPU result against the oracle on that same sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = long video, the graded one)")
+    ap.add_argument("--oracle-layers", type=int, default=4,
+                    help="how many leading batch entries the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--gen-workers", type=int, default=min(16, len(os.sched_getaffinity(0))))
+    ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
+                    help="launch-shape knob for sweeps, e.g. --set attn_chunk=256")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2510_17777_amd as sv
+    import sv_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sv.load_library()
+    for item in args.set:
+        name, val = item.split("=")
+        sv.sv_set_tuning(name, int(val))
+
+    w = sv_inputs.workload(args.config)
+    t0 = time.time()
+    inp = sv_inputs.make_inputs(w, workers=args.gen_workers)
+    t_gen = time.time() - t0
+    dev = "cuda:0"
+    d = {n: torch.from_numpy(inp[n]).to(dev) for n in ("q", "k_vis", "v_vis", "k_txt", "v_txt")}
+    ragged = w.structure == "ragged"
+    vis_len = inp["vis_len"] if ragged else None
+    txt_len = inp["txt_len"] if ragged else None
+    shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], w.k, vis_len=vis_len, txt_len=txt_len)
+    buf = sv.DecodeBuffers(shape, dev, with_scores=True)
+    queries = [d["q"]]
+    for rnd in range(1, w.rounds):
+        queries.append(torch.from_numpy(sv_inputs.round_query(w, rnd)).to(dev))
+
+    def step(i: int):
+        sv.sv_decode_step(shape, queries[i % len(queries)], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"],
+                          buf.scores, buf.idx, buf.count, buf.out, buf.lse, buf.workspace)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_per_step = wall / args.steps * 1e6
+
+    # The scoring kernel alone, bracketed by events on the stream it is launched on.
+    stream = torch.cuda.current_stream()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    for i in range(args.steps):
+        evs[i][0].record(stream)
+        sv.sv_score_visual(shape, queries[i % len(queries)], d["k_vis"], buf.scores, stream)
+        evs[i][1].record(stream)
+    torch.cuda.synchronize()
+    score_us = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+
+    # Leave the buffers holding the result of a step with query 0 for the parity report.
+    step(0)
+    torch.cuda.synchronize()
+
+    algo_bytes = sv_inputs.algorithmic_bytes(w, inp["vis_len"], inp["txt_len"])
+    k_bytes = int(w.n_kv_heads * w.head_dim * w.elem_size * inp["vis_len"].astype(np.int64).sum())
+    step_gbps = algo_bytes / (us_per_step * 1e-6) / 1e9
+    score_gbps = k_bytes / (float(score_us.mean()) * 1e-6) / 1e9
+
+    result = {
+        "metric": "sparse_decode_step_latency", "value": round(us_per_step, 2), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_per_step / 1e3, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg{w.cfg}_{w.name}", "batch": w.batch, "layers_folded": w.layers,
+                   "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "n_visual": w.n_vis, "n_text": w.n_txt, "k": w.k, "mode": "folded_layers_one_call",
+                   "score_rows_per_block": sv.sv_get_tuning("score_rows_per_block"),
+                   "attn_chunk": sv.sv_get_tuning("attn_chunk")},
+        "step_algorithmic_bytes": algo_bytes,
+        "step_achieved_GBps": round(step_gbps, 1),
+        "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": round(score_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "bytes_per_launch": k_bytes,
+                     "mean_us": round(float(score_us.mean()), 2), "median_us": round(float(np.median(score_us)), 2)},
+        "input_gen_s": round(t_gen, 1),
+    }
+
+    if args.oracle_layers > 0:
+        import oracle
+        from oracle.compare import check_index_sets, out_tolerance
+        nb = min(args.oracle_layers * w.batch, w.B)
+        sub = {n: inp[n][:nb] for n in ("q", "k_vis", "v_vis", "k_txt", "v_txt")}
+        vl = inp["vis_len"][:nb] if ragged else None
+        tl = inp["txt_len"][:nb] if ragged else None
+        cores = len(os.sched_getaffinity(0))
+        os.environ.setdefault("OMP_NUM_THREADS", str(cores))
+        t0 = time.perf_counter()
+        ref = oracle.decode_step(sub["q"], sub["k_vis"], sub["v_vis"], sub["k_txt"], sub["v_txt"], w.k,
+                                 vis_len=vl, txt_len=tl)
+        t_oracle = time.perf_counter() - t0
+        threads = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        result["cpu_baseline"] = {
+            "value": round(t_oracle / nb * w.B * 1e6, 1), "unit": "us", "cores": threads, "kind": "oracle",
+            "sample": f"first {nb} of {w.B} batch entries (layers) of the same inputs, one oracle step "
+                      f"took {t_oracle:.2f} s; value = that time scaled by {w.B}/{nb}"}
+        idx, cnt = buf.idx[:nb].cpu().numpy(), buf.count[:nb].cpu().numpy()
+        rep = check_index_sets(ref["scores"], w.k, vl, idx, cnt)
+        ref_out, _, _ = oracle.sparse_decode_attn(sub["q"], sub["k_vis"], sub["v_vis"], sub["k_txt"],
+                                                  sub["v_txt"], idx, cnt, txt_len=tl)
+        err = float(np.abs(buf.out[:nb].cpu().numpy() - ref_out).max())
+        result["parity"] = dict(rep.summary(), out_max_abs_err=err, out_tol=out_tolerance(w.np_dtype),
+                                ok=bool(rep.ok and err <= out_tolerance(w.np_dtype)))
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

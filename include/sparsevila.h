@@ -1,0 +1,172 @@
+/*
+ * sparsevila.h -- C ABI of the MI355X (gfx950) sparse decode library.
+ *
+ * One decode step of SparseVILA's decode stage (paper section 3.2, "Decode
+ * Phase: Query-Aware Retrieval"): the visual part of the KV cache stays
+ * resident in full; for the current query the library
+ *   (1) scores every cached visual key         -> sv_score_visual
+ *   (2) keeps the k highest-scoring tokens     -> sv_topk_select
+ *   (3) attends over all text tokens plus the
+ *       kept visual tokens                     -> sv_sparse_decode_attn
+ * and sv_decode_step chains the three.  The paper retrieves once per
+ * conversation round and then decodes many tokens; that use is
+ * sv_score_visual + sv_topk_select once, then sv_sparse_decode_attn per token
+ * with the same idx.  Retrieving at every step is sv_decode_step.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ * Pointers.  The sv_shape struct itself is HOST memory.  Every other pointer
+ *   (q, k_*, v_*, scores, idx, count, out, lse, workspace, and the vis_len /
+ *   txt_len pointers stored inside sv_shape) is DEVICE memory owned by the
+ *   caller.  The library never allocates, frees or keeps a pointer after the
+ *   call returns; q/K/V/vis_len/txt_len are only read.
+ * Layout.  head_dim is contiguous everywhere.  q is [B, Hq, D] addressed with
+ *   q_stride_b/q_stride_h; visual K and V share one set of strides
+ *   [B, Hkv, n_vis_max, D] (kv_vis_stride_*), text K and V another
+ *   (kv_txt_stride_*).  Strides are in ELEMENTS.  Outputs are dense:
+ *   scores [B, Hkv, n_vis_max] float, idx [B, Hkv, k] int32, count [B, Hkv]
+ *   int32, out [B, Hq, D] float, lse [B, Hq] float.
+ * Alignment.  Every K/V/q base pointer and every row (stride * element size)
+ *   must be a multiple of 16 bytes: rows are read with 128-bit loads.
+ * Groups.  Query head h reads kv head h / (Hq / Hkv).
+ * Ragged batches.  vis_len[b] <= n_vis_max and txt_len[b] <= n_txt_max give the
+ *   live rows of sequence b; NULL means "all rows".  Rows past the length are
+ *   never read.
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).  All work is enqueued asynchronously; nothing synchronises the
+ *   host.  Results are valid once the caller has synchronised the stream.
+ * Errors.  The return value is an sv_status; SV_OK is 0, errors are negative.
+ *   Arguments are checked on the host before anything is launched, so a failed
+ *   call has launched nothing.  A launch failure reported by the HIP runtime
+ *   maps to SV_ERR_LAUNCH.  Nothing is printed and nothing is thrown.
+ * Determinism.  Equal inputs give bit-identical scores, idx, count, out, lse.
+ * Inputs are assumed finite; behaviour on NaN is unspecified.
+ */
+#ifndef SPARSEVILA_H
+#define SPARSEVILA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SV_OK = 0,
+    SV_ERR_NULL = -1,      /* a required pointer is NULL                          */
+    SV_ERR_SHAPE = -2,     /* sizes/strides out of range or inconsistent          */
+    SV_ERR_DTYPE = -3,     /* dtype is neither SV_F16 nor SV_F32                  */
+    SV_ERR_ALIGN = -4,     /* a base pointer or row stride is not 16-byte aligned */
+    SV_ERR_WORKSPACE = -5, /* workspace missing, misaligned or too small          */
+    SV_ERR_LAUNCH = -6     /* the HIP runtime rejected a launch                   */
+} sv_status;
+
+typedef enum { SV_F16 = 0, SV_F32 = 1 } sv_dtype;
+
+typedef struct sv_shape {
+    int32_t batch;       /* B >= 1; independent layers may be folded in here        */
+    int32_t n_q_heads;   /* Hq, a multiple of n_kv_heads                             */
+    int32_t n_kv_heads;  /* Hkv >= 1                                                 */
+    int32_t head_dim;    /* D: 64 or 128                                             */
+    int32_t n_vis_max;   /* rows of the visual segment per (b, kv head), >= 0        */
+    int32_t n_txt_max;   /* rows of the text segment per (b, kv head), >= 0          */
+    int32_t k;           /* visual tokens to keep, >= 0; k_b = min(k, vis_len[b])    */
+    int32_t dtype;       /* sv_dtype of q, K and V                                   */
+    float scale;         /* softmax / score scale; 0 selects 1/sqrt(D)               */
+    int32_t reserved;    /* must be 0                                                */
+    const int32_t *vis_len; /* DEVICE [B] or NULL                                    */
+    const int32_t *txt_len; /* DEVICE [B] or NULL                                    */
+    int64_t q_stride_b, q_stride_h;
+    int64_t kv_vis_stride_b, kv_vis_stride_h, kv_vis_stride_n;
+    int64_t kv_txt_stride_b, kv_txt_stride_h, kv_txt_stride_n;
+} sv_shape;
+
+/* Fills the eight stride fields for dense row-major tensors of this shape. */
+void sv_shape_set_contiguous(sv_shape *shape);
+
+/*
+ * Bytes of device workspace that sv_topk_select, sv_sparse_decode_attn and
+ * sv_decode_step need for this shape (the maximum over the three; it covers the
+ * split partial results of step 3 and, for sv_decode_step called without a
+ * scores buffer, the scores).  Returns 0 for an invalid shape.  The workspace
+ * must be 256-byte aligned; its contents need not be preserved between calls.
+ */
+size_t sv_workspace_bytes(const sv_shape *shape);
+
+/*
+ * Step 1 -- query-aware relevance (section 3.2, "Query-Aware Token Selection":
+ * the aggregate attention strength between the query and each visual entry of
+ * the KV cache).  The paper gives no formula; the aggregate used here is the
+ * sum, over the query heads of the key's GQA group, of the scaled logit:
+ *   scores[b,g,j] = sum_{h in group g} scale * <q[b,h,:], k_vis[b,g,j,:]>,
+ * accumulated in fp32, for j < vis_len[b]; -inf for vis_len[b] <= j < n_vis_max.
+ * k and the text fields of the shape are ignored.
+ */
+sv_status sv_score_visual(const sv_shape *shape, const void *q, const void *k_vis,
+                          float *scores, void *stream);
+
+/*
+ * Step 2 -- retention (section 3.2: the tokens with the highest relevance are
+ * kept for decoding, the rest stay cached but inactive).  For every (b, g):
+ * idx[b,g,0..count) = the k_b = min(k, vis_len[b]) indices j < vis_len[b] with
+ * the largest scores[b,g,j]; equal scores are resolved toward the lower index
+ * (+0 and -0 are equal); indices ascend; idx[b,g,count..k) = -1;
+ * count[b,g] = k_b.  Only the visual fields and k of the shape are used.
+ * Integer-exact: the result is the unique set defined above for the given
+ * float scores.  k == 0 is valid (nothing is written to idx).
+ */
+sv_status sv_topk_select(const sv_shape *shape, const float *scores,
+                         int32_t *idx, int32_t *count,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Step 3 -- sparse decode attention (section 3.2, first paragraph: only the
+ * most query-relevant visual tokens take part in decoding attention; section
+ * 4.5, "Decoding Attention Kernel Efficiency": the step is bound by KV-cache
+ * traffic, which shrinks with the kept set).  For every query head h with kv
+ * head g: one softmax over T = text tokens i < txt_len[b] followed by visual
+ * tokens idx[b,g,0..count[b,g]), logits scale * <q[b,h,:], key>,
+ *   out[b,h,:] = sum_t softmax_t * value_t      lse[b,h] = log sum_t exp(logit_t).
+ * The caller appends the current token's own K/V to the text segment before the
+ * call; there is no mask and no rotary embedding inside.  idx entries must lie
+ * in [0, vis_len[b]); count[b,g] <= k.  With k == 0, idx and count may be NULL
+ * (text-only attention).  A (b,g) with no token at all yields out = 0 and
+ * lse = -inf.  lse may be NULL.  Accumulation is fp32; T is processed in
+ * chunks whose partial results are merged by a second pass.
+ */
+sv_status sv_sparse_decode_attn(const sv_shape *shape, const void *q,
+                                const void *k_vis, const void *v_vis,
+                                const void *k_txt, const void *v_txt,
+                                const int32_t *idx, const int32_t *count,
+                                float *out, float *lse,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Steps 1 -> 2 -> 3 on one stream.  scores may be NULL (the workspace then
+ * holds them); idx and count are outputs and are required when k > 0; with k == 0
+ * count, if given, is set to 0.
+ */
+sv_status sv_decode_step(const sv_shape *shape, const void *q,
+                         const void *k_vis, const void *v_vis,
+                         const void *k_txt, const void *v_txt,
+                         float *scores, int32_t *idx, int32_t *count,
+                         float *out, float *lse,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *sv_strerror(sv_status status);
+
+/*
+ * Launch-shape knobs for measurement sweeps (not needed for correct use):
+ * "score_rows_per_block", "attn_chunk".  Values outside the documented range of
+ * a knob are rejected with SV_ERR_SHAPE and change nothing; 0 restores the
+ * default.  Process-wide; not thread-safe against concurrent calls.
+ */
+sv_status sv_set_tuning(const char *name, int32_t value);
+int32_t sv_get_tuning(const char *name);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSEVILA_H */

@@ -1,0 +1,11 @@
+"""MI355X (gfx950) sparse decode path of SparseVILA: score -> top-k -> sparse attention.
+
+The package is a thin ctypes binding over ``libsparsevila.so`` (hand-written HIP
+kernels behind the C ABI declared in ``include/sparsevila.h``).  There is no CPU
+fallback: calling any entry point without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    SVError, SvShape, Shape, library_path, load_library, make_shape, workspace_bytes,
+    sv_score_visual, sv_topk_select, sv_sparse_decode_attn, sv_decode_step,
+    sv_set_tuning, sv_get_tuning, sv_strerror, DecodeBuffers,
+)

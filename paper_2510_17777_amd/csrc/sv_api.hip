@@ -1,0 +1,288 @@
+// C-ABI layer of the sparse decode library: argument validation on the host (a
+// failed call launches nothing), workspace carving, and dispatch to the three
+// kernel stages.  See include/sparsevila.h for the contract of every entry point.
+#include "../../include/sparsevila.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "sv_kernels.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kMinChunk = 64;      // smallest attention chunk; sizes the workspace
+constexpr int kMaxChunk = 1024;
+constexpr int kMaxGridYZ = 65535;
+
+struct Tuning {
+    int32_t score_rows_per_block = 0;   // 0 = default
+    int32_t attn_chunk = 0;
+    int32_t score_stream_loads = -1;    // -1 = default
+};
+Tuning g_tuning;
+
+constexpr int kDefaultScoreRows = 512;
+constexpr int kDefaultAttnChunk = 128;
+constexpr int kDefaultStreamLoads = 1;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int elem_size(int dtype) { return dtype == SV_F16 ? 2 : 4; }
+
+// Which parts of the shape a call depends on.
+enum : unsigned { kNeedQ = 1, kNeedVis = 2, kNeedTxt = 4 };
+
+sv_status check_shape(const sv_shape* s, unsigned need) {
+    if (!s) return SV_ERR_NULL;
+    if (s->dtype != SV_F16 && s->dtype != SV_F32) return SV_ERR_DTYPE;
+    if (s->reserved != 0) return SV_ERR_SHAPE;
+    if (s->batch < 1 || s->batch > kMaxGridYZ) return SV_ERR_SHAPE;
+    if (s->n_kv_heads < 1 || s->n_q_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return SV_ERR_SHAPE;
+    if ((int64_t)s->n_kv_heads * ((s->n_q_heads / s->n_kv_heads + 7) / 8) > kMaxGridYZ) return SV_ERR_SHAPE;
+    if (s->n_q_heads > kMaxGridYZ) return SV_ERR_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128) return SV_ERR_SHAPE;
+    if (s->n_vis_max < 0 || s->n_txt_max < 0 || s->k < 0) return SV_ERR_SHAPE;
+    if (!(s->scale >= 0.f) || std::isinf(s->scale)) return SV_ERR_SHAPE;
+    const int64_t D = s->head_dim;
+    const int es = elem_size(s->dtype);
+    if (need & kNeedQ) {
+        if (s->q_stride_h < D || s->q_stride_b < 0) return SV_ERR_SHAPE;
+        if ((s->q_stride_h * es) % 16 || (s->q_stride_b * es) % 16) return SV_ERR_ALIGN;
+    }
+    if ((need & kNeedVis) && s->n_vis_max > 0) {
+        if (s->kv_vis_stride_n < D || s->kv_vis_stride_h < 0 || s->kv_vis_stride_b < 0) return SV_ERR_SHAPE;
+        if ((s->kv_vis_stride_n * es) % 16 || (s->kv_vis_stride_h * es) % 16 || (s->kv_vis_stride_b * es) % 16)
+            return SV_ERR_ALIGN;
+    }
+    if ((need & kNeedTxt) && s->n_txt_max > 0) {
+        if (s->kv_txt_stride_n < D || s->kv_txt_stride_h < 0 || s->kv_txt_stride_b < 0) return SV_ERR_SHAPE;
+        if ((s->kv_txt_stride_n * es) % 16 || (s->kv_txt_stride_h * es) % 16 || (s->kv_txt_stride_b * es) % 16)
+            return SV_ERR_ALIGN;
+    }
+    return SV_OK;
+}
+
+inline float effective_scale(const sv_shape* s) {
+    return s->scale > 0.f ? s->scale : 1.0f / std::sqrt((float)s->head_dim);
+}
+
+inline int kept_max(const sv_shape* s) { return s->k < s->n_vis_max ? s->k : s->n_vis_max; }
+
+struct Workspace {
+    size_t scores_off, scores_bytes;
+    size_t acc_off, acc_bytes;
+    size_t ml_off, ml_bytes;
+    size_t total;
+};
+
+// Sized for the smallest chunk so that the layout never depends on the tuning knobs.
+Workspace plan_workspace(const sv_shape* s) {
+    Workspace w{};
+    const size_t B = (size_t)s->batch, Hq = (size_t)s->n_q_heads, Hkv = (size_t)s->n_kv_heads;
+    const size_t S = ((size_t)s->n_txt_max + (size_t)kept_max(s) + kMinChunk - 1) / kMinChunk;
+    w.scores_off = 0;
+    w.scores_bytes = align_up(B * Hkv * (size_t)s->n_vis_max * sizeof(float));
+    w.acc_off = w.scores_off + w.scores_bytes;
+    w.acc_bytes = align_up(B * Hq * S * (size_t)s->head_dim * sizeof(float));
+    w.ml_off = w.acc_off + w.acc_bytes;
+    w.ml_bytes = align_up(B * Hq * S * 2 * sizeof(float));
+    w.total = w.ml_off + w.ml_bytes;
+    if (w.total == 0) w.total = kAlign;
+    return w;
+}
+
+sv_status check_workspace(const Workspace& w, const void* ws, size_t bytes) {
+    if (!ws) return SV_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign) return SV_ERR_WORKSPACE;
+    if (bytes < w.total) return SV_ERR_WORKSPACE;
+    return SV_OK;
+}
+
+sv::ScoreArgs make_score_args(const sv_shape* s, const void* q, const void* k_vis, float* scores) {
+    sv::ScoreArgs a{};
+    a.q = q; a.k_vis = k_vis; a.scores = scores; a.vis_len = s->vis_len;
+    a.B = s->batch; a.Hkv = s->n_kv_heads; a.G = s->n_q_heads / s->n_kv_heads;
+    a.D = s->head_dim; a.n_vis_max = s->n_vis_max; a.dtype = s->dtype;
+    a.scale = effective_scale(s);
+    a.q_sb = s->q_stride_b; a.q_sh = s->q_stride_h;
+    a.k_sb = s->kv_vis_stride_b; a.k_sh = s->kv_vis_stride_h; a.k_sn = s->kv_vis_stride_n;
+    a.rows_per_block = g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block : kDefaultScoreRows;
+    a.stream_loads = g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
+    return a;
+}
+
+sv::SelectArgs make_select_args(const sv_shape* s, const float* scores, int32_t* idx, int32_t* count) {
+    sv::SelectArgs a{};
+    a.scores = scores; a.idx = idx; a.count = count; a.vis_len = s->vis_len;
+    a.B = s->batch; a.Hkv = s->n_kv_heads; a.n_vis_max = s->n_vis_max; a.k = s->k;
+    return a;
+}
+
+sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, const void* q,
+                            const void* k_vis, const void* v_vis, const void* k_txt, const void* v_txt,
+                            const int32_t* idx, const int32_t* count, float* out, float* lse) {
+    sv::AttnArgs a{};
+    a.q = q; a.k_vis = k_vis; a.v_vis = v_vis; a.k_txt = k_txt; a.v_txt = v_txt;
+    a.idx = idx; a.count = count; a.txt_len = s->txt_len;
+    a.part_acc = reinterpret_cast<float*>(static_cast<char*>(ws) + w.acc_off);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + w.ml_off);
+    a.out = out; a.lse = lse;
+    a.B = s->batch; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads; a.G = s->n_q_heads / s->n_kv_heads;
+    a.D = s->head_dim; a.n_vis_max = s->n_vis_max; a.n_txt_max = s->n_txt_max;
+    a.k = kept_max(s) > 0 ? s->k : 0;
+    a.dtype = s->dtype; a.scale = effective_scale(s);
+    a.q_sb = s->q_stride_b; a.q_sh = s->q_stride_h;
+    a.vis_sb = s->kv_vis_stride_b; a.vis_sh = s->kv_vis_stride_h; a.vis_sn = s->kv_vis_stride_n;
+    a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
+    a.chunk = g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
+    const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
+    a.n_chunks = (int32_t)((t_max + a.chunk - 1) / a.chunk);
+    return a;
+}
+
+sv_status check_attn_pointers(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                              const void* k_txt, const void* v_txt, const int32_t* idx,
+                              const int32_t* count, const float* out) {
+    if (!q || !out) return SV_ERR_NULL;
+    const bool has_vis = kept_max(s) > 0;
+    if (has_vis && (!k_vis || !v_vis || !idx || !count)) return SV_ERR_NULL;
+    if (s->n_txt_max > 0 && (!k_txt || !v_txt)) return SV_ERR_NULL;
+    if (!aligned16(q)) return SV_ERR_ALIGN;
+    if (has_vis && (!aligned16(k_vis) || !aligned16(v_vis))) return SV_ERR_ALIGN;
+    if (s->n_txt_max > 0 && (!aligned16(k_txt) || !aligned16(v_txt))) return SV_ERR_ALIGN;
+    return SV_OK;
+}
+
+inline sv_status from_hip(hipError_t e) { return e == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+void sv_shape_set_contiguous(sv_shape* s) {
+    if (!s) return;
+    const int64_t D = s->head_dim;
+    s->q_stride_h = D;
+    s->q_stride_b = D * s->n_q_heads;
+    s->kv_vis_stride_n = D;
+    s->kv_vis_stride_h = D * s->n_vis_max;
+    s->kv_vis_stride_b = D * s->n_vis_max * s->n_kv_heads;
+    s->kv_txt_stride_n = D;
+    s->kv_txt_stride_h = D * s->n_txt_max;
+    s->kv_txt_stride_b = D * s->n_txt_max * s->n_kv_heads;
+}
+
+size_t sv_workspace_bytes(const sv_shape* s) {
+    if (check_shape(s, 0) != SV_OK) return 0;
+    return plan_workspace(s).total;
+}
+
+sv_status sv_score_visual(const sv_shape* s, const void* q, const void* k_vis, float* scores, void* stream) {
+    sv_status st = check_shape(s, kNeedQ | kNeedVis);
+    if (st != SV_OK) return st;
+    if (s->n_vis_max == 0) return SV_OK;
+    if (!q || !k_vis || !scores) return SV_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_vis)) return SV_ERR_ALIGN;
+    return from_hip(sv::launch_score(make_score_args(s, q, k_vis, scores), static_cast<hipStream_t>(stream)));
+}
+
+sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, int32_t* count,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;   // the selection keeps all its state on chip
+    sv_status st = check_shape(s, 0);
+    if (st != SV_OK) return st;
+    if (!count) return SV_ERR_NULL;
+    if (s->k > 0 && !idx) return SV_ERR_NULL;
+    if (s->n_vis_max > 0 && !scores) return SV_ERR_NULL;
+    return from_hip(sv::launch_select(make_select_args(s, scores, idx, count), static_cast<hipStream_t>(stream)));
+}
+
+sv_status sv_sparse_decode_attn(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                                const void* k_txt, const void* v_txt, const int32_t* idx,
+                                const int32_t* count, float* out, float* lse, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    if (st != SV_OK) return st;
+    st = check_attn_pointers(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
+    if (st != SV_OK) return st;
+    const Workspace w = plan_workspace(s);
+    st = check_workspace(w, workspace, workspace_bytes);
+    if (st != SV_OK) return st;
+    const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
+    return from_hip(sv::launch_attend(a, static_cast<hipStream_t>(stream)));
+}
+
+sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                         const void* k_txt, const void* v_txt, float* scores, int32_t* idx,
+                         int32_t* count, float* out, float* lse, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    if (st != SV_OK) return st;
+    const bool has_vis = kept_max(s) > 0;
+    if (has_vis && (!idx || !count)) return SV_ERR_NULL;
+    st = check_attn_pointers(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
+    if (st != SV_OK) return st;
+    const Workspace w = plan_workspace(s);
+    st = check_workspace(w, workspace, workspace_bytes);
+    if (st != SV_OK) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (has_vis) {
+        float* sc = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(workspace) + w.scores_off);
+        hipError_t e = sv::launch_score(make_score_args(s, q, k_vis, sc), hs);
+        if (e != hipSuccess) return SV_ERR_LAUNCH;
+        e = sv::launch_select(make_select_args(s, sc, idx, count), hs);
+        if (e != hipSuccess) return SV_ERR_LAUNCH;
+    } else if (count && (idx || s->k == 0)) {
+        // nothing can be kept (k == 0 or no visual rows): the kept sets are empty, count = 0
+        hipError_t e = sv::launch_select(make_select_args(s, scores, idx, count), hs);
+        if (e != hipSuccess) return SV_ERR_LAUNCH;
+    }
+    const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
+    return from_hip(sv::launch_attend(a, hs));
+}
+
+const char* sv_strerror(sv_status status) {
+    switch (status) {
+        case SV_OK: return "ok";
+        case SV_ERR_NULL: return "a required pointer is NULL";
+        case SV_ERR_SHAPE: return "invalid shape, stride or knob value";
+        case SV_ERR_DTYPE: return "unsupported dtype";
+        case SV_ERR_ALIGN: return "pointer or row stride not 16-byte aligned";
+        case SV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SV_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+sv_status sv_set_tuning(const char* name, int32_t value) {
+    if (!name) return SV_ERR_NULL;
+    if (!std::strcmp(name, "score_rows_per_block")) {
+        if (value != 0 && (value < 64 || value > 65536)) return SV_ERR_SHAPE;
+        g_tuning.score_rows_per_block = value;
+        return SV_OK;
+    }
+    if (!std::strcmp(name, "attn_chunk")) {
+        if (value != 0 && (value < kMinChunk || value > kMaxChunk || value % 64)) return SV_ERR_SHAPE;
+        g_tuning.attn_chunk = value;
+        return SV_OK;
+    }
+    if (!std::strcmp(name, "score_stream_loads")) {
+        if (value < -1 || value > 1) return SV_ERR_SHAPE;
+        g_tuning.score_stream_loads = value;
+        return SV_OK;
+    }
+    return SV_ERR_SHAPE;
+}
+
+int32_t sv_get_tuning(const char* name) {
+    if (!name) return -1;
+    if (!std::strcmp(name, "score_rows_per_block"))
+        return g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block : kDefaultScoreRows;
+    if (!std::strcmp(name, "attn_chunk")) return g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
+    if (!std::strcmp(name, "score_stream_loads"))
+        return g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
+    return -1;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Host-side view of the kernels: plain argument structs and one launcher per stage.
+// The launchers assume arguments already validated by the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sv {
+
+struct ScoreArgs {
+    const void* q;
+    const void* k_vis;
+    float* scores;            // [B, Hkv, n_vis_max]
+    const int32_t* vis_len;   // device [B] or nullptr
+    int32_t B, Hkv, G, D, n_vis_max;
+    int32_t dtype;            // 0 = f16, 1 = f32
+    float scale;
+    int64_t q_sb, q_sh;       // element strides
+    int64_t k_sb, k_sh, k_sn;
+    int32_t rows_per_block;   // tuning; rounded up to the kernel's granule by the launcher
+    int32_t stream_loads;     // 1: non-temporal K loads
+};
+
+struct SelectArgs {
+    const float* scores;      // [B, Hkv, n_vis_max]
+    int32_t* idx;             // [B, Hkv, k]
+    int32_t* count;           // [B, Hkv]
+    const int32_t* vis_len;
+    int32_t B, Hkv, n_vis_max, k;
+};
+
+struct AttnArgs {
+    const void* q;
+    const void* k_vis; const void* v_vis;
+    const void* k_txt; const void* v_txt;
+    const int32_t* idx;       // [B, Hkv, k] or nullptr when k == 0
+    const int32_t* count;     // [B, Hkv]    or nullptr when k == 0
+    const int32_t* txt_len;   // device [B] or nullptr
+    float* part_acc;          // [B, Hq, S, D]  un-normalised chunk outputs
+    float* part_ml;           // [B, Hq, S, 2]  chunk max and chunk sum of exp
+    float* out;               // [B, Hq, D]
+    float* lse;               // [B, Hq] or nullptr
+    int32_t B, Hq, Hkv, G, D, n_vis_max, n_txt_max, k;
+    int32_t dtype;
+    float scale;
+    int64_t q_sb, q_sh;
+    int64_t vis_sb, vis_sh, vis_sn;
+    int64_t txt_sb, txt_sh, txt_sn;
+    int32_t chunk;            // tokens per workgroup
+    int32_t n_chunks;         // S = ceil((n_txt_max + k) / chunk)
+};
+
+hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
+hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
+hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials + combine
+
+// Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
+int score_row_granule(int dtype, int D);
+
+}  // namespace sv

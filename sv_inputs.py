@@ -140,10 +140,17 @@ def make_layer(w: Workload, layer: int) -> Dict[str, np.ndarray]:
                 vis_len=vis_len, txt_len=txt_len)
 
 
-def make_inputs(w: Workload, layers: Optional[range] = None) -> Dict[str, np.ndarray]:
-    """All (or a range of) layers folded into the batch dimension, layer-major."""
+def make_inputs(w: Workload, layers: Optional[range] = None, workers: int = 1) -> Dict[str, np.ndarray]:
+    """All (or a range of) layers folded into the batch dimension, layer-major.
+
+    Layers have independent seeds, so drawing them on several threads gives the same bits."""
     layers = range(w.layers) if layers is None else layers
-    parts = [make_layer(w, l) for l in layers]
+    if workers > 1 and len(layers) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            parts = list(ex.map(lambda l: make_layer(w, l), layers))
+    else:
+        parts = [make_layer(w, l) for l in layers]
     if len(parts) == 1:
         return parts[0]
     return {key: np.concatenate([p[key] for p in parts], axis=0) for key in parts[0]}

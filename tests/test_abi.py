@@ -1,0 +1,179 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments on the host before anything could be launched (no GPU needed:
+none of these calls gets as far as a kernel launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_17777_amd as sv
+from paper_2510_17777_amd.binding import SvShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sparsevila.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH = 0, -1, -2, -3, -4, -5, -6
+FAKE = 0x7F0000001000      # never dereferenced by the host code under test (4 KiB aligned)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sv_[a-z_]+)\s*\(", text)))
+
+
+def good_shape(**kw) -> SvShape:
+    s = SvShape()
+    s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim = 2, 28, 4, 128
+    s.n_vis_max, s.n_txt_max, s.k, s.dtype, s.scale, s.reserved = 1000, 64, 100, 0, 0.0, 0
+    for key, val in kw.items():
+        setattr(s, key, val)
+    sv.load_library().sv_shape_set_contiguous(ctypes.byref(s))
+    return s
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("sv_score_visual", "sv_topk_select", "sv_sparse_decode_attn", "sv_decode_step",
+                 "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sv.load_library()
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in sparsevila.h but not exported"
+
+
+def test_struct_layout_matches_the_header():
+    # 10 4-byte fields, 2 pointers, 8 int64 strides
+    assert ctypes.sizeof(SvShape) == 10 * 4 + 2 * 8 + 8 * 8
+    assert SvShape.vis_len.offset == 40 and SvShape.q_stride_b.offset == 56
+
+
+def test_contiguous_strides():
+    s = good_shape()
+    assert (s.q_stride_h, s.q_stride_b) == (128, 128 * 28)
+    assert (s.kv_vis_stride_n, s.kv_vis_stride_h, s.kv_vis_stride_b) == (128, 128000, 512000)
+    assert (s.kv_txt_stride_n, s.kv_txt_stride_h, s.kv_txt_stride_b) == (128, 8192, 32768)
+
+
+def test_workspace_size_is_positive_aligned_and_monotone():
+    lib = sv.load_library()
+    a = lib.sv_workspace_bytes(ctypes.byref(good_shape()))
+    b = lib.sv_workspace_bytes(ctypes.byref(good_shape(n_vis_max=2000)))
+    c = lib.sv_workspace_bytes(ctypes.byref(good_shape(k=900)))
+    assert a > 0 and a % 256 == 0 and b > a and c > a
+    # scores + partial accumulators + partial (max, sum) for 64-token chunks
+    S = (64 + 100 + 63) // 64
+    assert a >= 2 * 4 * 1000 * 4 + 2 * 28 * S * (128 + 2) * 4
+    assert lib.sv_workspace_bytes(ctypes.byref(good_shape(head_dim=96))) == 0
+    assert lib.sv_workspace_bytes(None) == 0
+
+
+@pytest.mark.parametrize("field,value,want", [
+    ("batch", 0, E_SHAPE), ("batch", 70000, E_SHAPE), ("n_kv_heads", 0, E_SHAPE),
+    ("n_q_heads", 30, E_SHAPE), ("head_dim", 96, E_SHAPE), ("n_vis_max", -1, E_SHAPE),
+    ("n_txt_max", -1, E_SHAPE), ("k", -1, E_SHAPE), ("dtype", 2, E_DTYPE),
+    ("scale", -1.0, E_SHAPE), ("scale", float("nan"), E_SHAPE), ("reserved", 1, E_SHAPE),
+])
+def test_bad_shape_fields_are_rejected(field, value, want):
+    lib = sv.load_library()
+    s = good_shape()
+    setattr(s, field, value)
+    assert lib.sv_score_visual(ctypes.byref(s), FAKE, FAKE, FAKE, None) == want
+    assert lib.sv_decode_step(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                              None, FAKE, 1 << 40, None) == want
+
+
+def test_strides_are_checked():
+    lib = sv.load_library()
+    s = good_shape()
+    s.kv_vis_stride_n = 64                 # rows would overlap
+    assert lib.sv_score_visual(ctypes.byref(s), FAKE, FAKE, FAKE, None) == E_SHAPE
+    s = good_shape()
+    s.kv_vis_stride_n = 132                # 264-byte rows: not a multiple of 16
+    assert lib.sv_score_visual(ctypes.byref(s), FAKE, FAKE, FAKE, None) == E_ALIGN
+    s = good_shape()
+    s.q_stride_h = 129
+    assert lib.sv_score_visual(ctypes.byref(s), FAKE, FAKE, FAKE, None) == E_ALIGN
+    s = good_shape()
+    s.kv_txt_stride_h = 4
+    assert lib.sv_sparse_decode_attn(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                     None, FAKE, 1 << 40, None) == E_ALIGN
+
+
+def test_null_and_misaligned_pointers_are_rejected():
+    lib = sv.load_library()
+    s = good_shape()
+    sp = ctypes.byref(s)
+    assert lib.sv_score_visual(None, FAKE, FAKE, FAKE, None) == E_NULL
+    assert lib.sv_score_visual(sp, None, FAKE, FAKE, None) == E_NULL
+    assert lib.sv_score_visual(sp, FAKE, None, FAKE, None) == E_NULL
+    assert lib.sv_score_visual(sp, FAKE, FAKE, None, None) == E_NULL
+    assert lib.sv_score_visual(sp, FAKE + 8, FAKE, FAKE, None) == E_ALIGN
+    assert lib.sv_score_visual(sp, FAKE, FAKE + 2, FAKE, None) == E_ALIGN
+    assert lib.sv_topk_select(sp, FAKE, None, FAKE, None, 0, None) == E_NULL
+    assert lib.sv_topk_select(sp, FAKE, FAKE, None, None, 0, None) == E_NULL
+    assert lib.sv_topk_select(sp, None, FAKE, FAKE, None, 0, None) == E_NULL
+    args = [FAKE] * 9
+    for missing in (0, 1, 2, 3, 4, 5, 6, 7):          # q, k_vis, v_vis, k_txt, v_txt, idx, count, out
+        a = list(args)
+        a[missing] = None
+        a[8] = None                                    # lse is optional
+        assert lib.sv_sparse_decode_attn(sp, *a, FAKE, 1 << 40, None) == E_NULL, missing
+    a = [FAKE] * 8 + [None]
+    a[2] = FAKE + 4
+    assert lib.sv_sparse_decode_attn(sp, *a, FAKE, 1 << 40, None) == E_ALIGN
+
+
+def test_workspace_is_checked():
+    lib = sv.load_library()
+    s = good_shape()
+    sp = ctypes.byref(s)
+    need = lib.sv_workspace_bytes(sp)
+    a = [FAKE] * 8 + [None]
+    assert lib.sv_sparse_decode_attn(sp, *a, None, need, None) == E_WS
+    assert lib.sv_sparse_decode_attn(sp, *a, FAKE, need - 1, None) == E_WS
+    assert lib.sv_sparse_decode_attn(sp, *a, FAKE + 128, need, None) == E_WS
+    d = [FAKE] * 10
+    assert lib.sv_decode_step(sp, *d, FAKE, need - 1, None) == E_WS
+
+
+def test_text_only_shape_needs_no_visual_pointers():
+    lib = sv.load_library()
+    s = good_shape(k=0)
+    sp = ctypes.byref(s)
+    # k == 0: k_vis/v_vis/idx/count may be NULL; the call gets past validation, and what
+    # happens next depends on the presence of a GPU, so only the workspace error is probed.
+    assert lib.sv_sparse_decode_attn(sp, FAKE, None, None, FAKE, FAKE, None, None, FAKE, None,
+                                     None, 0, None) == E_WS
+
+
+def test_strerror_and_tuning_knobs():
+    assert sv.sv_strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert sv.sv_strerror(code) not in ("ok", "unknown status")
+    assert sv.sv_strerror(-99) == "unknown status"
+    lib = sv.load_library()
+    assert sv.sv_get_tuning("attn_chunk") >= 64
+    assert lib.sv_set_tuning(b"attn_chunk", 100) == E_SHAPE        # not a multiple of 64
+    assert lib.sv_set_tuning(b"attn_chunk", 4096) == E_SHAPE
+    assert lib.sv_set_tuning(b"score_rows_per_block", 8) == E_SHAPE
+    assert lib.sv_set_tuning(b"no_such_knob", 1) == E_SHAPE
+    assert lib.sv_set_tuning(None, 1) == E_NULL
+    before = sv.sv_get_tuning("attn_chunk")
+    sv.sv_set_tuning("attn_chunk", 256)
+    assert sv.sv_get_tuning("attn_chunk") == 256
+    sv.sv_set_tuning("attn_chunk", 0)
+    assert sv.sv_get_tuning("attn_chunk") == before
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    q = torch.zeros((1, 4, 64), dtype=torch.float16)
+    k = torch.zeros((1, 1, 8, 64), dtype=torch.float16)
+    shape = sv.make_shape(q, k, None, 2)
+    with pytest.raises(ValueError):
+        sv.sv_score_visual(shape, q, k, torch.zeros((1, 1, 8)))
