@@ -22,7 +22,7 @@ struct Tuning {
 };
 Tuning g_tuning;
 
-constexpr int kDefaultScoreRows = 512;
+constexpr int kDefaultScoreRows = 256;
 constexpr int kDefaultAttnChunk = 128;
 constexpr int kDefaultStreamLoads = 1;
 
@@ -73,6 +73,7 @@ struct Workspace {
     size_t scores_off, scores_bytes;
     size_t acc_off, acc_bytes;
     size_t ml_off, ml_bytes;
+    size_t sel_off, sel_bytes;
     size_t total;
 };
 
@@ -87,7 +88,9 @@ Workspace plan_workspace(const sv_shape* s) {
     w.acc_bytes = align_up(B * Hq * S * (size_t)s->head_dim * sizeof(float));
     w.ml_off = w.acc_off + w.acc_bytes;
     w.ml_bytes = align_up(B * Hq * S * 2 * sizeof(float));
-    w.total = w.ml_off + w.ml_bytes;
+    w.sel_off = w.ml_off + w.ml_bytes;
+    w.sel_bytes = align_up(sv::select_workspace_bytes(s->batch, s->n_kv_heads, s->n_vis_max));
+    w.total = w.sel_off + w.sel_bytes;
     if (w.total == 0) w.total = kAlign;
     return w;
 }
@@ -112,9 +115,11 @@ sv::ScoreArgs make_score_args(const sv_shape* s, const void* q, const void* k_vi
     return a;
 }
 
-sv::SelectArgs make_select_args(const sv_shape* s, const float* scores, int32_t* idx, int32_t* count) {
+sv::SelectArgs make_select_args(const sv_shape* s, const Workspace& w, void* ws, const float* scores,
+                                int32_t* idx, int32_t* count) {
     sv::SelectArgs a{};
     a.scores = scores; a.idx = idx; a.count = count; a.vis_len = s->vis_len;
+    a.ws = ws ? static_cast<char*>(ws) + w.sel_off : nullptr;
     a.B = s->batch; a.Hkv = s->n_kv_heads; a.n_vis_max = s->n_vis_max; a.k = s->k;
     return a;
 }
@@ -189,13 +194,18 @@ sv_status sv_score_visual(const sv_shape* s, const void* q, const void* k_vis, f
 
 sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, int32_t* count,
                          void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;   // the selection keeps all its state on chip
     sv_status st = check_shape(s, 0);
     if (st != SV_OK) return st;
     if (!count) return SV_ERR_NULL;
     if (s->k > 0 && !idx) return SV_ERR_NULL;
     if (s->n_vis_max > 0 && !scores) return SV_ERR_NULL;
-    return from_hip(sv::launch_select(make_select_args(s, scores, idx, count), static_cast<hipStream_t>(stream)));
+    const Workspace w = plan_workspace(s);
+    if (w.sel_bytes > 0) {   // short rows are selected entirely on chip and need no workspace
+        st = check_workspace(w, workspace, workspace_bytes);
+        if (st != SV_OK) return st;
+    }
+    return from_hip(sv::launch_select(make_select_args(s, w, workspace, scores, idx, count),
+                                      static_cast<hipStream_t>(stream)));
 }
 
 sv_status sv_sparse_decode_attn(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
@@ -231,11 +241,11 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
         float* sc = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(workspace) + w.scores_off);
         hipError_t e = sv::launch_score(make_score_args(s, q, k_vis, sc), hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
-        e = sv::launch_select(make_select_args(s, sc, idx, count), hs);
+        e = sv::launch_select(make_select_args(s, w, workspace, sc, idx, count), hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     } else if (count && (idx || s->k == 0)) {
         // nothing can be kept (k == 0 or no visual rows): the kept sets are empty, count = 0
-        hipError_t e = sv::launch_select(make_select_args(s, scores, idx, count), hs);
+        hipError_t e = sv::launch_select(make_select_args(s, w, workspace, scores, idx, count), hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     }
     const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);

@@ -25,6 +25,7 @@ struct SelectArgs {
     int32_t* idx;             // [B, Hkv, k]
     int32_t* count;           // [B, Hkv]
     const int32_t* vis_len;
+    void* ws;                 // select_workspace_bytes() bytes, 256-byte aligned (unused when that is 0)
     int32_t B, Hkv, n_vis_max, k;
 };
 
@@ -52,6 +53,9 @@ struct AttnArgs {
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials + combine
+
+// Scratch the selection needs for rows too long for one workgroup (0 for short rows).
+size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 
 // Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
 int score_row_granule(int dtype, int D);

@@ -1,165 +1,179 @@
 // Step 2 of the decode path: keep the k highest-scoring visual tokens of every
 // (batch, kv head) (paper section 3.2: the highest-relevance tokens are retained).
 //
-// Exact integer selection on the order-preserving uint32 image of the fp32 score:
-//   * MSD radix select (11 + 11 + 10 bits) finds the key T of the k-th largest
-//     score and how many keys equal to T belong to the set;
-//   * an ordered compaction emits {j : key_j > T} plus the first r keys equal to T
-//     in ascending index order, so ties go to the lower index and the output
-//     ascends -- the set is unique for the given scores.
-// One 1024-lane workgroup owns one (b, g).  Each wavefront owns a contiguous index
-// range; when the range fits (n <= 1024 * ITEMS) every lane keeps its keys in
-// registers, so the scores are read from memory once; longer rows re-read them
-// in every pass.  Histograms live in LDS; all counting is integer, hence the
-// result does not depend on the order in which lanes arrive.
+// Exact selection: the kept set is {j : (s_j, -j) is among the k largest pairs}, i.e.
+// ties go to the lower index, and it is emitted in ascending index order.
+//
+// Method (the same in both launch shapes below):
+//   1. a range [lo, hi] of the scores; 2. a histogram over equal-width VALUE bins of
+//   that range.  The bin map s -> trunc((s - lo) * inv), clamped, is monotone in s, so
+//   every score in a higher bin is strictly larger and bins above the threshold bin are
+//   kept whole.  Value bins spread a bell-shaped score distribution thinly (the top bits
+//   of the float pattern do not), which keeps LDS atomic conflicts rare;
+//   3. a scan of the histogram from the top finds the threshold bin and how many of
+//   its members are still needed; its members (at most 1024) are ranked exactly by
+//   (order-preserving uint32 key, index), which yields the threshold pair;
+//   4. ordered compaction: per-wavefront counts, prefix sums, ballot ranks.
+// If the range is degenerate (all scores equal) or the threshold bin is overfull, an MSD
+// radix select (11 + 11 + 10 bits) on the uint32 keys takes over.  All counting is
+// integer: the result does not depend on the order in which lanes or workgroups run.
+//
+// Launch shapes:
+//   * rows of at most 4096 scores: one 1024-lane workgroup per (b, g), scores in
+//     registers, exact min/max as the range;
+//   * longer rows: a single compute unit cannot pull a long row from memory fast
+//     enough, so the row is cut into parts of 4096 scores (at most 16 parts) and three
+//     kernels run over (part, g, b):  A. per-part histogram, the range taken from a
+//     256-score strided sample that every part reads identically;  B. every part sums
+//     the part histograms, finds the threshold bin, counts its own scores above it and
+//     appends its threshold-bin members to the row's candidate list;  C. every part
+//     ranks the candidates, derives its output offset, and emits its kept indices.
+//     No workgroup waits for another: the kernel boundaries are the only barriers.
 #include "sv_device.h"
 #include "sv_kernels.h"
+
+#include <cfloat>
 
 namespace sv {
 namespace {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / kWave;   // 16
-constexpr int kBins = 2048;
+constexpr int kBins = 2048;        // single-workgroup shape, and radix digits
+constexpr int kPartBins = 512;     // multi-part shape
+constexpr int kMaxCand = 1024;
+constexpr int kPartLen = 4096;
+constexpr int kMaxParts = 16;
+constexpr int kPartThreads = 256;
+constexpr int kSingleThreads = 1024;
+constexpr int kSingleMaxN = 4096;
 
-struct SelShared {
-    uint32_t hist[kBins];
-    uint32_t wave_tot[kSelWaves];
-    uint32_t wave_tot2[kSelWaves];
-    uint32_t bin, above, in_bin;
+enum : uint32_t { kFlagOk = 0, kFlagDegenerate = 1, kFlagOverfull = 2 };
+
+struct RowParams {   // one per (b, g), written by kernel A / B, read by B / C
+    float lo, inv;
+    uint32_t flag, tbin, need, in_bin, pad0, pad1;
 };
 
+__device__ __forceinline__ float wave_min_f(float x) { return -wave_max(-x); }
+__device__ __forceinline__ float clamp_finite(float s) { return fminf(fmaxf(s, -FLT_MAX), FLT_MAX); }
+
+template <int NBINS>
+__device__ __forceinline__ int value_bin(float s, float lo, float inv) {
+    float t = (clamp_finite(s) - lo) * inv;
+    t = fminf(fmaxf(t, 0.f), (float)(NBINS - 1));
+    return (int)t;
+}
+
+__device__ __forceinline__ int live_rows(const int32_t* vis_len, int b, int n_max) {
+    if (!vis_len) return n_max;
+    const int v = vis_len[b];
+    return v < 0 ? 0 : (v < n_max ? v : n_max);
+}
+
 // Block-wide inclusive scan of one value per thread (thread order = index order).
-__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t x, uint32_t* wave_tot,
-                                                         int lane, int wave) {
+template <int NT>
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t x, uint32_t* wave_tot, int lane, int wave) {
+    constexpr int NW = NT / kWave;
     const uint32_t incl = wave_inclusive_scan(x, lane);
     if (lane == kWave - 1) wave_tot[wave] = incl;
     __syncthreads();
     uint32_t base = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) base += (w < wave) ? wave_tot[w] : 0u;
+    for (int w = 0; w < NW; ++w) base += (w < wave) ? wave_tot[w] : 0u;
     __syncthreads();
     return incl + base;
 }
 
-// ITEMS > 0: keys register-resident (n <= 1024*ITEMS).  ITEMS == 0: re-read per pass.
-template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a) {
-    __shared__ SelShared sh;
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    const int64_t unit = (int64_t)b * a.Hkv + g;
-    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
-    int32_t* __restrict__ out = a.idx + unit * a.k;
+struct ThresholdBin { uint32_t bin, above, in_bin; };
 
-    int n = a.n_vis_max;
-    if (a.vis_len) {
-        const int v = a.vis_len[b];
-        n = v < 0 ? 0 : (v < n ? v : n);
-    }
-    const int kb = a.k < n ? a.k : n;
-    if (tid == 0) a.count[unit] = kb;
-    for (int i = kb + tid; i < a.k; i += kSelThreads) out[i] = -1;
-    if (kb == 0) return;
-    if (kb == n) {   // everything is kept
-        for (int i = tid; i < n; i += kSelThreads) out[i] = i;
-        return;
-    }
-
-    // Index range of this wavefront: [wave*seg, wave*seg + seg) clipped to n.
-    const int seg = ((n + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int seg_items = seg / kWave;
-    const int j0 = wave * seg + lane;
-
-    constexpr int R = ITEMS > 0 ? ITEMS : 1;
-    uint32_t keys[R];
-    if (ITEMS > 0) {
+// Scans hist[0..NBINS) from the top for the bin that holds the need-th largest entry.
+// Thread t owns the NBINS/NT bins just below NBINS - t*NBINS/NT.  `res` is LDS.
+template <int NT, int NBINS>
+__device__ __forceinline__ ThresholdBin find_threshold_bin(const uint32_t* hist, uint32_t need, uint32_t* wave_tot,
+                                                           ThresholdBin* res, int tid, int lane, int wave) {
+    constexpr int BPT = NBINS / NT;
+    static_assert(BPT >= 1 && BPT * NT == NBINS, "bins must divide over threads");
+    uint32_t c[BPT];
+    uint32_t sum = 0;
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int j = j0 + i * kWave;
-            keys[i] = (i < seg_items && j < n) ? score_key(s[j]) : 0u;   // 0 = "no key"
+    for (int i = 0; i < BPT; ++i) { c[i] = hist[NBINS - 1 - (tid * BPT + i)]; sum += c[i]; }
+    if (tid == 0) { res->bin = 0; res->above = 0; res->in_bin = 0; }
+    const uint32_t incl = block_inclusive_scan<NT>(sum, wave_tot, lane, wave);
+    uint32_t run = incl - sum;
+    if (run < need && need <= incl) {   // exactly one thread
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            if (run < need && need <= run + c[i]) {
+                res->bin = NBINS - 1 - (tid * BPT + i);
+                res->above = run;
+                res->in_bin = c[i];
+            }
+            run += c[i];
         }
     }
-    // key of item i (valid keys are never 0: the smallest is the image of -inf)
-    auto key_at = [&](int i) -> uint32_t {
-        if (ITEMS > 0) return keys[i];
-        const int j = j0 + i * kWave;
-        return j < n ? score_key(s[j]) : 0u;
-    };
-    const int n_items = ITEMS > 0 ? R : seg_items;
+    __syncthreads();
+    const ThresholdBin r = *res;
+    __syncthreads();
+    return r;
+}
 
+struct RadixShared {
+    uint32_t hist[kBins];
+    uint32_t wave_tot[16], wave_tot2[16];
+    ThresholdBin tb;
+};
+
+// MSD radix select over one whole row by one workgroup of NT lanes, re-reading the
+// scores in every pass; wavefront w owns the contiguous range [w*seg, (w+1)*seg).
+template <int NT>
+__device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* __restrict__ s,
+                                                 int32_t* __restrict__ out, int n, int kb, int tid, int lane, int wave) {
+    constexpr int NW = NT / kWave;
+    const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
+    const int seg_items = seg / kWave;
+    const int j0 = wave * seg + lane;
+    const int seg_end = min(n, wave * seg + seg);
+    auto key_at = [&](int i) -> uint32_t {   // 0 = "no key" (valid keys are never 0)
+        const int j = j0 + i * kWave;
+        return j < seg_end ? score_key(s[j]) : 0u;
+    };
     uint32_t prefix = 0, mask = 0;
-    uint32_t need = (uint32_t)kb;   // how many keys with (key & mask) == prefix are kept
+    uint32_t need = (uint32_t)kb;
     for (int pass = 0; pass < 3; ++pass) {
         const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
         const uint32_t digit_mask = pass == 2 ? 0x3FFu : 0x7FFu;
-        sh.hist[tid] = 0;
-        sh.hist[tid + kSelThreads] = 0;
-        if (tid == 0) { sh.bin = 0; sh.above = 0; sh.in_bin = 0; }
+        for (int i = tid; i < kBins; i += NT) sh.hist[i] = 0;
         __syncthreads();
-        if (ITEMS > 0) {
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const uint32_t key = key_at(i);
-                if (key != 0u && (key & mask) == prefix)
-                    atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
-            }
-        } else {
-            for (int i = 0; i < n_items; ++i) {
-                const uint32_t key = key_at(i);
-                if (key != 0u && (key & mask) == prefix)
-                    atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
-            }
+        for (int i = 0; i < seg_items; ++i) {
+            const uint32_t key = key_at(i);
+            if (key != 0u && (key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
         }
         __syncthreads();
-        // Scan the bins from the top: thread t owns bins 2047-2t and 2046-2t.
-        const uint32_t c0 = sh.hist[kBins - 1 - 2 * tid];
-        const uint32_t c1 = sh.hist[kBins - 2 - 2 * tid];
-        const uint32_t incl = block_inclusive_scan(c0 + c1, sh.wave_tot, lane, wave);
-        const uint32_t excl = incl - (c0 + c1);
-        if (excl < need && need <= incl) {   // exactly one thread
-            if (need <= excl + c0) { sh.bin = kBins - 1 - 2 * tid; sh.above = excl; sh.in_bin = c0; }
-            else { sh.bin = kBins - 2 - 2 * tid; sh.above = excl + c0; sh.in_bin = c1; }
-        }
-        __syncthreads();
-        prefix |= sh.bin << shift;
+        const ThresholdBin tb = find_threshold_bin<NT, kBins>(sh.hist, need, sh.wave_tot, &sh.tb, tid, lane, wave);
+        prefix |= tb.bin << shift;
         mask |= digit_mask << shift;
-        need -= sh.above;
-        const uint32_t in_bin = sh.in_bin;
-        __syncthreads();
-        if (need == in_bin) break;   // the whole bin is kept: no finer digit needed
+        need -= tb.above;
+        if (need == tb.in_bin) break;   // the whole bin is kept: no finer digit needed
     }
-
-    // ---- ordered compaction ----
-    // kept(j) = (key&mask) > prefix, or (key&mask) == prefix and fewer than `need`
-    // equal keys precede j.  Per-wave counts of "greater" and "equal" keys first.
+    // kept(j) = (key&mask) > prefix, or (key&mask) == prefix and fewer than `need` equal keys precede j
     uint32_t n_gt = 0, n_eq = 0;
-    auto count_item = [&](int i) {
+    for (int i = 0; i < seg_items; ++i) {
         const uint32_t key = key_at(i);
         const uint32_t kp = key & mask;
         n_gt += __popcll(__ballot(key != 0u && kp > prefix));
         n_eq += __popcll(__ballot(key != 0u && kp == prefix));
-    };
-    if (ITEMS > 0) {
-#pragma unroll
-        for (int i = 0; i < R; ++i) count_item(i);
-    } else {
-        for (int i = 0; i < n_items; ++i) count_item(i);
     }
     if (lane == 0) { sh.wave_tot[wave] = n_gt; sh.wave_tot2[wave] = n_eq; }
     __syncthreads();
     uint32_t eq_before = 0, gt_before = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
+    for (int w = 0; w < NW; ++w) {
         eq_before += (w < wave) ? sh.wave_tot2[w] : 0u;
         gt_before += (w < wave) ? sh.wave_tot[w] : 0u;
     }
-    // kept keys before this wave = greater ones + min(equal ones, need)
     uint32_t pos = gt_before + (eq_before < need ? eq_before : need);
     uint32_t eq_seen = eq_before;
     const uint64_t lane_lt = (1ull << lane) - 1ull;
-    auto emit_item = [&](int i) {
+    for (int i = 0; i < seg_items; ++i) {
         const uint32_t key = key_at(i);
         const uint32_t kp = key & mask;
         const bool is_eq = key != 0u && kp == prefix;
@@ -168,35 +182,479 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectArgs a)
         const bool keep = (key != 0u && kp > prefix) || (is_eq && eq_rank < need);
         const uint64_t keep_ballot = __ballot(keep);
         const uint32_t slot = pos + (uint32_t)__popcll(keep_ballot & lane_lt);
-        if (keep && slot < (uint32_t)kb) out[slot] = j0 + i * kWave;   // slot < kb always holds for finite scores
+        if (keep && slot < (uint32_t)kb) out[slot] = j0 + i * kWave;   // slot < kb holds for finite scores
         pos += (uint32_t)__popcll(keep_ballot);
         eq_seen += (uint32_t)__popcll(eq_ballot);
+    }
+}
+
+// Exact ranking of the threshold bin's members held in LDS: finds the member with rank
+// need-1 in (score descending, index ascending) order.  Threads stride over members.
+template <int NT>
+__device__ __forceinline__ void rank_candidates(const uint32_t* cand_key, const int32_t* cand_idx, uint32_t n_cand,
+                                                uint32_t need, uint32_t* thr_key, int32_t* thr_idx, int tid) {
+    for (uint32_t c = tid; c < n_cand; c += NT) {
+        const uint32_t my_key = cand_key[c];
+        const int32_t my_idx = cand_idx[c];
+        uint32_t rank = 0;
+        for (uint32_t u = 0; u < n_cand; ++u) {
+            const uint32_t ok = cand_key[u];
+            rank += (ok > my_key || (ok == my_key && cand_idx[u] < my_idx)) ? 1u : 0u;
+        }
+        if (rank == need - 1) { *thr_key = my_key; *thr_idx = my_idx; }
+    }
+}
+
+// Writes count and the -1 padding of one (b, g); returns true when nothing else is left
+// to do (k_b == 0, or k_b == n where the kept set is every index).
+template <int NT>
+__device__ __forceinline__ bool emit_trivial(const SelectArgs& a, int64_t unit, int n, int kb, int first,
+                                             int stride_blocks, int tid) {
+    int32_t* out = a.idx + unit * a.k;
+    if (first == 0 && tid == 0) a.count[unit] = kb;
+    for (int i = kb + first * NT + tid; i < a.k; i += stride_blocks * NT) out[i] = -1;
+    if (kb == 0) return true;
+    if (kb == n) {
+        for (int i = first * NT + tid; i < n; i += stride_blocks * NT) out[i] = i;
+        return true;
+    }
+    return false;
+}
+
+// ------------------------------------------------------------------ single workgroup
+struct SingleShared {
+    RadixShared rx;
+    uint32_t cand_key[kMaxCand];
+    int32_t cand_idx[kMaxCand];
+    float wave_min[16], wave_max[16];
+    uint32_t n_cand, thr_key;
+    int32_t thr_idx;
+};
+
+template <int ITEMS>
+__global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const SelectArgs a) {
+    constexpr int NT = kSingleThreads, NW = NT / kWave;
+    __shared__ SingleShared sh;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
+    int32_t* __restrict__ out = a.idx + unit * a.k;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
+
+    const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
+    const int j0 = wave * seg + lane;
+    const int range_end = min(n, wave * seg + seg);
+    const int my_items = j0 < range_end ? (range_end - j0 + kWave - 1) / kWave : 0;
+    float vals[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? s[j0 + i * kWave] : 0.f;
+
+    float lo = FLT_MAX, hi = -FLT_MAX;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i)
+        if (i < my_items) { const float v = clamp_finite(vals[i]); lo = fminf(lo, v); hi = fmaxf(hi, v); }
+    lo = wave_min_f(lo);
+    hi = wave_max(hi);
+    if (lane == 0) { sh.wave_min[wave] = lo; sh.wave_max[wave] = hi; }
+    for (int i = tid; i < kBins; i += NT) sh.rx.hist[i] = 0;
+    if (tid == 0) { sh.n_cand = 0; sh.thr_key = 0; sh.thr_idx = -1; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { lo = fminf(lo, sh.wave_min[w]); hi = fmaxf(hi, sh.wave_max[w]); }
+    const float inv = (float)kBins / (hi - lo);
+    const bool spread = hi > lo && inv > 0.f && inv <= FLT_MAX;   // block-uniform
+
+    bool done = false;
+    if (spread) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+            if (i < my_items) atomicAdd(&sh.rx.hist[value_bin<kBins>(vals[i], lo, inv)], 1u);
+        __syncthreads();
+        const ThresholdBin tb =
+            find_threshold_bin<NT, kBins>(sh.rx.hist, (uint32_t)kb, sh.rx.wave_tot, &sh.rx.tb, tid, lane, wave);
+        const int tbin = (int)tb.bin;
+        const uint32_t need = (uint32_t)kb - tb.above;
+        if (tb.in_bin <= (uint32_t)kMaxCand) {
+            uint32_t thr_key = 0;
+            int32_t thr_idx = 0x7fffffff;   // whole bin kept unless the ranking says otherwise
+            if (need < tb.in_bin) {
+#pragma unroll
+                for (int i = 0; i < ITEMS; ++i)
+                    if (i < my_items && value_bin<kBins>(vals[i], lo, inv) == tbin) {
+                        const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
+                        if (slot < (uint32_t)kMaxCand) {
+                            sh.cand_key[slot] = score_key(vals[i]);
+                            sh.cand_idx[slot] = j0 + i * kWave;
+                        }
+                    }
+                __syncthreads();
+                rank_candidates<NT>(sh.cand_key, sh.cand_idx, tb.in_bin, need, &sh.thr_key, &sh.thr_idx, tid);
+                __syncthreads();
+                thr_key = sh.thr_key;
+                thr_idx = sh.thr_idx;
+            }
+            uint32_t keep_bits = 0, n_keep = 0;
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                bool keep = false;
+                if (i < my_items) {
+                    const int bin = value_bin<kBins>(vals[i], lo, inv);
+                    const uint32_t key = score_key(vals[i]);
+                    keep = bin != tbin ? bin > tbin : (key > thr_key || (key == thr_key && (j0 + i * kWave) <= thr_idx));
+                }
+                keep_bits |= keep ? (1u << i) : 0u;
+                n_keep += (uint32_t)__popcll(__ballot(keep));
+            }
+            if (lane == 0) sh.rx.wave_tot2[wave] = n_keep;
+            __syncthreads();
+            uint32_t pos = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) pos += (w < wave) ? sh.rx.wave_tot2[w] : 0u;
+            const uint64_t lane_lt = (1ull << lane) - 1ull;
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                const bool keep = (keep_bits >> i) & 1u;
+                const uint64_t ballot = __ballot(keep);
+                const uint32_t slot = pos + (uint32_t)__popcll(ballot & lane_lt);
+                if (keep && slot < (uint32_t)kb) out[slot] = j0 + i * kWave;
+                pos += (uint32_t)__popcll(ballot);
+            }
+            done = true;
+        }
+    }
+    if (!done) {   // block-uniform
+        __syncthreads();
+        radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave);
+    }
+}
+
+// ------------------------------------------------------------------ multi-part shape
+struct PartView {   // how one 256-lane workgroup sees its part of the row
+    int part_len;   // scores per part (multiple of 256)
+    int items;      // scores per lane: part_len / 256
+    int j0;         // index of this lane's item 0
+    int my_items;   // live items of this lane
+};
+
+__device__ __forceinline__ PartView part_view(int part, int part_len, int n, int lane, int wave) {
+    PartView v;
+    v.part_len = part_len;
+    v.items = part_len / kPartThreads;
+    const int wave_len = part_len / (kPartThreads / kWave);   // contiguous range of one wavefront
+    v.j0 = part * part_len + wave * wave_len + lane;
+    const int end = min(n, part * part_len + (wave + 1) * wave_len);
+    v.my_items = v.j0 < end ? (end - v.j0 + kWave - 1) / kWave : 0;
+    return v;
+}
+
+// Runs the statement(s) on this lane's live items with `i` the item number and `v` its
+// score: from registers when ITEMS > 0, else from memory.
+#define SV_PART_ITEMS(...)                                                                          \
+    if (ITEMS > 0) {                                                                                \
+        _Pragma("unroll") for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) {                       \
+            if (i < pv.my_items) { const float v = vals[i]; __VA_ARGS__ }                           \
+        }                                                                                           \
+    } else {                                                                                        \
+        for (int i = 0; i < pv.my_items; ++i) { const float v = s[pv.j0 + i * kWave]; __VA_ARGS__ } \
+    }
+
+#define SV_PART_LOAD()                                                      \
+    float vals[ITEMS > 0 ? ITEMS : 1];                                      \
+    if (ITEMS > 0) {                                                        \
+        _Pragma("unroll") for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) \
+            vals[i] = i < pv.my_items ? s[pv.j0 + i * kWave] : 0.f;         \
+    }                                                                       \
+    (void)vals;
+
+struct SelectWorkspace {
+    uint32_t* part_hist;    // [units][parts][kPartBins]
+    uint32_t* part_above;   // [units][parts]
+    uint32_t* cand_count;   // [units]
+    uint32_t* cand_key;     // [units][kMaxCand]
+    int32_t* cand_idx;      // [units][kMaxCand]
+    RowParams* params;      // [units]
+};
+
+// A. per-part value histogram; the bin range comes from a strided 256-score sample.
+template <int ITEMS>
+__global__ __launch_bounds__(kPartThreads) void select_hist_kernel(const SelectArgs a, const SelectWorkspace ws,
+                                                                  const int parts, const int part_len) {
+    __shared__ uint32_t hist[kPartBins];
+    __shared__ float wmin[4], wmax[4];
+    const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (kb == 0 || kb == n) return;   // kernel C handles these without the histogram
+
+    // Range estimate: every part of the row reads the same sample, hence the same range.
+    const float sv = clamp_finite(s[(int)(((int64_t)tid * n) / kPartThreads)]);
+    float lo = wave_min_f(sv), hi = wave_max(sv);
+    if (lane == 0) { wmin[wave] = lo; wmax[wave] = hi; }
+    hist[tid] = 0;
+    hist[tid + kPartThreads] = 0;
+    __syncthreads();
+    lo = fminf(fminf(wmin[0], wmin[1]), fminf(wmin[2], wmin[3]));
+    hi = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    // widen by the sample range on both sides: scores outside the sample's span still
+    // land in distinct bins; anything beyond clamps into the end bins
+    const float r = hi - lo;
+    const float lo_w = lo - r;
+    const float inv = (float)kPartBins / (3.f * r);
+    const bool ok = r > 0.f && r <= FLT_MAX / 4.f && inv > 0.f && inv <= FLT_MAX;
+    if (part == 0 && tid == 0) {
+        RowParams p{};
+        p.lo = lo_w; p.inv = inv; p.flag = ok ? kFlagOk : kFlagDegenerate;
+        ws.params[unit] = p;
+        ws.cand_count[unit] = 0;
+    }
+    if (!ok) return;   // block-uniform, and the same in every part of the row
+
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
+    SV_PART_ITEMS(atomicAdd(&hist[value_bin<kPartBins>(v, lo_w, inv)], 1u);)
+    __syncthreads();
+    uint32_t* dst = ws.part_hist + (unit * parts + part) * kPartBins;
+    dst[tid] = hist[tid];
+    dst[tid + kPartThreads] = hist[tid + kPartThreads];
+}
+
+// B. threshold bin of the row; this part's count above it; its threshold-bin members.
+template <int ITEMS>
+__global__ __launch_bounds__(kPartThreads) void select_threshold_kernel(const SelectArgs a, const SelectWorkspace ws,
+                                                                       const int parts, const int part_len) {
+    __shared__ uint32_t hist[kPartBins];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ ThresholdBin tb_sh;
+    const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (kb == 0 || kb == n) return;
+    const RowParams rp = ws.params[unit];
+    if (rp.flag != kFlagOk) return;
+
+    const int live_parts = (n + part_len - 1) / part_len;
+    const uint32_t* src = ws.part_hist + unit * parts * kPartBins;
+    uint32_t h0 = 0, h1 = 0;
+    for (int p = 0; p < live_parts; ++p) {
+        h0 += src[p * kPartBins + tid];
+        h1 += src[p * kPartBins + tid + kPartThreads];
+    }
+    hist[tid] = h0;
+    hist[tid + kPartThreads] = h1;
+    __syncthreads();
+    const ThresholdBin tb =
+        find_threshold_bin<kPartThreads, kPartBins>(hist, (uint32_t)kb, wave_tot, &tb_sh, tid, lane, wave);
+    const bool overfull = tb.in_bin > (uint32_t)kMaxCand;
+    if (part == 0 && tid == 0) {
+        RowParams* p = ws.params + unit;
+        p->tbin = tb.bin; p->need = (uint32_t)kb - tb.above; p->in_bin = tb.in_bin;
+        if (overfull) p->flag = kFlagOverfull;
+    }
+    if (overfull) return;   // the same decision in every part of the row
+
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
+    const int tbin = (int)tb.bin;
+    uint32_t n_above = 0;
+    SV_PART_ITEMS({
+        const int bin = value_bin<kPartBins>(v, rp.lo, rp.inv);
+        n_above += bin > tbin ? 1u : 0u;
+        if (bin == tbin) {
+            const uint32_t slot = atomicAdd(ws.cand_count + unit, 1u);
+            if (slot < (uint32_t)kMaxCand) {
+                ws.cand_key[unit * kMaxCand + slot] = score_key(v);
+                ws.cand_idx[unit * kMaxCand + slot] = pv.j0 + i * kWave;
+            }
+        }
+    })
+    // integer sum over the workgroup
+    n_above = wave_inclusive_scan(n_above, lane);
+    if (lane == kWave - 1) wave_tot[wave] = n_above;
+    __syncthreads();
+    if (tid == 0) ws.part_above[unit * parts + part] = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+}
+
+// C. exact threshold from the candidates, output offset of this part, ordered emission.
+template <int ITEMS>
+__global__ __launch_bounds__(kPartThreads) void select_emit_kernel(const SelectArgs a, const SelectWorkspace ws,
+                                                                  const int parts, const int part_len) {
+    __shared__ union {
+        struct {
+            uint32_t cand_key[kMaxCand];
+            int32_t cand_idx[kMaxCand];
+        } c;
+        RadixShared rx;
+    } sh;
+    __shared__ uint32_t part_kept[kMaxParts];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t thr_key_sh;
+    __shared__ int32_t thr_idx_sh;
+    const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
+    int32_t* __restrict__ out = a.idx + unit * a.k;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (emit_trivial<kPartThreads>(a, unit, n, kb, part, parts, tid)) return;
+    const RowParams rp = ws.params[unit];
+    if (rp.flag != kFlagOk) {   // degenerate range or overfull threshold bin: one workgroup redoes the row
+        if (part == 0) radix_select_row<kPartThreads>(sh.rx, s, out, n, kb, tid, lane, wave);
+        return;
+    }
+    const int tbin = (int)rp.tbin;
+    const uint32_t need = rp.need, in_bin = rp.in_bin;
+    const int live_parts = (n + part_len - 1) / part_len;
+
+    if (tid < kMaxParts) part_kept[tid] = 0;
+    if (tid == 0) { thr_key_sh = 0; thr_idx_sh = 0x7fffffff; }   // default: the whole threshold bin is kept
+    for (uint32_t c = tid; c < in_bin; c += kPartThreads) {
+        sh.c.cand_key[c] = ws.cand_key[unit * kMaxCand + c];
+        sh.c.cand_idx[c] = ws.cand_idx[unit * kMaxCand + c];
+    }
+    __syncthreads();
+    if (need < in_bin)
+        rank_candidates<kPartThreads>(sh.c.cand_key, sh.c.cand_idx, in_bin, need, &thr_key_sh, &thr_idx_sh, tid);
+    __syncthreads();
+    const uint32_t thr_key = thr_key_sh;
+    const int32_t thr_idx = thr_idx_sh;
+    // kept threshold-bin members of the parts before this one
+    for (uint32_t c = tid; c < in_bin; c += kPartThreads) {
+        const uint32_t key = sh.c.cand_key[c];
+        const int32_t j = sh.c.cand_idx[c];
+        const bool keep = key > thr_key || (key == thr_key && j <= thr_idx);
+        const int p = j / part_len;
+        if (keep && p < part) atomicAdd(&part_kept[p], 1u);
+    }
+    __syncthreads();
+    uint32_t base = 0;
+    for (int p = 0; p < part && p < live_parts; ++p) base += ws.part_above[unit * parts + p] + part_kept[p];
+
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
+    uint32_t keep_bits = 0, n_keep = 0;
+    auto is_kept = [&](float v, int i) -> bool {
+        const int bin = value_bin<kPartBins>(v, rp.lo, rp.inv);
+        if (bin != tbin) return bin > tbin;
+        const uint32_t key = score_key(v);
+        return key > thr_key || (key == thr_key && (pv.j0 + i * kWave) <= thr_idx);
+    };
+    const int loop_items = ITEMS > 0 ? ITEMS : pv.items;
+    if (ITEMS > 0) {
+#pragma unroll
+        for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) {
+            const bool keep = i < pv.my_items && is_kept(vals[i], i);
+            keep_bits |= keep ? (1u << i) : 0u;
+            n_keep += (uint32_t)__popcll(__ballot(keep));
+        }
+    } else {
+        for (int i = 0; i < loop_items; ++i) {
+            const bool keep = i < pv.my_items && is_kept(s[pv.j0 + i * kWave], i);
+            n_keep += (uint32_t)__popcll(__ballot(keep));
+        }
+    }
+    if (lane == 0) wave_tot[wave] = n_keep;
+    __syncthreads();
+    uint32_t pos = base;
+#pragma unroll
+    for (int w = 0; w < kPartThreads / kWave; ++w) pos += (w < wave) ? wave_tot[w] : 0u;
+    const uint64_t lane_lt = (1ull << lane) - 1ull;
+    auto emit = [&](bool keep, int i) {
+        const uint64_t ballot = __ballot(keep);
+        const uint32_t slot = pos + (uint32_t)__popcll(ballot & lane_lt);
+        if (keep && slot < (uint32_t)kb) out[slot] = pv.j0 + i * kWave;
+        pos += (uint32_t)__popcll(ballot);
     };
     if (ITEMS > 0) {
 #pragma unroll
-        for (int i = 0; i < R; ++i) emit_item(i);
+        for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) emit((keep_bits >> i) & 1u, i);
     } else {
-        for (int i = 0; i < n_items; ++i) emit_item(i);
+        for (int i = 0; i < loop_items; ++i) emit(i < pv.my_items && is_kept(s[pv.j0 + i * kWave], i), i);
     }
+}
+
+#undef SV_PART_ITEMS
+#undef SV_PART_LOAD
+
+struct SelectPlan { int parts, part_len, items; };   // items == 0: scores re-read from memory
+
+SelectPlan plan_select(int n_vis_max) {
+    SelectPlan p{};
+    if (n_vis_max <= kSingleMaxN) { p.parts = 1; p.part_len = kSingleMaxN; p.items = 4; return p; }
+    if (n_vis_max <= kPartLen * kMaxParts) {
+        p.parts = (n_vis_max + kPartLen - 1) / kPartLen;
+        p.part_len = kPartLen;
+        p.items = kPartLen / kPartThreads;
+        return p;
+    }
+    p.parts = kMaxParts;
+    p.part_len = ((n_vis_max + kMaxParts - 1) / kMaxParts + kPartThreads - 1) / kPartThreads * kPartThreads;
+    p.items = 0;
+    return p;
+}
+
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct WsLayout { size_t hist, above, count, key, idx, params, total; };
+
+WsLayout layout_select_ws(size_t units, int parts) {
+    WsLayout l{};
+    size_t off = 0;
+    l.hist = off; off += align256(units * parts * kPartBins * sizeof(uint32_t));
+    l.above = off; off += align256(units * parts * sizeof(uint32_t));
+    l.count = off; off += align256(units * sizeof(uint32_t));
+    l.key = off; off += align256(units * kMaxCand * sizeof(uint32_t));
+    l.idx = off; off += align256(units * kMaxCand * sizeof(int32_t));
+    l.params = off; off += align256(units * sizeof(RowParams));
+    l.total = off;
+    return l;
 }
 
 }  // namespace
 
+size_t select_workspace_bytes(int B, int Hkv, int n_vis_max) {
+    const SelectPlan p = plan_select(n_vis_max);
+    if (p.parts == 1) return 0;
+    return layout_select_ws((size_t)B * Hkv, p.parts).total;
+}
+
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     if (a.B == 0 || a.Hkv == 0) return hipSuccess;
-    dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSelThreads);
-    const int n = a.n_vis_max;
-    // register-resident variants up to 50 keys per lane (128 VGPRs at 1024 lanes per workgroup)
-    if (n <= kSelThreads * 4)
-        hipLaunchKernelGGL((select_kernel<4>), grid, block, 0, stream, a);
-    else if (n <= kSelThreads * 16)
-        hipLaunchKernelGGL((select_kernel<16>), grid, block, 0, stream, a);
-    else if (n <= kSelThreads * 32)
-        hipLaunchKernelGGL((select_kernel<32>), grid, block, 0, stream, a);
-    else if (n <= kSelThreads * 50)
-        hipLaunchKernelGGL((select_kernel<50>), grid, block, 0, stream, a);
-    else
-        hipLaunchKernelGGL((select_kernel<0>), grid, block, 0, stream, a);
+    const SelectPlan p = plan_select(a.n_vis_max);
+    if (p.parts == 1) {
+        dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
+        hipLaunchKernelGGL((select_single_kernel<4>), grid, block, 0, stream, a);
+        return hipGetLastError();
+    }
+    const WsLayout l = layout_select_ws((size_t)a.B * a.Hkv, p.parts);
+    char* base = static_cast<char*>(a.ws);
+    SelectWorkspace ws;
+    ws.part_hist = reinterpret_cast<uint32_t*>(base + l.hist);
+    ws.part_above = reinterpret_cast<uint32_t*>(base + l.above);
+    ws.cand_count = reinterpret_cast<uint32_t*>(base + l.count);
+    ws.cand_key = reinterpret_cast<uint32_t*>(base + l.key);
+    ws.cand_idx = reinterpret_cast<int32_t*>(base + l.idx);
+    ws.params = reinterpret_cast<RowParams*>(base + l.params);
+    dim3 grid((unsigned)p.parts, (unsigned)a.Hkv, (unsigned)a.B), block(kPartThreads);
+    if (p.items > 0) {
+        hipLaunchKernelGGL((select_hist_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_threshold_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_emit_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+    } else {
+        hipLaunchKernelGGL((select_hist_kernel<0>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_threshold_kernel<0>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_emit_kernel<0>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+    }
     return hipGetLastError();
 }
 

@@ -134,30 +134,41 @@ def test_strided_token_major_cache_layout():
 
 # ------------------------------------------------------------------ selection, integer-exact
 @pytest.mark.parametrize("n,k", [(1, 1), (63, 5), (64, 64), (1000, 1), (4096, 512), (4097, 4000),
-                                 (16385, 300), (33000, 1650), (50176, 2509), (53000, 17), (70000, 3500)])
+                                 (8192, 512), (16385, 300), (33000, 1650), (50176, 2509), (53000, 17),
+                                 (65536, 65535), (70000, 3500), (200001, 777)])
 def test_select_is_bit_exact_on_given_scores(n, k):
+    """Every launch shape of the selection (one workgroup; 4096-score parts; streaming parts) and
+    every data-dependent path (value bins, exact ranking, radix fallback) against a full sort."""
     import paper_2510_17777_amd as sv
     rng = np.random.default_rng(n + k)
-    B, Hkv = 2, 3
+    B, Hkv = 3, 3
     s = rng.standard_normal((B, Hkv, n)).astype(np.float32)
-    s[0, 0] = np.round(s[0, 0] * 4) / 4          # heavy ties
-    s[0, 1] = 0.5                                 # all equal
+    s[0, 0] = np.round(s[0, 0] * 4) / 4          # heavy ties: overfull threshold bin -> radix path
+    s[0, 1] = 0.5                                 # all equal: degenerate range
     s[1, 0, ::3] = -0.0
     s[1, 0, 1::3] = 0.0                           # signed zeros tie
     s[1, 1] = -np.abs(s[1, 1])                    # all negative
     s[1, 2] = np.sort(s[1, 2])                    # winners at the end of the row
-    vis_len = np.array([n, max(n - 7, 0)], np.int32)
+    s[2, 0] = 1.0
+    s[2, 0, rng.integers(0, n, size=max(1, n // 50))] = 1e30     # a few huge outliers over a constant
+    s[2, 1] = np.where(rng.random(n) < 0.5, -np.inf, s[2, 1])    # half the row masked out
+    s[2, 2] = (rng.standard_normal(n) * 1e-30).astype(np.float32)  # tiny magnitudes
+    vis_len = np.array([n, max(n - 7, 0), n // 3], np.int32)
     sd = torch.from_numpy(s).to("cuda:0")
     q = torch.zeros((B, Hkv, 64), dtype=torch.float16, device="cuda:0")
     kv = torch.zeros((B, Hkv, n, 64), dtype=torch.float16, device="meta")
     shape = sv.make_shape(q, kv, None, k, vis_len=vis_len)
+    ws = torch.empty((sv.workspace_bytes(shape),), dtype=torch.uint8, device="cuda:0")
     idx = torch.full((B, Hkv, k), -9, dtype=torch.int32, device="cuda:0")
     cnt = torch.full((B, Hkv), -9, dtype=torch.int32, device="cuda:0")
-    sv.sv_topk_select(shape, sd, idx, cnt)
+    sv.sv_topk_select(shape, sd, idx, cnt, ws)
     torch.cuda.synchronize()
     want_idx, want_cnt = oracle.topk_select(s.astype(np.float64), k, vis_len)
     assert np.array_equal(cnt.cpu().numpy(), want_cnt)
-    assert np.array_equal(idx.cpu().numpy(), want_idx)
+    got = idx.cpu().numpy()
+    for b in range(B):
+        for g in range(Hkv):
+            assert np.array_equal(got[b, g], want_idx[b, g]), (b, g)
 
 
 # ------------------------------------------------------------------ edge cases
