@@ -22,13 +22,16 @@
 //   * rows of at most 4096 scores: one 1024-lane workgroup per (b, g), scores in
 //     registers, exact min/max as the range;
 //   * longer rows: a single compute unit cannot pull a long row from memory fast
-//     enough, so the row is cut into parts of 4096 scores (at most 16 parts) and three
+//     enough, so the row is cut into parts of 8192 scores (at most 8 parts) and three
 //     kernels run over (part, g, b):  A. per-part histogram, the range taken from a
-//     256-score strided sample that every part reads identically;  B. every part sums
+//     64-score strided sample that every part reads identically;  B. every part sums
 //     the part histograms, finds the threshold bin, counts its own scores above it and
-//     appends its threshold-bin members to the row's candidate list;  C. every part
-//     ranks the candidates, derives its output offset, and emits its kept indices.
-//     No workgroup waits for another: the kernel boundaries are the only barriers.
+//     stores its threshold-bin members in its own candidate slots;  C. every part
+//     gathers and ranks the candidates, derives its output offset, and emits its kept
+//     indices.  No workgroup waits for another (kernel boundaries are the only
+//     barriers) and no global atomic is used: a returning device-scope atomic costs
+//     microseconds here.  Every kernel issues all its global loads up front, because
+//     one dependent round trip through memory costs more than the arithmetic.
 #include "sv_device.h"
 #include "sv_kernels.h"
 
@@ -38,11 +41,14 @@ namespace sv {
 namespace {
 
 constexpr int kBins = 2048;        // single-workgroup shape, and radix digits
-constexpr int kPartBins = 512;     // multi-part shape
+constexpr int kPartBins = 2048;    // multi-part shape
 constexpr int kMaxCand = 1024;
-constexpr int kPartLen = 4096;
-constexpr int kMaxParts = 16;
+constexpr int kPartLen = 8192;
+constexpr int kMaxParts = 8;
+constexpr int kPartItems = kPartLen / 256;    // scores per lane when a part sits in registers
+constexpr int kPartCand = kMaxCand / kMaxParts;   // candidate slots per part
 constexpr int kPartThreads = 256;
+constexpr int kSampleLanes = 64;
 constexpr int kSingleThreads = 1024;
 constexpr int kSingleMaxN = 4096;
 
@@ -334,15 +340,13 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
 
 // ------------------------------------------------------------------ multi-part shape
 struct PartView {   // how one 256-lane workgroup sees its part of the row
-    int part_len;   // scores per part (multiple of 256)
-    int items;      // scores per lane: part_len / 256
+    int items;      // item slots per lane: part_len / 256
     int j0;         // index of this lane's item 0
     int my_items;   // live items of this lane
 };
 
 __device__ __forceinline__ PartView part_view(int part, int part_len, int n, int lane, int wave) {
     PartView v;
-    v.part_len = part_len;
     v.items = part_len / kPartThreads;
     const int wave_len = part_len / (kPartThreads / kWave);   // contiguous range of one wavefront
     v.j0 = part * part_len + wave * wave_len + lane;
@@ -362,6 +366,7 @@ __device__ __forceinline__ PartView part_view(int part, int part_len, int n, int
         for (int i = 0; i < pv.my_items; ++i) { const float v = s[pv.j0 + i * kWave]; __VA_ARGS__ } \
     }
 
+// Issues the loads of this lane's items (register-resident shape only).
 #define SV_PART_LOAD()                                                      \
     float vals[ITEMS > 0 ? ITEMS : 1];                                      \
     if (ITEMS > 0) {                                                        \
@@ -370,21 +375,21 @@ __device__ __forceinline__ PartView part_view(int part, int part_len, int n, int
     }                                                                       \
     (void)vals;
 
+struct PartMeta { uint32_t above, n_cand; };   // n_cand > kPartCand: this part overflowed its slots
+
 struct SelectWorkspace {
-    uint32_t* part_hist;    // [units][parts][kPartBins]
-    uint32_t* part_above;   // [units][parts]
-    uint32_t* cand_count;   // [units]
-    uint32_t* cand_key;     // [units][kMaxCand]
-    int32_t* cand_idx;      // [units][kMaxCand]
+    uint16_t* part_hist;    // [units][parts][kPartBins], saturating at 65535
+    PartMeta* part_meta;    // [units][parts]
+    uint2* cand;            // [units][parts][kPartCand]  (key, index); key 0 = empty slot
     RowParams* params;      // [units]
 };
 
-// A. per-part value histogram; the bin range comes from a strided 256-score sample.
+// A. per-part value histogram; the bin range comes from a strided 64-score sample.
 template <int ITEMS>
 __global__ __launch_bounds__(kPartThreads) void select_hist_kernel(const SelectArgs a, const SelectWorkspace ws,
                                                                   const int parts, const int part_len) {
     __shared__ uint32_t hist[kPartBins];
-    __shared__ float wmin[4], wmax[4];
+    __shared__ float range_sh[2];
     const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
@@ -393,45 +398,50 @@ __global__ __launch_bounds__(kPartThreads) void select_hist_kernel(const SelectA
     const int kb = a.k < n ? a.k : n;
     if (kb == 0 || kb == n) return;   // kernel C handles these without the histogram
 
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
     // Range estimate: every part of the row reads the same sample, hence the same range.
-    const float sv = clamp_finite(s[(int)(((int64_t)tid * n) / kPartThreads)]);
-    float lo = wave_min_f(sv), hi = wave_max(sv);
-    if (lane == 0) { wmin[wave] = lo; wmax[wave] = hi; }
-    hist[tid] = 0;
-    hist[tid + kPartThreads] = 0;
+    if (wave == 0) {
+        const float sv = clamp_finite(s[(int)(((int64_t)lane * n) / kSampleLanes)]);
+        const float lo = wave_min_f(sv), hi = wave_max(sv);
+        if (lane == 0) { range_sh[0] = lo; range_sh[1] = hi; }
+    }
+#pragma unroll
+    for (int i = 0; i < kPartBins / kPartThreads; ++i) hist[tid + i * kPartThreads] = 0;
     __syncthreads();
-    lo = fminf(fminf(wmin[0], wmin[1]), fminf(wmin[2], wmin[3]));
-    hi = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
     // widen by the sample range on both sides: scores outside the sample's span still
     // land in distinct bins; anything beyond clamps into the end bins
-    const float r = hi - lo;
-    const float lo_w = lo - r;
+    const float r = range_sh[1] - range_sh[0];
+    const float lo_w = range_sh[0] - r;
     const float inv = (float)kPartBins / (3.f * r);
     const bool ok = r > 0.f && r <= FLT_MAX / 4.f && inv > 0.f && inv <= FLT_MAX;
     if (part == 0 && tid == 0) {
         RowParams p{};
         p.lo = lo_w; p.inv = inv; p.flag = ok ? kFlagOk : kFlagDegenerate;
         ws.params[unit] = p;
-        ws.cand_count[unit] = 0;
     }
     if (!ok) return;   // block-uniform, and the same in every part of the row
 
-    const PartView pv = part_view(part, part_len, n, lane, wave);
-    SV_PART_LOAD()
     SV_PART_ITEMS(atomicAdd(&hist[value_bin<kPartBins>(v, lo_w, inv)], 1u);)
     __syncthreads();
-    uint32_t* dst = ws.part_hist + (unit * parts + part) * kPartBins;
-    dst[tid] = hist[tid];
-    dst[tid + kPartThreads] = hist[tid + kPartThreads];
+    uint16_t* dst = ws.part_hist + (unit * parts + part) * kPartBins;
+#pragma unroll
+    for (int i = 0; i < kPartBins / kPartThreads; ++i) {
+        const uint32_t c = hist[tid + i * kPartThreads];
+        dst[tid + i * kPartThreads] = (uint16_t)(c < 65535u ? c : 65535u);
+    }
 }
 
 // B. threshold bin of the row; this part's count above it; its threshold-bin members.
 template <int ITEMS>
 __global__ __launch_bounds__(kPartThreads) void select_threshold_kernel(const SelectArgs a, const SelectWorkspace ws,
                                                                        const int parts, const int part_len) {
+    constexpr int BPT = kPartBins / kPartThreads;   // 8 consecutive bins per thread
     __shared__ uint32_t hist[kPartBins];
+    __shared__ uint2 cand_sh[kPartCand];
     __shared__ uint32_t wave_tot[4];
     __shared__ ThresholdBin tb_sh;
+    __shared__ uint32_t n_cand_sh, saturated_sh;
     const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
@@ -439,22 +449,42 @@ __global__ __launch_bounds__(kPartThreads) void select_threshold_kernel(const Se
     const int n = live_rows(a.vis_len, b, a.n_vis_max);
     const int kb = a.k < n ? a.k : n;
     if (kb == 0 || kb == n) return;
+
+    // all global loads first: parameters, the part histograms (8 bins per thread per part), own scores
     const RowParams rp = ws.params[unit];
+    const int live_parts = (n + part_len - 1) / part_len;
+    const uint16_t* src = ws.part_hist + unit * parts * kPartBins + tid * BPT;
+    uint4 hraw[kMaxParts];
+#pragma unroll
+    for (int p = 0; p < kMaxParts; ++p)
+        hraw[p] = p < live_parts ? *reinterpret_cast<const uint4*>(src + p * kPartBins) : make_uint4(0, 0, 0, 0);
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
     if (rp.flag != kFlagOk) return;
 
-    const int live_parts = (n + part_len - 1) / part_len;
-    const uint32_t* src = ws.part_hist + unit * parts * kPartBins;
-    uint32_t h0 = 0, h1 = 0;
-    for (int p = 0; p < live_parts; ++p) {
-        h0 += src[p * kPartBins + tid];
-        h1 += src[p * kPartBins + tid + kPartThreads];
+    uint32_t sum[BPT];
+    bool sat = false;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) sum[i] = 0;
+#pragma unroll
+    for (int p = 0; p < kMaxParts; ++p) {
+        const uint32_t w[4] = {hraw[p].x, hraw[p].y, hraw[p].z, hraw[p].w};
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            const uint32_t c = (w[i / 2] >> (16 * (i & 1))) & 0xFFFFu;
+            sat |= c == 65535u;
+            sum[i] += c;
+        }
     }
-    hist[tid] = h0;
-    hist[tid + kPartThreads] = h1;
+    if (tid == 0) { n_cand_sh = 0; saturated_sh = 0; }
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) hist[tid * BPT + i] = sum[i];
+    if (tid < kPartCand) cand_sh[tid] = make_uint2(0u, 0u);
     __syncthreads();
+    if (sat) saturated_sh = 1;   // a 16-bit count hit its ceiling: the sums cannot be trusted
     const ThresholdBin tb =
         find_threshold_bin<kPartThreads, kPartBins>(hist, (uint32_t)kb, wave_tot, &tb_sh, tid, lane, wave);
-    const bool overfull = tb.in_bin > (uint32_t)kMaxCand;
+    const bool overfull = tb.in_bin > (uint32_t)kMaxCand || saturated_sh != 0;
     if (part == 0 && tid == 0) {
         RowParams* p = ws.params + unit;
         p->tbin = tb.bin; p->need = (uint32_t)kb - tb.above; p->in_bin = tb.in_bin;
@@ -462,26 +492,26 @@ __global__ __launch_bounds__(kPartThreads) void select_threshold_kernel(const Se
     }
     if (overfull) return;   // the same decision in every part of the row
 
-    const PartView pv = part_view(part, part_len, n, lane, wave);
-    SV_PART_LOAD()
     const int tbin = (int)tb.bin;
     uint32_t n_above = 0;
     SV_PART_ITEMS({
         const int bin = value_bin<kPartBins>(v, rp.lo, rp.inv);
         n_above += bin > tbin ? 1u : 0u;
         if (bin == tbin) {
-            const uint32_t slot = atomicAdd(ws.cand_count + unit, 1u);
-            if (slot < (uint32_t)kMaxCand) {
-                ws.cand_key[unit * kMaxCand + slot] = score_key(v);
-                ws.cand_idx[unit * kMaxCand + slot] = pv.j0 + i * kWave;
-            }
+            const uint32_t slot = atomicAdd(&n_cand_sh, 1u);   // LDS
+            if (slot < (uint32_t)kPartCand) cand_sh[slot] = make_uint2(score_key(v), (uint32_t)(pv.j0 + i * kWave));
         }
     })
-    // integer sum over the workgroup
-    n_above = wave_inclusive_scan(n_above, lane);
+    n_above = wave_inclusive_scan(n_above, lane);   // integer sum over the workgroup
     if (lane == kWave - 1) wave_tot[wave] = n_above;
     __syncthreads();
-    if (tid == 0) ws.part_above[unit * parts + part] = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    if (tid < kPartCand) ws.cand[(unit * parts + part) * kPartCand + tid] = cand_sh[tid];
+    if (tid == 0) {
+        PartMeta m;
+        m.above = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        m.n_cand = n_cand_sh;
+        ws.part_meta[unit * parts + part] = m;
+    }
 }
 
 // C. exact threshold from the candidates, output offset of this part, ordered emission.
@@ -489,16 +519,13 @@ template <int ITEMS>
 __global__ __launch_bounds__(kPartThreads) void select_emit_kernel(const SelectArgs a, const SelectWorkspace ws,
                                                                   const int parts, const int part_len) {
     __shared__ union {
-        struct {
-            uint32_t cand_key[kMaxCand];
-            int32_t cand_idx[kMaxCand];
-        } c;
+        uint64_t cand[kMaxCand];   // (key << 32) | ~index: larger = earlier in (score desc, index asc) order
         RadixShared rx;
     } sh;
-    __shared__ uint32_t part_kept[kMaxParts];
+    __shared__ uint32_t part_kept[kMaxParts], part_above[kMaxParts];
     __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t thr_key_sh;
-    __shared__ int32_t thr_idx_sh;
+    __shared__ uint32_t n_cand_sh, overflow_sh;
+    __shared__ uint64_t thr_sh;
     const int part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
@@ -507,49 +534,76 @@ __global__ __launch_bounds__(kPartThreads) void select_emit_kernel(const SelectA
     const int n = live_rows(a.vis_len, b, a.n_vis_max);
     const int kb = a.k < n ? a.k : n;
     if (emit_trivial<kPartThreads>(a, unit, n, kb, part, parts, tid)) return;
+
+    // all global loads first
     const RowParams rp = ws.params[unit];
+    const int live_parts = (n + part_len - 1) / part_len;
+    uint2 craw[kMaxParts / 2];   // thread t: slot t%128 of parts 2m + t/128
+#pragma unroll
+    for (int m = 0; m < kMaxParts / 2; ++m) {
+        const int p = 2 * m + tid / kPartCand;
+        craw[m] = p < live_parts ? ws.cand[(unit * parts + p) * kPartCand + (tid % kPartCand)] : make_uint2(0u, 0u);
+    }
+    PartMeta meta{};
+    if (tid < live_parts) meta = ws.part_meta[unit * parts + tid];
+    const PartView pv = part_view(part, part_len, n, lane, wave);
+    SV_PART_LOAD()
+
     if (rp.flag != kFlagOk) {   // degenerate range or overfull threshold bin: one workgroup redoes the row
         if (part == 0) radix_select_row<kPartThreads>(sh.rx, s, out, n, kb, tid, lane, wave);
         return;
     }
-    const int tbin = (int)rp.tbin;
-    const uint32_t need = rp.need, in_bin = rp.in_bin;
-    const int live_parts = (n + part_len - 1) / part_len;
-
-    if (tid < kMaxParts) part_kept[tid] = 0;
-    if (tid == 0) { thr_key_sh = 0; thr_idx_sh = 0x7fffffff; }   // default: the whole threshold bin is kept
-    for (uint32_t c = tid; c < in_bin; c += kPartThreads) {
-        sh.c.cand_key[c] = ws.cand_key[unit * kMaxCand + c];
-        sh.c.cand_idx[c] = ws.cand_idx[unit * kMaxCand + c];
+    if (tid == 0) { n_cand_sh = 0; overflow_sh = 0; thr_sh = 0; }   // threshold 0: the whole bin is kept
+    if (tid < kMaxParts) { part_kept[tid] = 0; part_above[tid] = 0; }
+    __syncthreads();
+    if (tid < live_parts) {
+        part_above[tid] = meta.above;
+        if (meta.n_cand > (uint32_t)kPartCand) overflow_sh = 1;
+    }
+#pragma unroll
+    for (int m = 0; m < kMaxParts / 2; ++m) {
+        if (craw[m].x != 0u) {
+            const uint32_t slot = atomicAdd(&n_cand_sh, 1u);   // LDS; order is irrelevant to the ranking
+            sh.cand[slot] = ((uint64_t)craw[m].x << 32) | (uint64_t)(0xFFFFFFFFu - craw[m].y);
+        }
     }
     __syncthreads();
-    if (need < in_bin)
-        rank_candidates<kPartThreads>(sh.c.cand_key, sh.c.cand_idx, in_bin, need, &thr_key_sh, &thr_idx_sh, tid);
+    if (overflow_sh) {   // a part had more threshold-bin members than slots (block-uniform)
+        __syncthreads();
+        if (part == 0) radix_select_row<kPartThreads>(sh.rx, s, out, n, kb, tid, lane, wave);
+        return;
+    }
+    const int tbin = (int)rp.tbin;
+    const uint32_t need = rp.need, n_cand = n_cand_sh;
+    if (need < n_cand) {
+        for (uint32_t c = tid; c < n_cand; c += kPartThreads) {
+            const uint64_t mine = sh.cand[c];
+            uint32_t rank = 0;
+#pragma unroll 8
+            for (uint32_t u = 0; u < n_cand; ++u) rank += sh.cand[u] > mine ? 1u : 0u;
+            if (rank == need - 1) thr_sh = mine;
+        }
+    }
     __syncthreads();
-    const uint32_t thr_key = thr_key_sh;
-    const int32_t thr_idx = thr_idx_sh;
+    const uint64_t thr = thr_sh;
     // kept threshold-bin members of the parts before this one
-    for (uint32_t c = tid; c < in_bin; c += kPartThreads) {
-        const uint32_t key = sh.c.cand_key[c];
-        const int32_t j = sh.c.cand_idx[c];
-        const bool keep = key > thr_key || (key == thr_key && j <= thr_idx);
-        const int p = j / part_len;
-        if (keep && p < part) atomicAdd(&part_kept[p], 1u);
+    for (uint32_t c = tid; c < n_cand; c += kPartThreads) {
+        const uint64_t e = sh.cand[c];
+        const int p = (int)(0xFFFFFFFFu - (uint32_t)e) / part_len;
+        if (e >= thr && p < part) atomicAdd(&part_kept[p], 1u);
     }
     __syncthreads();
     uint32_t base = 0;
-    for (int p = 0; p < part && p < live_parts; ++p) base += ws.part_above[unit * parts + p] + part_kept[p];
+#pragma unroll
+    for (int p = 0; p < kMaxParts; ++p) base += p < part ? part_above[p] + part_kept[p] : 0u;
 
-    const PartView pv = part_view(part, part_len, n, lane, wave);
-    SV_PART_LOAD()
     uint32_t keep_bits = 0, n_keep = 0;
     auto is_kept = [&](float v, int i) -> bool {
         const int bin = value_bin<kPartBins>(v, rp.lo, rp.inv);
         if (bin != tbin) return bin > tbin;
-        const uint32_t key = score_key(v);
-        return key > thr_key || (key == thr_key && (pv.j0 + i * kWave) <= thr_idx);
+        const uint64_t e = ((uint64_t)score_key(v) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)(pv.j0 + i * kWave));
+        return e >= thr;
     };
-    const int loop_items = ITEMS > 0 ? ITEMS : pv.items;
     if (ITEMS > 0) {
 #pragma unroll
         for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) {
@@ -558,7 +612,7 @@ __global__ __launch_bounds__(kPartThreads) void select_emit_kernel(const SelectA
             n_keep += (uint32_t)__popcll(__ballot(keep));
         }
     } else {
-        for (int i = 0; i < loop_items; ++i) {
+        for (int i = 0; i < pv.items; ++i) {
             const bool keep = i < pv.my_items && is_kept(s[pv.j0 + i * kWave], i);
             n_keep += (uint32_t)__popcll(__ballot(keep));
         }
@@ -579,22 +633,22 @@ __global__ __launch_bounds__(kPartThreads) void select_emit_kernel(const SelectA
 #pragma unroll
         for (int i = 0; i < (ITEMS > 0 ? ITEMS : 1); ++i) emit((keep_bits >> i) & 1u, i);
     } else {
-        for (int i = 0; i < loop_items; ++i) emit(i < pv.my_items && is_kept(s[pv.j0 + i * kWave], i), i);
+        for (int i = 0; i < pv.items; ++i) emit(i < pv.my_items && is_kept(s[pv.j0 + i * kWave], i), i);
     }
 }
 
 #undef SV_PART_ITEMS
 #undef SV_PART_LOAD
 
-struct SelectPlan { int parts, part_len, items; };   // items == 0: scores re-read from memory
+struct SelectPlan { bool single; int parts, part_len, items; };   // items == 0: scores re-read from memory
 
 SelectPlan plan_select(int n_vis_max) {
     SelectPlan p{};
-    if (n_vis_max <= kSingleMaxN) { p.parts = 1; p.part_len = kSingleMaxN; p.items = 4; return p; }
+    if (n_vis_max <= kSingleMaxN) { p.single = true; p.parts = 1; p.part_len = kSingleMaxN; p.items = 4; return p; }
     if (n_vis_max <= kPartLen * kMaxParts) {
         p.parts = (n_vis_max + kPartLen - 1) / kPartLen;
         p.part_len = kPartLen;
-        p.items = kPartLen / kPartThreads;
+        p.items = kPartItems;
         return p;
     }
     p.parts = kMaxParts;
@@ -605,16 +659,14 @@ SelectPlan plan_select(int n_vis_max) {
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
-struct WsLayout { size_t hist, above, count, key, idx, params, total; };
+struct WsLayout { size_t hist, meta, cand, params, total; };
 
 WsLayout layout_select_ws(size_t units, int parts) {
     WsLayout l{};
     size_t off = 0;
-    l.hist = off; off += align256(units * parts * kPartBins * sizeof(uint32_t));
-    l.above = off; off += align256(units * parts * sizeof(uint32_t));
-    l.count = off; off += align256(units * sizeof(uint32_t));
-    l.key = off; off += align256(units * kMaxCand * sizeof(uint32_t));
-    l.idx = off; off += align256(units * kMaxCand * sizeof(int32_t));
+    l.hist = off; off += align256(units * parts * kPartBins * sizeof(uint16_t));
+    l.meta = off; off += align256(units * parts * sizeof(PartMeta));
+    l.cand = off; off += align256(units * parts * kPartCand * sizeof(uint2));
     l.params = off; off += align256(units * sizeof(RowParams));
     l.total = off;
     return l;
@@ -624,14 +676,14 @@ WsLayout layout_select_ws(size_t units, int parts) {
 
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max) {
     const SelectPlan p = plan_select(n_vis_max);
-    if (p.parts == 1) return 0;
+    if (p.single) return 0;
     return layout_select_ws((size_t)B * Hkv, p.parts).total;
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     if (a.B == 0 || a.Hkv == 0) return hipSuccess;
     const SelectPlan p = plan_select(a.n_vis_max);
-    if (p.parts == 1) {
+    if (p.single) {
         dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
         hipLaunchKernelGGL((select_single_kernel<4>), grid, block, 0, stream, a);
         return hipGetLastError();
@@ -639,17 +691,15 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     const WsLayout l = layout_select_ws((size_t)a.B * a.Hkv, p.parts);
     char* base = static_cast<char*>(a.ws);
     SelectWorkspace ws;
-    ws.part_hist = reinterpret_cast<uint32_t*>(base + l.hist);
-    ws.part_above = reinterpret_cast<uint32_t*>(base + l.above);
-    ws.cand_count = reinterpret_cast<uint32_t*>(base + l.count);
-    ws.cand_key = reinterpret_cast<uint32_t*>(base + l.key);
-    ws.cand_idx = reinterpret_cast<int32_t*>(base + l.idx);
+    ws.part_hist = reinterpret_cast<uint16_t*>(base + l.hist);
+    ws.part_meta = reinterpret_cast<PartMeta*>(base + l.meta);
+    ws.cand = reinterpret_cast<uint2*>(base + l.cand);
     ws.params = reinterpret_cast<RowParams*>(base + l.params);
     dim3 grid((unsigned)p.parts, (unsigned)a.Hkv, (unsigned)a.B), block(kPartThreads);
     if (p.items > 0) {
-        hipLaunchKernelGGL((select_hist_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
-        hipLaunchKernelGGL((select_threshold_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
-        hipLaunchKernelGGL((select_emit_kernel<16>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_hist_kernel<kPartItems>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_threshold_kernel<kPartItems>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
+        hipLaunchKernelGGL((select_emit_kernel<kPartItems>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
     } else {
         hipLaunchKernelGGL((select_hist_kernel<0>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
         hipLaunchKernelGGL((select_threshold_kernel<0>), grid, block, 0, stream, a, ws, p.parts, p.part_len);
