@@ -159,9 +159,13 @@ const char *sv_strerror(sv_status status);
 
 /*
  * Launch-shape knobs for measurement sweeps (not needed for correct use):
- * "score_rows_per_block", "attn_chunk".  Values outside the documented range of
- * a knob are rejected with SV_ERR_SHAPE and change nothing; 0 restores the
- * default.  Process-wide; not thread-safe against concurrent calls.
+ *   "score_rows_per_block"  rows of visual K one scoring workgroup covers, 64..65536, 0 = default
+ *   "attn_chunk"            tokens per attention workgroup, multiple of 64 in 64..1024, 0 = default
+ *   "score_stream_loads"    1 = non-temporal loads of visual K, 0 = plain loads, -1 = default
+ *   "attn_mfma"             fp16 caches: 1 = logits on the matrix cores, 0 = vector FMA, -1 = default
+ * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
+ * Process-wide; not thread-safe against concurrent calls.  Results never depend on
+ * the knobs beyond fp32 summation order in step 3.
  */
 sv_status sv_set_tuning(const char *name, int32_t value);
 int32_t sv_get_tuning(const char *name);

@@ -19,12 +19,14 @@ struct Tuning {
     int32_t score_rows_per_block = 0;   // 0 = default
     int32_t attn_chunk = 0;
     int32_t score_stream_loads = -1;    // -1 = default
+    int32_t attn_mfma = -1;             // -1 = default
 };
 Tuning g_tuning;
 
 constexpr int kDefaultScoreRows = 256;
 constexpr int kDefaultAttnChunk = 128;
 constexpr int kDefaultStreamLoads = 1;
+constexpr int kDefaultAttnMfma = 1;
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -141,6 +143,7 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     a.vis_sb = s->kv_vis_stride_b; a.vis_sh = s->kv_vis_stride_h; a.vis_sn = s->kv_vis_stride_n;
     a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
     a.chunk = g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
+    a.use_mfma = g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma;
     const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
     a.n_chunks = (int32_t)((t_max + a.chunk - 1) / a.chunk);
     return a;
@@ -282,6 +285,11 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.score_stream_loads = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "attn_mfma")) {
+        if (value < -1 || value > 1) return SV_ERR_SHAPE;
+        g_tuning.attn_mfma = value;
+        return SV_OK;
+    }
     return SV_ERR_SHAPE;
 }
 
@@ -292,6 +300,7 @@ int32_t sv_get_tuning(const char* name) {
     if (!std::strcmp(name, "attn_chunk")) return g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
     if (!std::strcmp(name, "score_stream_loads"))
         return g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
+    if (!std::strcmp(name, "attn_mfma")) return g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma;
     return -1;
 }
 

@@ -13,30 +13,12 @@
 //      across lane groups and wavefronts at the end.
 // Chunks write (m, l, acc); a second kernel merges them with the usual
 // log-sum-exp rule.  Everything accumulates in fp32 in a fixed order.
-#include "sv_device.h"
-#include "sv_kernels.h"
-
-#include <type_traits>
+#include "sv_attend_common.h"
 
 namespace sv {
 namespace {
 
-constexpr int kAttnWaves = 4;
-constexpr int kAttnThreads = kAttnWaves * kWave;
 constexpr int kAttnUnroll = 4;    // row loads in flight per lane
-constexpr int kHeadBlock = 8;     // query heads per workgroup when G > 8
-
-template <typename T>
-__device__ __forceinline__ float exp_for(float x) {
-    // fp32 caches are held to 1e-5: use the accurate exponential there.
-    return std::is_same<T, float>::value ? expf(x) : __expf(x);
-}
-
-__device__ __forceinline__ int clamp_len(const int32_t* p, int i, int hi) {
-    if (!p) return hi;
-    const int v = p[i];
-    return v < 0 ? 0 : (v < hi ? v : hi);
-}
 
 template <typename T, int D, int GB>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const AttnArgs a, const int hblk) {
@@ -54,9 +36,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const AttnAr
     const int c = lane % LPR, grp = lane / LPR;
     const int64_t unit = (int64_t)b * a.Hkv + g;
 
-    const int nt = clamp_len(a.txt_len, b, a.n_txt_max);
-    const int kc = (a.k > 0 && a.count) ? clamp_len(a.count, (int)unit, a.k) : 0;
-    const int T_len = nt + kc;
+    const TokenList tokens = token_list(a, b, unit);
+    const int T_len = tokens.len;
     const int t0 = s * CH;
     if (t0 >= T_len) return;   // block-uniform
 
@@ -72,16 +53,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const AttnAr
     const T* vtxt = static_cast<const T*>(a.v_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh + c * EPL;
     const T* kvis = static_cast<const T*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh + c * EPL;
     const T* vvis = static_cast<const T*>(a.v_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh + c * EPL;
-    const int32_t* idx_row = a.idx ? a.idx + unit * a.k : nullptr;
-
-    // Element offset of token t's row inside its cache (text or visual).
-    auto token_offset = [&](int t, bool& is_txt) -> int64_t {
-        is_txt = t < nt;
-        if (is_txt) return (int64_t)t * a.txt_sn;
-        int j = idx_row[t - nt];
-        j = j < 0 ? 0 : (j < a.n_vis_max ? j : a.n_vis_max - 1);   // a faulty idx must not fault the GPU
-        return (int64_t)j * a.vis_sn;
-    };
+    auto token_offset = [&](int t, bool& is_txt) -> int64_t { return tokens.offset(t, is_txt); };
 
     const int CW = CH / kAttnWaves;          // tokens per wavefront
     const int tw0 = t0 + wave * CW;
@@ -217,34 +189,81 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const AttnAr
 }
 
 // Merge of the chunk results of one query head: out = sum_s e^{m_s-m} acc_s / sum_s e^{m_s-m} l_s.
+// One workgroup per (b, h).  Lane groups of D/4 lanes each take every NG-th chunk with
+// 128-bit loads; all loads are issued before the maximum is known, so the kernel costs one
+// round trip through memory.
 template <typename T, int D>
-__global__ __launch_bounds__(D) void attn_combine_kernel(const AttnArgs a) {
-    const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(kAttnThreads) void attn_combine_kernel(const AttnArgs a) {
+    constexpr int LPG = D / 4;                  // lanes per chunk row (float4 each)
+    constexpr int NG = kAttnThreads / LPG;      // chunk rows in flight per pass
+    constexpr int R = 4;                        // passes kept in registers
+    __shared__ float s_red[kAttnWaves];
+    __shared__ float s_part[NG][D + 1];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int g = h / a.G;
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    const int nt = clamp_len(a.txt_len, b, a.n_txt_max);
-    const int kc = (a.k > 0 && a.count) ? clamp_len(a.count, (int)unit, a.k) : 0;
-    const int T_len = nt + kc;
+    const TokenList tokens = token_list(a, b, unit);
     const int S = a.n_chunks;
-    const int Sb = (T_len + a.chunk - 1) / a.chunk;
+    const int Sb = (tokens.len + a.chunk - 1) / a.chunk;
     const int64_t bh = (int64_t)b * a.Hq + h;
     if (Sb == 0) {
-        a.out[bh * D + d] = 0.f;
-        if (a.lse && d == 0) a.lse[bh] = -INFINITY;
+        if (tid < D) a.out[bh * D + tid] = 0.f;
+        if (a.lse && tid == 0) a.lse[bh] = -INFINITY;
         return;
     }
     const float* ml = a.part_ml + bh * S * 2;
     const float* acc = a.part_acc + bh * S * D;
-    float m = -INFINITY;
-    for (int s = 0; s < Sb; ++s) m = fmaxf(m, ml[2 * s]);
-    float L = 0.f, o = 0.f;
-    for (int s = 0; s < Sb; ++s) {
-        const float w = exp_for<T>(ml[2 * s] - m);
-        L = fmaf(w, ml[2 * s + 1], L);
-        o = fmaf(w, acc[(int64_t)s * D + d], o);
+    const int grp = tid / LPG, c4 = (tid % LPG) * 4;
+
+    float4_t av[R];
+    float mv[R], lv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int sidx = grp + r * NG;
+        av[r] = 0;
+        mv[r] = -INFINITY;
+        lv[r] = 0.f;
+        if (sidx < Sb) {
+            av[r] = *reinterpret_cast<const float4_t*>(acc + (int64_t)sidx * D + c4);
+            mv[r] = ml[2 * sidx];
+            lv[r] = ml[2 * sidx + 1];
+        }
     }
-    a.out[bh * D + d] = o / L;
-    if (a.lse && d == 0) a.lse[bh] = m + logf(L);
+    float m = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < R; ++r) m = fmaxf(m, mv[r]);
+    for (int sidx = grp + R * NG; sidx < Sb; sidx += NG) m = fmaxf(m, ml[2 * sidx]);
+    m = wave_max(m);
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+
+    float4_t o = {0.f, 0.f, 0.f, 0.f};
+    float L = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float w = mv[r] == -INFINITY ? 0.f : exp_for<T>(mv[r] - m);
+        o += w * av[r];
+        L = fmaf(w, lv[r], L);
+    }
+    for (int sidx = grp + R * NG; sidx < Sb; sidx += NG) {
+        const float ms = ml[2 * sidx];
+        const float w = ms == -INFINITY ? 0.f : exp_for<T>(ms - m);
+        o += w * *reinterpret_cast<const float4_t*>(acc + (int64_t)sidx * D + c4);
+        L = fmaf(w, ml[2 * sidx + 1], L);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s_part[grp][c4 + i] = o[i];
+    if (c4 == 0) s_part[grp][D] = L;
+    __syncthreads();
+    if (tid < D) {
+        float x = 0.f, Lt = 0.f;
+#pragma unroll
+        for (int q = 0; q < NG; ++q) { x += s_part[q][tid]; Lt += s_part[q][D]; }
+        a.out[bh * D + tid] = x / Lt;
+        if (a.lse && tid == 0) a.lse[bh] = m + logf(Lt);
+    }
 }
 
 template <typename T, int D, int GB>
@@ -260,7 +279,8 @@ hipError_t launch_typed(const AttnArgs& a, hipStream_t stream) {
     hipError_t e = hipSuccess;
     if (a.n_chunks > 0) {
         const int G = a.G;
-        if (G == 1) e = launch_partial<T, D, 1>(a, 1, stream);
+        if (std::is_same<T, _Float16>::value && a.use_mfma) e = launch_attn_partial_mfma(a, stream);
+        else if (G == 1) e = launch_partial<T, D, 1>(a, 1, stream);
         else if (G == 2) e = launch_partial<T, D, 2>(a, 1, stream);
         else if (G <= 4) e = launch_partial<T, D, 4>(a, 1, stream);
         else if (G == 7) e = launch_partial<T, D, 7>(a, 1, stream);
@@ -268,7 +288,7 @@ hipError_t launch_typed(const AttnArgs& a, hipStream_t stream) {
         else e = launch_partial<T, D, 8>(a, (G + kHeadBlock - 1) / kHeadBlock, stream);
         if (e != hipSuccess) return e;
     }
-    dim3 grid((unsigned)a.Hq, (unsigned)a.B), block(D);
+    dim3 grid((unsigned)a.Hq, (unsigned)a.B), block(kAttnThreads);
     hipLaunchKernelGGL((attn_combine_kernel<T, D>), grid, block, 0, stream, a);
     return hipGetLastError();
 }

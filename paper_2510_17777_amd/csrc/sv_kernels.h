@@ -47,6 +47,7 @@ struct AttnArgs {
     int64_t vis_sb, vis_sh, vis_sn;
     int64_t txt_sb, txt_sh, txt_sn;
     int32_t chunk;            // tokens per workgroup
+    int32_t use_mfma;         // fp16 caches: 1 = logits on the matrix cores, 0 = vector FMA path
     int32_t n_chunks;         // S = ceil((n_txt_max + k) / chunk)
 };
 

@@ -105,10 +105,16 @@ def test_stages_with_oracle_supplied_indices(dtype, D, G):
     inp = rand_inputs(7 + D + G, 2, Hkv * G, Hkv, D, 1500, 333, dtype)
     k = 217
     o = oracle.decode_step(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"], k)
-    r = run_stages(inp, k, idx=o["idx"], count=o["count"])
+    import paper_2510_17777_amd as sv
     tol = out_tolerance(dtype)
-    assert np.abs(r["out"] - o["out"]).max() <= tol
-    assert np.abs(r["lse"] - o["lse"]).max() <= tol
+    try:
+        for mfma in (1, 0):      # matrix-core logits and the vector-FMA path (fp32 caches always use the latter)
+            sv.sv_set_tuning("attn_mfma", mfma)
+            r = run_stages(inp, k, idx=o["idx"], count=o["count"])
+            assert np.abs(r["out"] - o["out"]).max() <= tol, mfma
+            assert np.abs(r["lse"] - o["lse"]).max() <= tol, mfma
+    finally:
+        sv.sv_set_tuning("attn_mfma", -1)
     rep = check_index_sets(o["scores"], k, None, r["idx"], r["count"])
     assert rep.ok, rep.failures[:3]
 
@@ -246,10 +252,11 @@ def test_tuning_knobs_change_launch_shape_not_results():
     inp = sv_inputs.make_inputs(w)
     base = run_step(inp, w.k)
     try:
-        for rows, chunk, nt in [(128, 64, 0), (2048, 256, 1), (640, 512, 1)]:
+        for rows, chunk, nt, mfma in [(128, 64, 0, 1), (2048, 256, 1, 0), (640, 512, 1, 1), (256, 128, 1, 0)]:
             sv.sv_set_tuning("score_rows_per_block", rows)
             sv.sv_set_tuning("attn_chunk", chunk)
             sv.sv_set_tuning("score_stream_loads", nt)
+            sv.sv_set_tuning("attn_mfma", mfma)
             r = run_step(inp, w.k, dev=base["dev"])
             assert np.array_equal(r["scores"], base["scores"])
             assert np.array_equal(r["idx"], base["idx"])
@@ -258,3 +265,4 @@ def test_tuning_knobs_change_launch_shape_not_results():
         sv.sv_set_tuning("score_rows_per_block", 0)
         sv.sv_set_tuning("attn_chunk", 0)
         sv.sv_set_tuning("score_stream_loads", -1)
+        sv.sv_set_tuning("attn_mfma", -1)
