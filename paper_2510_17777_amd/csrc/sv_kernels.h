@@ -58,6 +58,9 @@ hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials +
 // Scratch the selection needs for rows too long for one workgroup (0 for short rows).
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 
+// Tokens per workgroup of the matrix-core attention kernel (fixed by its register layout).
+int attn_mfma_chunk();
+
 // Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
 int score_row_granule(int dtype, int D);
 
