@@ -154,6 +154,13 @@ sv_status sv_decode_step(const sv_shape *shape, const void *q,
                          float *out, float *lse,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aid, not part of the decode path: copies `bytes` (a multiple of 16; both
+ * DEVICE pointers 16-byte aligned, non-overlapping) with a plain kernel.  Hardware
+ * traffic counters are calibrated against the known size of this copy.
+ */
+sv_status sv_copy_bytes(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *sv_strerror(sv_status status);
 

@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.sv_sparse_decode_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sv_decode_step.restype = ctypes.c_int
     lib.sv_decode_step.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sv_copy_bytes.restype = ctypes.c_int
+    lib.sv_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.sv_strerror.restype = ctypes.c_char_p
     lib.sv_strerror.argtypes = [ctypes.c_int]
     lib.sv_set_tuning.restype = ctypes.c_int
@@ -203,6 +205,10 @@ def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, cou
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
         _stream(stream)), "sv_decode_step")
+
+
+def sv_copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None) -> None:
+    _check(load_library().sv_copy_bytes(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)), "sv_copy_bytes")
 
 
 class DecodeBuffers:

@@ -256,6 +256,12 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
     return from_hip(sv::launch_attend(a, hs));
 }
 
+sv_status sv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return SV_ERR_NULL;
+    if (bytes % 16 || !aligned16(dst) || !aligned16(src)) return SV_ERR_ALIGN;
+    return from_hip(sv::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
 const char* sv_strerror(sv_status status) {
     switch (status) {
         case SV_OK: return "ok";

@@ -58,6 +58,9 @@ hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials +
 // Scratch the selection needs for rows too long for one workgroup (0 for short rows).
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 
+// Plain copy of `bytes` (multiple of 16) device bytes; calibration aid for traffic counters.
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
 // Tokens per workgroup of the matrix-core attention kernel (fixed by its register layout).
 int attn_mfma_chunk();
 
