@@ -28,8 +28,16 @@
 namespace sv {
 namespace {
 
-constexpr int kWaveTokens = 64;                          // tokens per wavefront
+#ifndef SV_ATTN_TOK
+#define SV_ATTN_TOK 64
+#endif
+#ifndef SV_ATTN_NW
+#define SV_ATTN_NW 4
+#endif
+constexpr int kWaveTokens = SV_ATTN_TOK;                 // tokens per wavefront
 constexpr int kTiles = kWaveTokens / 16;                 // MFMA token tiles per wavefront
+constexpr int kNW = SV_ATTN_NW;                          // wavefronts per workgroup
+constexpr int kNT = kNW * kWave;
 
 __device__ __forceinline__ float row16_max(float x) {
     x = fmaxf(x, dpp_move<kDppQuadXor1>(x));
@@ -40,17 +48,17 @@ __device__ __forceinline__ float row16_max(float x) {
 }
 
 template <int D, int GB>
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_mfma_kernel(const AttnArgs a, const int hblk) {
+__global__ __launch_bounds__(kNT) void attn_partial_mfma_kernel(const AttnArgs a, const int hblk) {
     using T = _Float16;
     constexpr int EPL = 8;
     constexpr int LPR = D / EPL;                 // lanes per value row
     constexpr int RPW = kWave / LPR;             // value rows per wavefront load
     constexpr int VSTEPS = kWaveTokens / RPW;    // value loads per lane
     constexpr int KB = D / 32;                   // MFMAs per 16-token tile
-    constexpr int CH = kAttnWaves * kWaveTokens;
-    __shared__ float s_p[kAttnWaves][GB][kWaveTokens];
-    __shared__ float s_acc[kAttnWaves][GB][D];
-    __shared__ float s_m[kAttnWaves][GB], s_l[kAttnWaves][GB];
+    constexpr int CH = kNW * kWaveTokens;
+    __shared__ float s_p[kNW][GB][kWaveTokens];
+    __shared__ float s_acc[kNW][GB][D];
+    __shared__ float s_m[kNW][GB], s_l[kNW][GB];
 
     const int s = blockIdx.x;
     const int g = blockIdx.y / hblk, hb = blockIdx.y % hblk;
@@ -113,9 +121,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_mfma_kernel(const A
             }
         }
         const int c = lane % LPR, grp = lane / LPR;
+        // the first half of the V rows rides along with the K rows; the second half is issued
+        // once the MFMAs have released the K registers (keeps the kernel at 3 wavefronts per SIMD)
+        constexpr int VH = VSTEPS / 2;
         Chunk<T> vc[VSTEPS];
 #pragma unroll
-        for (int u = 0; u < VSTEPS; ++u) {
+        for (int u = 0; u < VH; ++u) {
             const int tl = u * RPW + grp;
             const int code = __shfl(my_code, tl, kWave);
             vc[u] = zero_chunk<T>();
@@ -133,6 +144,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_mfma_kernel(const A
             const bool live = (tt * 16 + row) < n_live;
 #pragma unroll
             for (int r = 0; r < 4; ++r) lg[tt][r] = live ? acc[r] * a.scale : -INFINITY;
+        }
+#pragma unroll
+        for (int u = VH; u < VSTEPS; ++u) {
+            const int tl = u * RPW + grp;
+            const int code = __shfl(my_code, tl, kWave);
+            vc[u] = zero_chunk<T>();
+            if (tl < n_live) vc[u] = load_chunk(row_ptr(code, vtxt, vvis) + c * EPL);
         }
         // ---- softmax statistics of the wavefront's 64 tokens, per head, inside the 16-lane rows ----
 #pragma unroll
@@ -198,15 +216,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_mfma_kernel(const A
 
     // ---- merge the four wavefronts: one partial result per (head, chunk) ----
     const int S = a.n_chunks;
-    for (int o = threadIdx.x; o < GB * D; o += kAttnThreads) {
+    for (int o = threadIdx.x; o < GB * D; o += kNT) {
         const int h = o / D, d = o % D;
         if (h >= g_valid) continue;
         float m = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kAttnWaves; ++w) m = fmaxf(m, s_m[w][h]);
+        for (int w = 0; w < kNW; ++w) m = fmaxf(m, s_m[w][h]);
         float x = 0.f, l = 0.f;
 #pragma unroll
-        for (int w = 0; w < kAttnWaves; ++w) {
+        for (int w = 0; w < kNW; ++w) {
             const float mw = s_m[w][h];
             const float e = mw == -INFINITY ? 0.f : __expf(mw - m);
             x = fmaf(e, s_acc[w][h][d], x);
@@ -220,7 +238,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_mfma_kernel(const A
 
 template <int D, int GB>
 hipError_t launch_one(const AttnArgs& a, int hblk, hipStream_t stream) {
-    dim3 grid((unsigned)a.n_chunks, (unsigned)(a.Hkv * hblk), (unsigned)a.B), block(kAttnThreads);
+    dim3 grid((unsigned)a.n_chunks, (unsigned)(a.Hkv * hblk), (unsigned)a.B), block(kNT);
     hipLaunchKernelGGL((attn_partial_mfma_kernel<D, GB>), grid, block, 0, stream, a, hblk);
     return hipGetLastError();
 }
@@ -238,7 +256,7 @@ hipError_t launch_dim(const AttnArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-int attn_mfma_chunk() { return kAttnWaves * kWaveTokens; }
+int attn_mfma_chunk() { return kNW * kWaveTokens; }
 
 hipError_t launch_attn_partial_mfma(const AttnArgs& a, hipStream_t stream) {
     if (a.chunk != attn_mfma_chunk()) return hipErrorInvalidValue;
