@@ -170,6 +170,11 @@ const char *sv_strerror(sv_status status);
  *   "attn_chunk"            tokens per attention workgroup, multiple of 64 in 64..1024, 0 = default
  *   "score_stream_loads"    1 = non-temporal loads of visual K, 0 = plain loads, -1 = default
  *   "attn_mfma"             fp16 caches: 1 = logits on the matrix cores, 0 = vector FMA, -1 = default
+ *   "select_filter"         sv_decode_step on long rows: 1 = the scoring kernel hands the selection only the
+ *                           scores above a sampled threshold, 0 = the selection re-reads every score, -1 = default
+ *   "filter_rank"           which order statistic of the 512-row sample is that threshold, 1..448; 0 = derived
+ *                           from k / vis_len.  Any value gives the same result (a threshold that admits too
+ *                           few or too many candidates makes the row fall back to the full selection)
  * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
  * Process-wide; not thread-safe against concurrent calls.  Results never depend on
  * the knobs beyond fp32 summation order in step 3.

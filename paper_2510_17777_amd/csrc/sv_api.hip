@@ -20,6 +20,8 @@ struct Tuning {
     int32_t attn_chunk = 0;
     int32_t score_stream_loads = -1;    // -1 = default
     int32_t attn_mfma = -1;             // -1 = default
+    int32_t select_filter = -1;         // -1 = default
+    int32_t filter_rank = 0;            // 0 = derived from k / n
 };
 Tuning g_tuning;
 
@@ -27,6 +29,7 @@ constexpr int kDefaultScoreRows = 256;
 constexpr int kDefaultAttnChunk = 128;
 constexpr int kDefaultStreamLoads = 1;
 constexpr int kDefaultAttnMfma = 1;
+constexpr int kDefaultSelectFilter = 1;
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -76,6 +79,7 @@ struct Workspace {
     size_t acc_off, acc_bytes;
     size_t ml_off, ml_bytes;
     size_t sel_off, sel_bytes;
+    size_t filt_off, filt_bytes;   // candidate filter of sv_decode_step; 0 bytes when the shape does not qualify
     size_t total;
 };
 
@@ -92,7 +96,11 @@ Workspace plan_workspace(const sv_shape* s) {
     w.ml_bytes = align_up(B * Hq * S * 2 * sizeof(float));
     w.sel_off = w.ml_off + w.ml_bytes;
     w.sel_bytes = align_up(sv::select_workspace_bytes(s->batch, s->n_kv_heads, s->n_vis_max));
-    w.total = w.sel_off + w.sel_bytes;
+    w.filt_off = w.sel_off + w.sel_bytes;
+    w.filt_bytes = 0;
+    if (sv::filtered_select_applies(s->dtype, s->head_dim, s->n_vis_max, s->k))
+        w.filt_bytes = align_up(sv::filtered_workspace_bytes(s->dtype, s->head_dim, s->batch, s->n_kv_heads, s->n_vis_max));
+    w.total = w.filt_off + w.filt_bytes;
     if (w.total == 0) w.total = kAlign;
     return w;
 }
@@ -243,9 +251,21 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (has_vis) {
         float* sc = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(workspace) + w.scores_off);
-        hipError_t e = sv::launch_score(make_score_args(s, q, k_vis, sc), hs);
+        sv::ScoreArgs sa = make_score_args(s, q, k_vis, sc);
+        const bool filter = w.filt_bytes > 0 &&
+                            (g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter) != 0;
+        hipError_t e;
+        if (filter) {   // long rows: sample a threshold, let the scoring kernel emit the candidates above it
+            sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, s->dtype, s->head_dim,
+                                                 s->batch, s->n_kv_heads, s->n_vis_max, s->k, sa.rows_per_block);
+            sa.filt.rank_override = g_tuning.filter_rank;
+            e = sv::launch_presample(sa, hs);
+            if (e != hipSuccess) return SV_ERR_LAUNCH;
+        }
+        e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
-        e = sv::launch_select(make_select_args(s, w, workspace, sc, idx, count), hs);
+        const sv::SelectArgs sel = make_select_args(s, w, workspace, sc, idx, count);
+        e = filter ? sv::launch_select_filtered(sel, sa.filt, hs) : sv::launch_select(sel, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     } else if (count && (idx || s->k == 0)) {
         // nothing can be kept (k == 0 or no visual rows): the kept sets are empty, count = 0
@@ -297,6 +317,16 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.attn_mfma = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "select_filter")) {
+        if (value < -1 || value > 1) return SV_ERR_SHAPE;
+        g_tuning.select_filter = value;
+        return SV_OK;
+    }
+    if (!std::strcmp(name, "filter_rank")) {
+        if (value < 0 || value > 448) return SV_ERR_SHAPE;
+        g_tuning.filter_rank = value;
+        return SV_OK;
+    }
     return SV_ERR_SHAPE;
 }
 
@@ -308,6 +338,9 @@ int32_t sv_get_tuning(const char* name) {
     if (!std::strcmp(name, "score_stream_loads"))
         return g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
     if (!std::strcmp(name, "attn_mfma")) return g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma;
+    if (!std::strcmp(name, "select_filter"))
+        return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
+    if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;
     return -1;
 }
 

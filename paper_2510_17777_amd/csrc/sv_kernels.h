@@ -6,6 +6,26 @@
 
 namespace sv {
 
+// Candidate filter of sv_decode_step for long rows.  A threshold t_lo per (b, g), an order statistic
+// of the scores of a small sample of the row, lies below the k-th largest score with overwhelming
+// probability.  Every scoring workgroup stores the (score bits, row) pairs of its tile with
+// score >= t_lo, in row order: a 512-byte primary record per tile ({count,0,0,0}, then the first 62
+// pairs; records of consecutive tiles are adjacent) and, for fuller tiles, pair number f >= 62 at
+// position f of the tile's overflow rows.  The selection ranks those few candidates on chip.  The
+// outcome is checked on the device (at least k candidates, no more than fit); a row that fails is
+// selected from all its scores.
+constexpr int kFilterRecordPairs = 62;   // pairs in a primary record: 16-byte header + 62 * 8 bytes = 512 bytes
+
+struct FilterArgs {
+    float* t_lo;            // [units]
+    uint4* tiles;           // [units][n_tiles][32]
+    uint2* overflow;        // [units][n_tiles][tile_rows]
+    int32_t n_tiles;        // ceil(n_vis_max / tile_rows)
+    int32_t tile_rows;      // rows per scoring workgroup while the filter is on
+    int32_t k;
+    int32_t rank_override;  // > 0: use this sample rank for t_lo (tests force the fallbacks with it)
+};
+
 struct ScoreArgs {
     const void* q;
     const void* k_vis;
@@ -18,6 +38,7 @@ struct ScoreArgs {
     int64_t k_sb, k_sh, k_sn;
     int32_t rows_per_block;   // tuning; rounded up to the kernel's granule by the launcher
     int32_t stream_loads;     // 1: non-temporal K loads
+    FilterArgs filt;          // filt.tiles == nullptr: no candidate emission
 };
 
 struct SelectArgs {
@@ -55,6 +76,19 @@ hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials + combine
 
+// Candidate-filtered selection (sv_decode_step only).  filtered_select_applies(): is the shape
+// inside the limits of the on-chip ranking and is the expected candidate count small enough?
+bool filtered_select_applies(int dtype, int D, int n_vis_max, int k);
+size_t filtered_workspace_bytes(int dtype, int D, int B, int Hkv, int n_vis_max);   // for any tile_rows
+FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, int n_vis_max, int k,
+                                  int requested_tile_rows);
+// Tile rows the filter will use: `requested` rounded to the scoring kernel's granule, at most 512, raised
+// until the row has at most max_tiles tiles; 0 if that is impossible.
+int filter_tile_rows(int dtype, int D, int requested, int n_vis_max, int max_tiles);
+hipError_t launch_presample(const ScoreArgs& a, hipStream_t stream);   // writes filt.t_lo
+int presample_rows();                                                  // rows sampled per (b, g)
+hipError_t launch_select_filtered(const SelectArgs& a, const FilterArgs& f, hipStream_t stream);
+
 // Scratch the selection needs for rows too long for one workgroup (0 for short rows).
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 
@@ -66,5 +100,8 @@ int attn_mfma_chunk();
 
 // Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
 int score_row_granule(int dtype, int D);
+
+// Rows one wavefront pass of the scoring kernel covers (= rows of one candidate slot).
+int score_wave_rows(int dtype, int D);
 
 }  // namespace sv

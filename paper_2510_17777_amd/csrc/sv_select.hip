@@ -36,6 +36,7 @@
 #include "sv_kernels.h"
 
 #include <cfloat>
+#include <cmath>
 
 namespace sv {
 namespace {
@@ -130,9 +131,11 @@ struct RadixShared {
 
 // MSD radix select over one whole row by one workgroup of NT lanes, re-reading the
 // scores in every pass; wavefront w owns the contiguous range [w*seg, (w+1)*seg).
+// `map` (or nullptr) renames position j to map[j] on output; it must ascend with j.
 template <int NT>
 __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* __restrict__ s,
-                                                 int32_t* __restrict__ out, int n, int kb, int tid, int lane, int wave) {
+                                                 int32_t* __restrict__ out, int n, int kb, int tid, int lane, int wave,
+                                                 const int32_t* map = nullptr) {
     constexpr int NW = NT / kWave;
     const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
     const int seg_items = seg / kWave;
@@ -188,7 +191,10 @@ __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* _
         const bool keep = (key != 0u && kp > prefix) || (is_eq && eq_rank < need);
         const uint64_t keep_ballot = __ballot(keep);
         const uint32_t slot = pos + (uint32_t)__popcll(keep_ballot & lane_lt);
-        if (keep && slot < (uint32_t)kb) out[slot] = j0 + i * kWave;   // slot < kb holds for finite scores
+        if (keep && slot < (uint32_t)kb) {   // slot < kb holds for finite scores
+            const int j = j0 + i * kWave;
+            out[slot] = map ? map[j] : j;
+        }
         pos += (uint32_t)__popcll(keep_ballot);
         eq_seen += (uint32_t)__popcll(eq_ballot);
     }
@@ -237,20 +243,14 @@ struct SingleShared {
     int32_t thr_idx;
 };
 
+// Exact top-kb of the n <= ITEMS*1024 scores at s (global or LDS) by one 1024-lane workgroup,
+// scores in registers; out[0..kb) receives the kept positions (renamed through `map` when given)
+// in ascending order.  Requires 0 < kb < n.
 template <int ITEMS>
-__global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const SelectArgs a) {
+__device__ __forceinline__ void select_block(SingleShared& sh, const float* __restrict__ s, int32_t* __restrict__ out,
+                                             int n, int kb, int tid, int lane, int wave,
+                                             const int32_t* map = nullptr) {
     constexpr int NT = kSingleThreads, NW = NT / kWave;
-    __shared__ SingleShared sh;
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    const int64_t unit = (int64_t)b * a.Hkv + g;
-    const float* __restrict__ s = a.scores + unit * a.n_vis_max;
-    int32_t* __restrict__ out = a.idx + unit * a.k;
-    const int n = live_rows(a.vis_len, b, a.n_vis_max);
-    const int kb = a.k < n ? a.k : n;
-    if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
-
     const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
     const int j0 = wave * seg + lane;
     const int range_end = min(n, wave * seg + seg);
@@ -326,7 +326,10 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
                 const bool keep = (keep_bits >> i) & 1u;
                 const uint64_t ballot = __ballot(keep);
                 const uint32_t slot = pos + (uint32_t)__popcll(ballot & lane_lt);
-                if (keep && slot < (uint32_t)kb) out[slot] = j0 + i * kWave;
+                if (keep && slot < (uint32_t)kb) {
+                    const int j = j0 + i * kWave;
+                    out[slot] = map ? map[j] : j;
+                }
                 pos += (uint32_t)__popcll(ballot);
             }
             done = true;
@@ -334,8 +337,118 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
     }
     if (!done) {   // block-uniform
         __syncthreads();
-        radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave);
+        radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave, map);
     }
+}
+
+__global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const SelectArgs a) {
+    __shared__ SingleShared sh;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (emit_trivial<kSingleThreads>(a, unit, n, kb, 0, 1, tid)) return;
+    select_block<kSingleMaxN / kSingleThreads>(sh, a.scores + unit * a.n_vis_max, a.idx + unit * a.k, n, kb, tid,
+                                               lane, wave);
+}
+
+// ------------------------------------------------------------------ candidate-filtered shape
+// One workgroup per (b, g).  The scoring kernel left, per tile of the row, a 512-byte record
+// {count; the first 62 (score, row) pairs >= t_lo in row order}; the records of a row are one
+// contiguous block, fetched in a single trip through memory (a second one brings the overflow of
+// the few fuller tiles).  Prefix sums of the counts pack the candidates, still in row order, in
+// LDS; then the same on-chip selection as for a short row runs on them, positions renamed to the
+// original rows.  If fewer than k_b candidates exist (t_lo was too high) or more than fit, the
+// workgroup selects from the full score row.
+constexpr int kFiltCap = 8192;                       // candidates ranked on chip
+constexpr int kFiltItems = kFiltCap / kSingleThreads;
+constexpr int kFiltMaxTiles = 256;
+constexpr int kFiltPrimary = kFilterRecordPairs;     // pairs in a primary record
+constexpr int kFiltRec16 = kFiltPrimary / 2 + 1;     // 16-byte words per primary record
+constexpr int kFiltLoads = kFiltMaxTiles * kFiltRec16 / kSingleThreads;
+
+struct FilteredShared {
+    SingleShared sel;
+    float c_score[kFiltCap];
+    int32_t c_row[kFiltCap];
+    uint32_t tile_cnt[kFiltMaxTiles];
+    uint32_t tile_off[kFiltMaxTiles + 1];   // exclusive prefix sums of the tile counts
+    uint32_t wave_tot[16];
+};
+
+__global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const SelectArgs a, const FilterArgs f) {
+    constexpr int NT = kSingleThreads;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    FilteredShared& sh = *reinterpret_cast<FilteredShared*>(smem_raw);
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
+    int32_t* __restrict__ out = a.idx + unit * a.k;
+
+    const int live_tiles = (n + f.tile_rows - 1) / f.tile_rows;   // <= kFiltMaxTiles (checked by the host)
+    const uint4* recs = f.tiles + unit * f.n_tiles * kFiltRec16;
+    const uint2* ovf = f.overflow + unit * f.n_tiles * f.tile_rows;
+    // one trip: word (tid + u*NT) of the row's block of records
+    uint4 word[kFiltLoads];
+#pragma unroll
+    for (int u = 0; u < kFiltLoads; ++u) {
+        const int w = tid + u * NT;
+        word[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (w < live_tiles * kFiltRec16) word[u] = recs[w];
+    }
+#pragma unroll
+    for (int u = 0; u < kFiltLoads; ++u) {
+        const int w = tid + u * NT;
+        if (w % kFiltRec16 == 0 && w < kFiltMaxTiles * kFiltRec16)
+            sh.tile_cnt[w / kFiltRec16] = w < live_tiles * kFiltRec16 ? min(word[u].x, (uint32_t)f.tile_rows) : 0u;
+    }
+    __syncthreads();
+    const uint32_t my_count = tid < kFiltMaxTiles ? sh.tile_cnt[tid] : 0u;
+    const uint32_t incl = block_inclusive_scan<NT>(my_count, sh.wave_tot, lane, wave);
+    if (tid < kFiltMaxTiles) sh.tile_off[tid] = incl - my_count;
+    if (tid == NT - 1) sh.tile_off[kFiltMaxTiles] = incl;
+    __syncthreads();
+    const uint32_t m = sh.tile_off[kFiltMaxTiles];   // candidates of the row
+
+    if (m < (uint32_t)kb || m > (uint32_t)kFiltCap) {   // block-uniform: the filter missed, take the whole row
+        radix_select_row<NT>(sh.sel.rx, a.scores + unit * a.n_vis_max, out, n, kb, tid, lane, wave);
+        return;
+    }
+#pragma unroll
+    for (int u = 0; u < kFiltLoads; ++u) {
+        const int w = tid + u * NT;
+        const int tile = w / kFiltRec16, q = w % kFiltRec16;
+        if (tile < live_tiles && q > 0) {
+            const uint32_t off = sh.tile_off[tile], cnt = sh.tile_cnt[tile];
+            const uint32_t e = 2 * (q - 1);
+            if (e < cnt) {
+                sh.c_score[off + e] = __uint_as_float(word[u].x);
+                sh.c_row[off + e] = (int32_t)word[u].y;
+            }
+            if (e + 1 < cnt) {
+                sh.c_score[off + e + 1] = __uint_as_float(word[u].z);
+                sh.c_row[off + e + 1] = (int32_t)word[u].w;
+            }
+            // the rare fuller tile: its remaining pairs from the overflow rows
+            for (uint32_t x = kFiltPrimary + (q - 1); x < cnt; x += kFiltRec16 - 1) {
+                const uint2 v = ovf[(int64_t)tile * f.tile_rows + x];
+                sh.c_score[off + x] = __uint_as_float(v.x);
+                sh.c_row[off + x] = (int32_t)v.y;
+            }
+        }
+    }
+    __syncthreads();
+    if (m == (uint32_t)kb) {   // every candidate is kept
+        for (uint32_t i = tid; i < m; i += NT) out[i] = sh.c_row[i];
+        return;
+    }
+    select_block<kFiltItems>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row);
 }
 
 // ------------------------------------------------------------------ multi-part shape
@@ -674,6 +787,68 @@ WsLayout layout_select_ws(size_t units, int parts) {
 
 }  // namespace
 
+namespace {
+struct FilterLayout { size_t t_lo, tiles, overflow, total; };
+
+// Sized for the smallest tile the scoring kernel can be asked for, so that the layout does not
+// depend on the launch-shape knobs.
+FilterLayout layout_filter_ws(int dtype, int D, size_t units, int n_vis_max) {
+    FilterLayout l{};
+    const int granule = score_row_granule(dtype, D);
+    const size_t max_tiles = (size_t)(n_vis_max + granule - 1) / granule;
+    size_t off = 0;
+    l.t_lo = off; off += align256(units * sizeof(float));
+    l.tiles = off; off += align256(units * max_tiles * kFiltRec16 * sizeof(uint4));
+    l.overflow = off; off += align256(units * ((size_t)n_vis_max + 512) * sizeof(uint2));
+    l.total = off;
+    return l;
+}
+}  // namespace
+
+// Long rows whose expected candidate count (the sample-rank fraction of the row, plus four standard
+// deviations of that fraction) fits the on-chip ranking.
+bool filtered_select_applies(int dtype, int D, int n_vis_max, int k) {
+    if (n_vis_max <= kSingleMaxN || k <= 0 || k >= n_vis_max) return false;
+    if (filter_tile_rows(dtype, D, 0, n_vis_max, kFiltMaxTiles) == 0) return false;
+    const double S = presample_rows();
+    const double mean = S * (double)k / (double)n_vis_max;
+    const double frac = (mean + 5.0 * std::sqrt(mean) + 4.0) / S;
+    if (frac >= 0.5) return false;
+    const double expect = frac * n_vis_max;
+    const double sigma = n_vis_max * std::sqrt(frac * (1.0 - frac) / S);
+    return expect + 4.0 * sigma <= (double)kFiltCap;
+}
+
+size_t filtered_workspace_bytes(int dtype, int D, int B, int Hkv, int n_vis_max) {
+    return layout_filter_ws(dtype, D, (size_t)B * Hkv, n_vis_max).total;
+}
+
+FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, int n_vis_max, int k,
+                                  int requested_tile_rows) {
+    const FilterLayout l = layout_filter_ws(dtype, D, (size_t)B * Hkv, n_vis_max);
+    char* p = static_cast<char*>(base);
+    FilterArgs f{};
+    f.t_lo = reinterpret_cast<float*>(p + l.t_lo);
+    f.tiles = reinterpret_cast<uint4*>(p + l.tiles);
+    f.overflow = reinterpret_cast<uint2*>(p + l.overflow);
+    f.tile_rows = filter_tile_rows(dtype, D, requested_tile_rows, n_vis_max, kFiltMaxTiles);
+    f.n_tiles = (n_vis_max + f.tile_rows - 1) / f.tile_rows;
+    f.k = k;
+    f.rank_override = 0;
+    return f;
+}
+
+hipError_t launch_select_filtered(const SelectArgs& a, const FilterArgs& f, hipStream_t stream) {
+    if (a.B == 0 || a.Hkv == 0) return hipSuccess;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_filtered_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)sizeof(FilteredShared));
+    if (attr != hipSuccess) return attr;
+    dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
+    hipLaunchKernelGGL(select_filtered_kernel, grid, block, sizeof(FilteredShared), stream, a, f);
+    return hipGetLastError();
+}
+
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max) {
     const SelectPlan p = plan_select(n_vis_max);
     if (p.single) return 0;
@@ -685,7 +860,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t stream) {
     const SelectPlan p = plan_select(a.n_vis_max);
     if (p.single) {
         dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
-        hipLaunchKernelGGL((select_single_kernel<4>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL(select_single_kernel, grid, block, 0, stream, a);
         return hipGetLastError();
     }
     const WsLayout l = layout_select_ws((size_t)a.B * a.Hkv, p.parts);

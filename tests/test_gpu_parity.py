@@ -177,6 +177,58 @@ def test_select_is_bit_exact_on_given_scores(n, k):
             assert np.array_equal(got[b, g], want_idx[b, g]), (b, g)
 
 
+# ------------------------------------------------------------------ candidate-filtered selection of sv_decode_step
+def _exact_sets(r, k, vis_len):
+    want_idx, want_cnt = oracle.topk_select(r["scores"].astype(np.float64), k, vis_len)
+    return np.array_equal(r["count"], want_cnt) and np.array_equal(r["idx"], want_idx)
+
+
+@pytest.mark.parametrize("dtype,D,G,Nv,k", [(np.float16, 128, 7, 20000, 1000), (np.float16, 64, 2, 9001, 450),
+                                           (np.float32, 128, 1, 6000, 300), (np.float32, 64, 4, 12345, 100)])
+def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
+    """Long rows inside sv_decode_step: the sampled threshold + candidate slots + on-chip ranking must
+    give exactly the set a full sort of the GPU's own scores gives -- with the filter on, with the
+    filter off, when the threshold is forced too high (too few candidates: whole-row fallback), for
+    ragged and empty rows, and for every tiling of the scoring kernel."""
+    import paper_2510_17777_amd as sv
+    Hkv, B = 2, 3
+    inp = rand_inputs(31 + D + G, B, Hkv * G, Hkv, D, Nv, 40, dtype)
+    inp["k_vis"][1, 0, Nv // 2:] = inp["k_vis"][1, 0, :Nv - Nv // 2]       # every score twice: ties at the cut
+    inp["k_vis"][1, 1, :] = np.round(inp["k_vis"][1, 1, :])                 # coarse keys: many equal scores
+    vis_len = np.array([Nv, Nv - 13, Nv // 3], np.int32)
+    base = None
+    try:
+        for filt, rank, rows in [(1, 0, 0), (0, 0, 0), (1, 1, 0), (1, 440, 0), (1, 0, 128), (1, 0, 1024)]:
+            sv.sv_set_tuning("select_filter", filt)
+            sv.sv_set_tuning("filter_rank", rank)
+            sv.sv_set_tuning("score_rows_per_block", rows)
+            r = run_step(inp, k, vis_len=vis_len, dev=None if base is None else base["dev"])
+            assert _exact_sets(r, k, vis_len), (filt, rank, rows)
+            if base is None:
+                base = r
+            else:
+                for key in ("scores", "idx", "count", "out", "lse"):
+                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows)
+    finally:
+        sv.sv_set_tuning("select_filter", -1)
+        sv.sv_set_tuning("filter_rank", 0)
+        sv.sv_set_tuning("score_rows_per_block", 0)
+    assert_step_matches(inp, k, vis_len=vis_len, label="filtered")
+
+
+def test_filtered_selection_degenerate_rows():
+    """All keys equal (every row is a candidate: more than fit on chip -> whole-row fallback), rows
+    shorter than k, shorter than the sample, and empty rows, on a shape that takes the filtered path."""
+    Nv, k = 9000, 500
+    inp = rand_inputs(41, 5, 4, 2, 128, Nv, 8, np.float16)
+    inp["k_vis"][0] = inp["k_vis"][0, :, :1]
+    vis_len = np.array([Nv, 0, 1, 300, 700], np.int32)
+    r = run_step(inp, k, vis_len=vis_len)
+    assert _exact_sets(r, k, vis_len)
+    assert np.array_equal(r["idx"][0, 0], np.arange(k))
+    assert_step_matches(inp, k, vis_len=vis_len, label="filtered degenerate")
+
+
 # ------------------------------------------------------------------ edge cases
 def test_k_zero_text_only_and_no_text_visual_only():
     inp = rand_inputs(21, 2, 8, 2, 128, 300, 40, np.float16)
