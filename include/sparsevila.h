@@ -175,6 +175,8 @@ const char *sv_strerror(sv_status status);
  *   "filter_rank"           which order statistic of the 512-row sample is that threshold, 1..448; 0 = derived
  *                           from k / vis_len.  Any value gives the same result (a threshold that admits too
  *                           few or too many candidates makes the row fall back to the full selection)
+ *   "filter_test_mode"      0; 1 / 2 make every third tile of the scoring kernel ignore the threshold and hand
+ *                           over none / all of its scores (tests of the selection's consistency check)
  * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
  * Process-wide; not thread-safe against concurrent calls.  Results never depend on
  * the knobs beyond fp32 summation order in step 3.

@@ -3,6 +3,7 @@
 // kernel stages.  See include/sparsevila.h for the contract of every entry point.
 #include "../../include/sparsevila.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -22,8 +23,10 @@ struct Tuning {
     int32_t attn_mfma = -1;             // -1 = default
     int32_t select_filter = -1;         // -1 = default
     int32_t filter_rank = 0;            // 0 = derived from k / n
+    int32_t filter_test_mode = 0;
 };
 Tuning g_tuning;
+std::atomic<uint32_t> g_epoch{0x5eed0001u};   // tags the threshold words of one sv_decode_step call
 
 constexpr int kDefaultScoreRows = 256;
 constexpr int kDefaultAttnChunk = 128;
@@ -254,15 +257,14 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
         sv::ScoreArgs sa = make_score_args(s, q, k_vis, sc);
         const bool filter = w.filt_bytes > 0 &&
                             (g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter) != 0;
-        hipError_t e;
         if (filter) {   // long rows: sample a threshold, let the scoring kernel emit the candidates above it
             sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, s->dtype, s->head_dim,
                                                  s->batch, s->n_kv_heads, s->n_vis_max, s->k, sa.rows_per_block);
             sa.filt.rank_override = g_tuning.filter_rank;
-            e = sv::launch_presample(sa, hs);
-            if (e != hipSuccess) return SV_ERR_LAUNCH;
+            sa.filt.test_mode = g_tuning.filter_test_mode;
+            sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
         }
-        e = sv::launch_score(sa, hs);
+        hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
         const sv::SelectArgs sel = make_select_args(s, w, workspace, sc, idx, count);
         e = filter ? sv::launch_select_filtered(sel, sa.filt, hs) : sv::launch_select(sel, hs);
@@ -327,6 +329,11 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.filter_rank = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "filter_test_mode")) {
+        if (value < 0 || value > 2) return SV_ERR_SHAPE;
+        g_tuning.filter_test_mode = value;
+        return SV_OK;
+    }
     return SV_ERR_SHAPE;
 }
 
@@ -341,6 +348,7 @@ int32_t sv_get_tuning(const char* name) {
     if (!std::strcmp(name, "select_filter"))
         return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
     if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;
+    if (!std::strcmp(name, "filter_test_mode")) return g_tuning.filter_test_mode;
     return -1;
 }
 

@@ -6,24 +6,28 @@
 
 namespace sv {
 
-// Candidate filter of sv_decode_step for long rows.  A threshold t_lo per (b, g), an order statistic
-// of the scores of a small sample of the row, lies below the k-th largest score with overwhelming
-// probability.  Every scoring workgroup stores the (score bits, row) pairs of its tile with
-// score >= t_lo, in row order: a 512-byte primary record per tile ({count,0,0,0}, then the first 62
-// pairs; records of consecutive tiles are adjacent) and, for fuller tiles, pair number f >= 62 at
-// position f of the tile's overflow rows.  The selection ranks those few candidates on chip.  The
-// outcome is checked on the device (at least k candidates, no more than fit); a row that fails is
-// selected from all its scores.
+// Candidate filter of sv_decode_step for long rows.  Sampler workgroups at the head of the scoring
+// launch publish, per (b, g), a threshold t_lo (an order statistic of the scores of a small sample
+// of the row) that lies below the k-th largest score with overwhelming probability.  Every scoring
+// workgroup stores the (score bits, row) pairs of its tile with score >= t_lo, in row order: a
+// 512-byte primary record per tile ({count, t_lo used, 0, 0}, then the first 62 pairs; records of
+// consecutive tiles are adjacent) and, for fuller tiles, pair number f >= 62 at position f of the
+// tile's overflow rows.  The selection ranks those few candidates on chip.  t_lo is only a hint:
+// the selection checks on the device that the candidates determine the kept set (at least k of them
+// at or above the largest t_lo any tile used, and no more than fit); a row that fails is selected
+// from all its scores.
 constexpr int kFilterRecordPairs = 62;   // pairs in a primary record: 16-byte header + 62 * 8 bytes = 512 bytes
 
 struct FilterArgs {
-    float* t_lo;            // [units]
+    uint64_t* hint;         // [units]  {epoch << 32 | t_lo bits}, written by the samplers
     uint4* tiles;           // [units][n_tiles][32]
     uint2* overflow;        // [units][n_tiles][tile_rows]
     int32_t n_tiles;        // ceil(n_vis_max / tile_rows)
     int32_t tile_rows;      // rows per scoring workgroup while the filter is on
     int32_t k;
     int32_t rank_override;  // > 0: use this sample rank for t_lo (tests force the fallbacks with it)
+    uint32_t epoch;         // differs from call to call: marks the hint words of this call
+    int32_t test_mode;      // 0; tests: every third tile ignores the hint (1: keeps nothing, 2: keeps all)
 };
 
 struct ScoreArgs {
@@ -85,7 +89,6 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
 // Tile rows the filter will use: `requested` rounded to the scoring kernel's granule, at most 512, raised
 // until the row has at most max_tiles tiles; 0 if that is impossible.
 int filter_tile_rows(int dtype, int D, int requested, int n_vis_max, int max_tiles);
-hipError_t launch_presample(const ScoreArgs& a, hipStream_t stream);   // writes filt.t_lo
 int presample_rows();                                                  // rows sampled per (b, g)
 hipError_t launch_select_filtered(const SelectArgs& a, const FilterArgs& f, hipStream_t stream);
 

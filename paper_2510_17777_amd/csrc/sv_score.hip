@@ -10,16 +10,25 @@
 // consecutive memory; eight such loads are issued before the first is consumed.
 // Lanes of one row are reduced with DPP inside a 16-lane row.
 //
-// Inside sv_decode_step the kernel also feeds the selection: a presample kernel scores a
-// jittered, stratified sample of each row and takes an order statistic of it as t_lo, a
-// value that lies below the k-th largest score of the row except with negligible
-// probability; the scoring kernel then stores every (score, row) >= t_lo in the slot of
-// the wavefront pass that produced it (LDS); after its last pass the workgroup's first
-// wavefront packs the tile's candidates, in row order, into the tile's record in memory
-// with (usually) one store instruction.  No atomics.  The selection ranks those few
-// candidates instead of re-reading every score.  Measured on the long-video shape: the
-// emission inside the loop is free, the barrier and the record store cost about 5 % of
-// the kernel; thousands of small scattered stores straight from the passes cost 8 %.
+// Inside sv_decode_step the same launch also feeds the selection (kFilter):
+//   * the first `units` workgroups of the (linear) grid are SAMPLERS, one per (b, g): each
+//     scores a jittered, stratified sample of 512 rows of its row and publishes an order
+//     statistic of those scores as t_lo -- a value below the k-th largest score of the
+//     row except with negligible probability -- as one 8-byte word {epoch, t_lo};
+//   * every other workgroup scores one TILE of a row as usual, keeps the tile's scores
+//     in LDS, and after its last pass its first wavefront reads t_lo and writes the
+//     tile's (score, row) pairs >= t_lo, in row order, to the tile's record, together
+//     with the t_lo it used, as one store of whole 128-byte lines.
+// t_lo is a hint, not a dependency: whatever value a tile uses, the selection verifies
+// on the device that the candidates it received determine the kept set, and otherwise
+// selects from all scores of the row.  So a tile may read t_lo without any ordering
+// guarantee; it polls the word a bounded number of times (samplers are dispatched first
+// and a tile needs the value only after streaming its rows, so in practice the first
+// read succeeds) and falls back to "every row is a candidate" if the word never shows
+// the call's epoch.  A separate sampler launch in front of the scoring launch cost
+// 13 us on the long-video shape, of which 4.5 us is the price of any kernel boundary.
+// The record store by one wavefront after a barrier costs about 5 % of the kernel;
+// small scattered stores straight from the passes cost 8 %.
 #include "sv_device.h"
 #include "sv_kernels.h"
 
@@ -28,11 +37,139 @@ namespace {
 
 constexpr int kScoreUnroll = 8;   // independent row loads in flight per lane
 constexpr int kScoreWaves = 4;    // wavefronts per workgroup
+constexpr int kScoreThreads = kScoreWaves * kWave;
 constexpr int kFilterMaxTileRows = 512;   // rows of one scoring workgroup when it emits candidates
 constexpr int kFilterPrimary = kFilterRecordPairs;
+constexpr int kSample = 512;              // sampled rows per (b, g)
+constexpr int kHintPolls = 64;            // bounded wait for t_lo
 
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {   // integer finaliser, for the sample jitter
+    x ^= x >> 16; x *= 0x7feb352du;
+    x ^= x >> 15; x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// Sample rank whose score serves as t_lo: with p = kb/n the number of sampled rows among the
+// row's true top kb is about Binomial(S, p) (less spread, since the sample is stratified);
+// t_lo exceeds the kb-th largest score only if that number reaches the rank.
+__device__ __forceinline__ int sample_rank(int n, int kb) {
+    const float m = (float)kSample * (float)kb / (float)n;
+    return (int)ceilf(m + 5.f * sqrtf(m) + 4.f);
+}
+
+__device__ __forceinline__ int live_rows_of(const ScoreArgs& a, int b) {
+    int n = a.n_vis_max;
+    if (a.vis_len) {
+        const int v = a.vis_len[b];
+        n = v < 0 ? 0 : (v < n ? v : n);
+    }
+    return n;
+}
+
+// Summed query of group g, the EPL dims of chunk c.
+template <typename T>
+__device__ __forceinline__ void summed_query(const ScoreArgs& a, int b, int g, int c, float (&qs)[Chunk<T>::kElems]) {
+    constexpr int EPL = Chunk<T>::kElems;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qs[i] = 0.f;
+    const T* qp = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)g * a.G * a.q_sh + c * EPL;
+    for (int h = 0; h < a.G; ++h) {
+        const Chunk<T> qc = load_chunk(qp + (int64_t)h * a.q_sh);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) qs[i] += qc.at(i);
+    }
+}
+
+__device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, float t_lo) {
+    const uint64_t word = ((uint64_t)a.filt.epoch << 32) | (uint64_t)__float_as_uint(t_lo);
+    __hip_atomic_store(a.filt.hint + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Sampler workgroup of one (b, g): 512 sample scores -> t_lo.
+template <typename T, int D>
+__device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int g, float* samp, uint32_t* s_probe) {
+    constexpr int EPL = Chunk<T>::kElems;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = kWave / LPR;
+    constexpr int U = kScoreUnroll / 2;                 // fewer loads in flight than the streaming loop: the
+                                                        // sampler must fit the register budget of that loop
+    constexpr int ROUND_ROWS = kScoreWaves * U * RPW;   // samples per round of loads
+    constexpr int ROUNDS = kSample / ROUND_ROWS;
+    static_assert(ROUNDS >= 1 && ROUNDS * ROUND_ROWS == kSample, "sample must divide over the workgroup");
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int c = lane % LPR, grp = lane / LPR;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const int n = live_rows_of(a, b);
+    const int kb = a.filt.k < n ? a.filt.k : n;
+    if (kb == 0 || kb == n) {   // the selection handles these rows without candidates
+        if (tid == 0) publish_hint(a, unit, INFINITY);
+        return;
+    }
+    const int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb);
+    if (rank > kSample - kSample / 8) {   // the sample cannot separate the top kb: every row is a candidate
+        if (tid == 0) publish_hint(a, unit, -INFINITY);
+        return;
+    }
+    float qs[EPL];
+    summed_query<T>(a, b, g, c, qs);
+    const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
+    const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
+    for (int r = 0; r < ROUNDS; ++r) {
+        Chunk<T> kc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = r * ROUND_ROWS + (wave * U + u) * RPW + grp;   // sample number
+            int row = (int)(((int64_t)i * n) / kSample);
+            if (stratum > 1) row += (int)(mix32((uint32_t)unit * 0x9E3779B9u + (uint32_t)i) % (uint32_t)stratum);
+            row = row < n ? row : n - 1;
+            kc[u] = load_chunk(kbase + (int64_t)row * a.k_sn);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) s = fmaf(kc[u].at(i), qs[i], s);
+            s = group_sum<LPR>(s) * a.scale;
+            if (c == 0) samp[r * ROUND_ROWS + (wave * U + u) * RPW + grp] = s;
+        }
+    }
+    __syncthreads();
+    // The rank-th largest sample, four bits of its order-preserving key per round: every
+    // wavefront holds all keys (kSample/64 per lane) and counts the keys >= four of the
+    // fifteen probes; the digit is the number of probes that still have `rank` keys.
+    constexpr int KPL = kSample / kWave;
+    uint32_t keys[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) keys[i] = score_key(samp[lane + i * kWave]);
+    uint32_t prefix = 0;
+    for (int round = 0; round < 8; ++round) {
+        const int shift = 28 - 4 * round;
+        uint32_t* probe_cnt = s_probe + (round & 1) * 16;
+        for (int d = wave + 1; d < 16; d += kScoreWaves) {
+            const uint32_t probe = prefix | ((uint32_t)d << shift);
+            int cnt = 0;
+#pragma unroll
+            for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
+            if (lane == 0) probe_cnt[d] = (uint32_t)cnt;
+        }
+        __syncthreads();
+        uint32_t digit = 0;
+#pragma unroll
+        for (int d = 1; d < 16; ++d) digit += probe_cnt[d] >= (uint32_t)rank ? 1u : 0u;
+        prefix |= digit << shift;
+    }
+    if (tid == 0) {
+        const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
+        publish_hint(a, unit, __uint_as_float(u));
+    }
+}
+
+// Eight wavefronts per SIMD (at most 64 VGPRs) is what the streaming loop is tuned for; the sampler
+// role must not raise the register count of the whole kernel.
 template <typename T, int D, bool kStream, bool kFilter>
-__global__ __launch_bounds__(kScoreWaves * kWave) void score_kernel(const ScoreArgs a) {
+__global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void score_kernel(const ScoreArgs a) {
     constexpr int EPL = Chunk<T>::kElems;   // elements per lane
     constexpr int LPR = D / EPL;            // lanes per row
     constexpr int RPW = kWave / LPR;        // rows per wavefront load
@@ -40,49 +177,47 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void score_kernel(const ScoreA
     constexpr int WAVE_ROWS = RPW * U;
     constexpr int BLOCK_ROWS = kScoreWaves * WAVE_ROWS;
     static_assert(U <= LPR, "store lane selection needs U <= lanes per row");
+    // kFilter: the tile's scores (tile role) or the sample scores (sampler role)
+    __shared__ float s_val[kFilter ? kFilterMaxTileRows : 1];
+    __shared__ uint32_t s_probe[kFilter ? 32 : 1];
+    __shared__ uint2 s_pair[kFilter ? kFilterMaxTileRows : 1];
 
-    const int b = blockIdx.z, g = blockIdx.y;
+    int b, g, tile;
+    if (kFilter) {   // linear grid: samplers first, then the tiles of unit 0, unit 1, ...
+        const int units = a.B * a.Hkv;
+        int id = (int)blockIdx.x;
+        if (id < units) {
+            sample_threshold<T, D>(a, id / a.Hkv, id % a.Hkv, s_val, s_probe);
+            return;
+        }
+        id -= units;
+        const int unit = id / a.filt.n_tiles;
+        tile = id - unit * a.filt.n_tiles;
+        b = unit / a.Hkv;
+        g = unit - b * a.Hkv;
+    } else {
+        b = blockIdx.z; g = blockIdx.y; tile = blockIdx.x;
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int c = lane % LPR;     // chunk of the row this lane owns
     const int grp = lane / LPR;   // which of the RPW rows of a load
 
-    int n = a.n_vis_max;
-    if (a.vis_len) {
-        const int v = a.vis_len[b];
-        n = v < 0 ? 0 : (v < n ? v : n);
-    }
-    const int row_begin = blockIdx.x * a.rows_per_block;
+    const int n = live_rows_of(a, b);
+    const int row_begin = tile * a.rows_per_block;
     const int row_end = min(row_begin + a.rows_per_block, a.n_vis_max);
     const int64_t unit = (int64_t)b * a.Hkv + g;
     float* __restrict__ srow = a.scores + unit * a.n_vis_max;
-    // Candidate filter: every wavefront pass owns a slot of WAVE_ROWS entries in LDS.
-    __shared__ uint2 s_ent[kFilter ? kFilterMaxTileRows : 1];
-    __shared__ uint32_t s_cnt[kFilter ? kFilterMaxTileRows / WAVE_ROWS : 1];
-    float t_lo = INFINITY;
-    uint64_t rows_before = 0;   // lanes whose stored row precedes this lane's: lane (grp, c) stores row c*RPW + grp
-    if (kFilter) {
-        t_lo = a.filt.t_lo[unit];
-        for (int gp = 0; gp < RPW; ++gp) {
-            rows_before |= ((1ull << c) - 1ull) << (gp * LPR);
-            if (gp < grp) rows_before |= 1ull << (gp * LPR + c);
-        }
-        if (lane == 0)
-            for (int sl = wave; sl < a.rows_per_block / WAVE_ROWS; sl += kScoreWaves) s_cnt[sl] = 0;
-    }
 
-    // Summed query of the group, this lane's EPL dims.
+    // The row's threshold word is requested up front: all but the first tiles of the launch find it
+    // ready, and the request rides along with the first loads instead of delaying the tile's end.
+    uint64_t hint_word = 0;
+    if (kFilter) hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
     float qs[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qs[i] = 0.f;
-    if (row_begin < n) {
-        const T* qp = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)g * a.G * a.q_sh + c * EPL;
-        for (int h = 0; h < a.G; ++h) {
-            const Chunk<T> qc = load_chunk(qp + (int64_t)h * a.q_sh);
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) qs[i] += qc.at(i);
-        }
-    }
+    if (row_begin < n) summed_query<T>(a, b, g, c, qs);
 
     const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
 
@@ -115,156 +250,59 @@ __global__ __launch_bounds__(kScoreWaves * kWave) void score_kernel(const ScoreA
 #pragma unroll
         for (int u = 1; u < U; ++u) o = (c == u) ? acc[u] : o;
         const int row = r0 + c * RPW + grp;
-        const float val = o * a.scale;
-        if (c < U && row < row_end) srow[row] = row < n ? val : -INFINITY;
-        if (kFilter) {
-            const bool is_cand = c < U && row < row_end && row < n && val >= t_lo;
-            const uint64_t cand_lanes = __ballot(is_cand);
-            const int slot = (r0 - row_begin) / WAVE_ROWS;
-            if (is_cand)
-                s_ent[slot * WAVE_ROWS + __popcll(cand_lanes & rows_before)] =
-                    make_uint2(__float_as_uint(val), (uint32_t)row);
-            if (lane == 0) s_cnt[slot] = (uint32_t)__popcll(cand_lanes);
+        const float val = row < n ? o * a.scale : -INFINITY;
+        if (c < U && row < row_end) {
+            srow[row] = val;
+            if (kFilter) s_val[row - row_begin] = val;
         }
     }
     if (kFilter) {
         __syncthreads();
         if (wave != 0) return;
-        // Record of this tile, 8-byte items: {count, 0}, {0, 0}, then the first kFilterPrimary entries;
-        // records of consecutive tiles are adjacent.  Entries beyond that go to the tile's overflow rows.
-        const int64_t tile = unit * a.filt.n_tiles + blockIdx.x;
-        uint2* rec = reinterpret_cast<uint2*>(a.filt.tiles) + tile * (kFilterPrimary + 2);
-        uint2* ovf = a.filt.overflow + tile * a.rows_per_block;
-        const int n_slots = a.rows_per_block / WAVE_ROWS;
-        uint32_t total = 0;
-        for (int sl = 0; sl < n_slots; ++sl) total += s_cnt[sl];
-        for (uint32_t item = lane; item < total + 2; item += kWave) {
-            uint2 v = make_uint2(item == 0 ? total : 0u, 0u);
-            if (item >= 2) {
-                uint32_t f = item - 2, base = 0;   // the f-th candidate of the tile: find its slot
-                int sl = 0;
-                for (; sl < n_slots - 1; ++sl) {
-                    const uint32_t cs = s_cnt[sl];
-                    if (f < base + cs) break;
-                    base += cs;
-                }
-                v = s_ent[sl * WAVE_ROWS + (f - base)];
+        // t_lo of the row: the sampler's word, once it carries this call's epoch
+        float t_lo = -INFINITY;
+        for (int poll = 0; poll < kHintPolls; ++poll) {
+            if ((uint32_t)(hint_word >> 32) == a.filt.epoch) {
+                t_lo = __uint_as_float((uint32_t)hint_word);
+                if (t_lo != t_lo) t_lo = -INFINITY;   // a stale word that happens to carry the epoch
+                break;
             }
-            if (item < kFilterPrimary + 2) rec[item] = v;
-            else ovf[item - 2] = v;
+            __builtin_amdgcn_s_sleep(32);
+            hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-    }
-}
-
-// ---------------------------------------------------------------- presample: t_lo per (b, g)
-constexpr int kSample = 512;          // sampled rows per (b, g)
-constexpr int kSampleThreads = 1024;
-
-__device__ __forceinline__ uint32_t mix32(uint32_t x) {   // integer finaliser, for the sample jitter
-    x ^= x >> 16; x *= 0x7feb352du;
-    x ^= x >> 15; x *= 0x846ca68bu;
-    x ^= x >> 16;
-    return x;
-}
-
-// Sample rank whose score serves as t_lo: with p = kb/n the number of sampled rows among the
-// row's true top kb is about Binomial(S, p) (less spread, since the sample is stratified);
-// t_lo exceeds the kb-th largest score only if that number reaches the rank.
-__device__ __forceinline__ int sample_rank(int n, int kb) {
-    const float m = (float)kSample * (float)kb / (float)n;
-    return (int)ceilf(m + 5.f * sqrtf(m) + 4.f);
-}
-
-template <typename T, int D>
-__global__ __launch_bounds__(kSampleThreads) void presample_kernel(const ScoreArgs a) {
-    constexpr int EPL = Chunk<T>::kElems;
-    constexpr int LPR = D / EPL;
-    constexpr int RPW = kWave / LPR;
-    constexpr int NW = kSampleThreads / kWave;
-    constexpr int LOADS = kSample / (NW * RPW);
-    static_assert(LOADS >= 1 && LOADS * NW * RPW == kSample, "sample must divide over the workgroup");
-    __shared__ float samp[kSample];
-
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int c = lane % LPR, grp = lane / LPR;
-    const int64_t unit = (int64_t)b * a.Hkv + g;
-    int n = a.n_vis_max;
-    if (a.vis_len) {
-        const int v = a.vis_len[b];
-        n = v < 0 ? 0 : (v < n ? v : n);
-    }
-    const int kb = a.filt.k < n ? a.filt.k : n;
-    if (kb == 0 || kb == n) {   // the selection handles these without candidates
-        if (tid == 0) a.filt.t_lo[unit] = INFINITY;
-        return;
-    }
-    int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb);
-    if (rank > kSample - kSample / 8) {   // the sample cannot separate the top kb: every row is a candidate
-        if (tid == 0) a.filt.t_lo[unit] = -INFINITY;
-        return;
-    }
-
-    const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
-    Chunk<T> kc[LOADS];
-    const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
-#pragma unroll
-    for (int u = 0; u < LOADS; ++u) {
-        const int i = (wave * LOADS + u) * RPW + grp;   // sample number
-        int row = (int)(((int64_t)i * n) / kSample);
-        if (stratum > 1) row += (int)(mix32((uint32_t)unit * 0x9E3779B9u + (uint32_t)i) % (uint32_t)stratum);
-        row = row < n ? row : n - 1;
-        kc[u] = load_chunk(kbase + (int64_t)row * a.k_sn);
-    }
-    float qs[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) qs[i] = 0.f;
-    {
-        const T* qp = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)g * a.G * a.q_sh + c * EPL;
-        for (int h = 0; h < a.G; ++h) {
-            const Chunk<T> qc = load_chunk(qp + (int64_t)h * a.q_sh);
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) qs[i] += qc.at(i);
+        if (a.filt.test_mode != 0 && tile % 3 == 1) t_lo = a.filt.test_mode == 1 ? INFINITY : -INFINITY;
+        // Record of this tile, 8-byte items: {count, t_lo used}, {0, 0}, then the first kFilterPrimary
+        // pairs in row order; records of consecutive tiles are adjacent.  A tile with more pairs also
+        // writes all of them to its overflow rows.  Every store covers whole 128-byte lines (the
+        // tail of the last line is zero-filled): a partially written line costs a fetch of the rest.
+        const int64_t tile_id = unit * a.filt.n_tiles + tile;
+        uint2* rec = reinterpret_cast<uint2*>(a.filt.tiles) + tile_id * (kFilterPrimary + 2);
+        uint2* ovf = a.filt.overflow + tile_id * a.rows_per_block;
+        const int tile_len = row_end - row_begin;
+        const uint64_t lanes_below = (1ull << lane) - 1ull;
+        uint32_t count = 0;
+        for (int r = lane; r - lane < tile_len; r += kWave) {   // wave-uniform trip count
+            const float v = r < tile_len ? s_val[r] : -INFINITY;
+            const bool is_cand = r < tile_len && v >= t_lo && v > -INFINITY;
+            const uint64_t cand_lanes = __ballot(is_cand);
+            if (is_cand)
+                s_pair[count + (uint32_t)__popcll(cand_lanes & lanes_below)] =
+                    make_uint2(__float_as_uint(v), (uint32_t)(row_begin + r));
+            count += (uint32_t)__popcll(cand_lanes);
         }
-    }
-#pragma unroll
-    for (int u = 0; u < LOADS; ++u) {
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) s = fmaf(kc[u].at(i), qs[i], s);
-        s = group_sum<LPR>(s) * a.scale;
-        if (c == 0) samp[(wave * LOADS + u) * RPW + grp] = s;
-    }
-    __syncthreads();
-    // The rank-th largest sample, four bits of its order-preserving key per round: every
-    // wavefront holds all keys (kSample/64 per lane); wavefront w counts the keys >= the probe
-    // with digit w+1, and the digit is the number of probes that still have `rank` keys.
-    {
-        constexpr int KPL = kSample / kWave;
-        __shared__ uint32_t s_probe[2][NW];
-        uint32_t keys[KPL];
-#pragma unroll
-        for (int i = 0; i < KPL; ++i) keys[i] = score_key(samp[lane + i * kWave]);
-        uint32_t prefix = 0;
-#pragma unroll
-        for (int round = 0; round < 8; ++round) {
-            const int shift = 28 - 4 * round;
-            if (wave < 15) {
-                const uint32_t probe = prefix | ((uint32_t)(wave + 1) << shift);
-                int cnt = 0;
-#pragma unroll
-                for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
-                if (lane == 0) s_probe[round & 1][wave] = (uint32_t)cnt;
+        __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+        {
+            const uint32_t items = min(count + 2u, (uint32_t)kFilterPrimary + 2u);
+            if ((uint32_t)lane < ((items + 15u) & ~15u)) {
+                uint2 v = make_uint2(0u, 0u);
+                if (lane == 0) v = make_uint2(count, __float_as_uint(t_lo));
+                else if (lane >= 2 && (uint32_t)lane < items) v = s_pair[lane - 2];
+                rec[lane] = v;
             }
-            __syncthreads();
-            uint32_t digit = 0;
-#pragma unroll
-            for (int w = 0; w < 15; ++w) digit += s_probe[round & 1][w] >= (uint32_t)rank ? 1u : 0u;
-            prefix |= digit << shift;
         }
-        if (tid == 0) {
-            const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
-            a.filt.t_lo[unit] = __uint_as_float(u);
+        if (count > (uint32_t)kFilterPrimary) {
+            const uint32_t padded = min((count + 15u) & ~15u, (uint32_t)a.rows_per_block);
+            for (uint32_t f = lane; f < padded; f += kWave) ovf[f] = f < count ? s_pair[f] : make_uint2(0u, 0u);
         }
     }
 }
@@ -279,22 +317,18 @@ hipError_t launch_typed(const ScoreArgs& a, hipStream_t stream) {
     k.rows_per_block = rpb;
     const unsigned tiles = (unsigned)((a.n_vis_max + rpb - 1) / rpb);
     if (tiles == 0 || a.B == 0) return hipSuccess;
-    dim3 grid(tiles, (unsigned)a.Hkv, (unsigned)a.B), block(kScoreWaves * kWave);
+    dim3 block(kScoreThreads);
     if (a.filt.tiles) {
+        const uint64_t blocks = (uint64_t)a.B * a.Hkv * (1u + tiles);
+        if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+        dim3 grid((unsigned)blocks);
         if (a.stream_loads) hipLaunchKernelGGL((score_kernel<T, D, true, true>), grid, block, 0, stream, k);
         else hipLaunchKernelGGL((score_kernel<T, D, false, true>), grid, block, 0, stream, k);
     } else {
+        dim3 grid(tiles, (unsigned)a.Hkv, (unsigned)a.B);
         if (a.stream_loads) hipLaunchKernelGGL((score_kernel<T, D, true, false>), grid, block, 0, stream, k);
         else hipLaunchKernelGGL((score_kernel<T, D, false, false>), grid, block, 0, stream, k);
     }
-    return hipGetLastError();
-}
-
-template <typename T, int D>
-hipError_t launch_presample_typed(const ScoreArgs& a, hipStream_t stream) {
-    if (a.B == 0 || a.Hkv == 0) return hipSuccess;
-    dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSampleThreads);
-    hipLaunchKernelGGL((presample_kernel<T, D>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -306,8 +340,6 @@ int score_row_granule(int dtype, int D) {
     return kScoreWaves * (kWave / lpr) * kScoreUnroll;
 }
 
-int score_wave_rows(int dtype, int D) { return score_row_granule(dtype, D) / kScoreWaves; }
-
 int presample_rows() { return kSample; }
 
 int filter_tile_rows(int dtype, int D, int requested, int n_vis_max, int max_tiles) {
@@ -317,17 +349,6 @@ int filter_tile_rows(int dtype, int D, int requested, int n_vis_max, int max_til
     if (rpb > kFilterMaxTileRows) rpb = kFilterMaxTileRows / granule * granule;
     while ((n_vis_max + rpb - 1) / rpb > max_tiles && rpb + granule <= kFilterMaxTileRows) rpb += granule;
     return (n_vis_max + rpb - 1) / rpb > max_tiles ? 0 : rpb;
-}
-
-hipError_t launch_presample(const ScoreArgs& a, hipStream_t stream) {
-    if (a.dtype == 0) {
-        if (a.D == 128) return launch_presample_typed<_Float16, 128>(a, stream);
-        if (a.D == 64) return launch_presample_typed<_Float16, 64>(a, stream);
-    } else {
-        if (a.D == 128) return launch_presample_typed<float, 128>(a, stream);
-        if (a.D == 64) return launch_presample_typed<float, 64>(a, stream);
-    }
-    return hipErrorInvalidValue;
 }
 
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream) {

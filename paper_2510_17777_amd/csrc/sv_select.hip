@@ -374,8 +374,11 @@ struct FilteredShared {
     float c_score[kFiltCap];
     int32_t c_row[kFiltCap];
     uint32_t tile_cnt[kFiltMaxTiles];
+    float tile_tlo[kFiltMaxTiles];          // the threshold each tile used
     uint32_t tile_off[kFiltMaxTiles + 1];   // exclusive prefix sums of the tile counts
     uint32_t wave_tot[16];
+    float tlo_min[4], tlo_max[4];
+    uint32_t n_at_or_above;
 };
 
 __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const SelectArgs a, const FilterArgs f) {
@@ -405,11 +408,21 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
 #pragma unroll
     for (int u = 0; u < kFiltLoads; ++u) {
         const int w = tid + u * NT;
-        if (w % kFiltRec16 == 0 && w < kFiltMaxTiles * kFiltRec16)
-            sh.tile_cnt[w / kFiltRec16] = w < live_tiles * kFiltRec16 ? min(word[u].x, (uint32_t)f.tile_rows) : 0u;
+        if (w % kFiltRec16 == 0 && w < kFiltMaxTiles * kFiltRec16) {
+            const bool live = w < live_tiles * kFiltRec16;
+            sh.tile_cnt[w / kFiltRec16] = live ? min(word[u].x, (uint32_t)f.tile_rows) : 0u;
+            sh.tile_tlo[w / kFiltRec16] = live ? __uint_as_float(word[u].y) : 0.f;
+        }
     }
+    if (tid == 0) sh.n_at_or_above = 0;
     __syncthreads();
     const uint32_t my_count = tid < kFiltMaxTiles ? sh.tile_cnt[tid] : 0u;
+    if (tid < kFiltMaxTiles) {   // wavefronts 0..3: the spread of the thresholds the tiles used
+        const float t = sh.tile_tlo[tid];
+        const float lo = wave_min_f(tid < live_tiles ? t : INFINITY);
+        const float hi = wave_max(tid < live_tiles ? t : -INFINITY);
+        if (lane == 0) { sh.tlo_min[wave] = lo; sh.tlo_max[wave] = hi; }
+    }
     const uint32_t incl = block_inclusive_scan<NT>(my_count, sh.wave_tot, lane, wave);
     if (tid < kFiltMaxTiles) sh.tile_off[tid] = incl - my_count;
     if (tid == NT - 1) sh.tile_off[kFiltMaxTiles] = incl;
@@ -435,7 +448,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
                 sh.c_score[off + e + 1] = __uint_as_float(word[u].z);
                 sh.c_row[off + e + 1] = (int32_t)word[u].w;
             }
-            // the rare fuller tile: its remaining pairs from the overflow rows
+            // the rare fuller tile: its remaining pairs from the overflow rows (which hold all its pairs)
             for (uint32_t x = kFiltPrimary + (q - 1); x < cnt; x += kFiltRec16 - 1) {
                 const uint2 v = ovf[(int64_t)tile * f.tile_rows + x];
                 sh.c_score[off + x] = __uint_as_float(v.x);
@@ -444,6 +457,21 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         }
     }
     __syncthreads();
+    // Tiles that used different thresholds: a score below its tile's threshold is missing here, so
+    // the k_b-th largest candidate must not lie below the largest threshold used.
+    const float t_min = fminf(fminf(sh.tlo_min[0], sh.tlo_min[1]), fminf(sh.tlo_min[2], sh.tlo_min[3]));
+    const float t_max = fmaxf(fmaxf(sh.tlo_max[0], sh.tlo_max[1]), fmaxf(sh.tlo_max[2], sh.tlo_max[3]));
+    if (t_min != t_max) {   // block-uniform
+        uint32_t c = 0;
+        for (uint32_t i = tid; i < m; i += NT) c += sh.c_score[i] >= t_max ? 1u : 0u;
+        c = wave_inclusive_scan(c, lane);
+        if (lane == kWave - 1 && c > 0) atomicAdd(&sh.n_at_or_above, c);
+        __syncthreads();
+        if (sh.n_at_or_above < (uint32_t)kb) {
+            radix_select_row<NT>(sh.sel.rx, a.scores + unit * a.n_vis_max, out, n, kb, tid, lane, wave);
+            return;
+        }
+    }
     if (m == (uint32_t)kb) {   // every candidate is kept
         for (uint32_t i = tid; i < m; i += NT) out[i] = sh.c_row[i];
         return;
@@ -788,7 +816,7 @@ WsLayout layout_select_ws(size_t units, int parts) {
 }  // namespace
 
 namespace {
-struct FilterLayout { size_t t_lo, tiles, overflow, total; };
+struct FilterLayout { size_t hint, tiles, overflow, total; };
 
 // Sized for the smallest tile the scoring kernel can be asked for, so that the layout does not
 // depend on the launch-shape knobs.
@@ -797,7 +825,7 @@ FilterLayout layout_filter_ws(int dtype, int D, size_t units, int n_vis_max) {
     const int granule = score_row_granule(dtype, D);
     const size_t max_tiles = (size_t)(n_vis_max + granule - 1) / granule;
     size_t off = 0;
-    l.t_lo = off; off += align256(units * sizeof(float));
+    l.hint = off; off += align256(units * sizeof(uint64_t));
     l.tiles = off; off += align256(units * max_tiles * kFiltRec16 * sizeof(uint4));
     l.overflow = off; off += align256(units * ((size_t)n_vis_max + 512) * sizeof(uint2));
     l.total = off;
@@ -828,13 +856,15 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     const FilterLayout l = layout_filter_ws(dtype, D, (size_t)B * Hkv, n_vis_max);
     char* p = static_cast<char*>(base);
     FilterArgs f{};
-    f.t_lo = reinterpret_cast<float*>(p + l.t_lo);
+    f.hint = reinterpret_cast<uint64_t*>(p + l.hint);
     f.tiles = reinterpret_cast<uint4*>(p + l.tiles);
     f.overflow = reinterpret_cast<uint2*>(p + l.overflow);
     f.tile_rows = filter_tile_rows(dtype, D, requested_tile_rows, n_vis_max, kFiltMaxTiles);
     f.n_tiles = (n_vis_max + f.tile_rows - 1) / f.tile_rows;
     f.k = k;
     f.rank_override = 0;
+    f.epoch = 0;
+    f.test_mode = 0;
     return f;
 }
 

@@ -188,8 +188,10 @@ def _exact_sets(r, k, vis_len):
 def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     """Long rows inside sv_decode_step: the sampled threshold + candidate slots + on-chip ranking must
     give exactly the set a full sort of the GPU's own scores gives -- with the filter on, with the
-    filter off, when the threshold is forced too high (too few candidates: whole-row fallback), for
-    ragged and empty rows, and for every tiling of the scoring kernel."""
+    filter off, when the threshold is forced too high or too low (too few / too many candidates:
+    whole-row fallback), when tiles disagree on the threshold (every third tile hands over nothing,
+    or everything: the consistency check must catch the first and accept the second), for ragged
+    and empty rows, and for every tiling of the scoring kernel."""
     import paper_2510_17777_amd as sv
     Hkv, B = 2, 3
     inp = rand_inputs(31 + D + G, B, Hkv * G, Hkv, D, Nv, 40, dtype)
@@ -198,21 +200,24 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     vis_len = np.array([Nv, Nv - 13, Nv // 3], np.int32)
     base = None
     try:
-        for filt, rank, rows in [(1, 0, 0), (0, 0, 0), (1, 1, 0), (1, 440, 0), (1, 0, 128), (1, 0, 1024)]:
+        for filt, rank, rows, mode in [(1, 0, 0, 0), (0, 0, 0, 0), (1, 1, 0, 0), (1, 440, 0, 0), (1, 0, 128, 0),
+                                       (1, 0, 1024, 0), (1, 0, 0, 1), (1, 0, 0, 2), (1, 300, 128, 2)]:
             sv.sv_set_tuning("select_filter", filt)
             sv.sv_set_tuning("filter_rank", rank)
             sv.sv_set_tuning("score_rows_per_block", rows)
+            sv.sv_set_tuning("filter_test_mode", mode)
             r = run_step(inp, k, vis_len=vis_len, dev=None if base is None else base["dev"])
-            assert _exact_sets(r, k, vis_len), (filt, rank, rows)
+            assert _exact_sets(r, k, vis_len), (filt, rank, rows, mode)
             if base is None:
                 base = r
             else:
                 for key in ("scores", "idx", "count", "out", "lse"):
-                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows)
+                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode)
     finally:
         sv.sv_set_tuning("select_filter", -1)
         sv.sv_set_tuning("filter_rank", 0)
         sv.sv_set_tuning("score_rows_per_block", 0)
+        sv.sv_set_tuning("filter_test_mode", 0)
     assert_step_matches(inp, k, vis_len=vis_len, label="filtered")
 
 
@@ -318,3 +323,4 @@ def test_tuning_knobs_change_launch_shape_not_results():
         sv.sv_set_tuning("attn_chunk", 0)
         sv.sv_set_tuning("score_stream_loads", -1)
         sv.sv_set_tuning("attn_mfma", -1)
+
