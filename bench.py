@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only launch the library's plain 1 GiB copy kernel 5 times (run under rocprofv3 --pmc "
                          "to learn what FETCH_SIZE / WRITE_SIZE report for a known size)")
+    ap.add_argument("--keep-scores", action="store_true",
+                    help="hand sv_decode_step a scores buffer (it then also stores all 22 MB of scores per step)")
     ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
                     help="launch-shape knob for sweeps, e.g. --set attn_chunk=256")
     return ap.parse_args()
@@ -101,13 +103,14 @@ def main():
     txt_len = inp["txt_len"] if ragged else None
     shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], w.k, vis_len=vis_len, txt_len=txt_len)
     buf = sv.DecodeBuffers(shape, dev, with_scores=True)
+    step_scores = buf.scores if args.keep_scores else None
     queries = [d["q"]]
     for rnd in range(1, w.rounds):
         queries.append(torch.from_numpy(sv_inputs.round_query(w, rnd)).to(dev))
 
     def step(i: int):
         sv.sv_decode_step(shape, queries[i % len(queries)], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"],
-                          buf.scores, buf.idx, buf.count, buf.out, buf.lse, buf.workspace)
+                          step_scores, buf.idx, buf.count, buf.out, buf.lse, buf.workspace)
 
     for i in range(args.warmup):
         step(i)

@@ -125,6 +125,7 @@ sv::ScoreArgs make_score_args(const sv_shape* s, const void* q, const void* k_vi
     a.k_sb = s->kv_vis_stride_b; a.k_sh = s->kv_vis_stride_h; a.k_sn = s->kv_vis_stride_n;
     a.rows_per_block = g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block : kDefaultScoreRows;
     a.stream_loads = g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
+    a.write_scores = 1;
     return a;
 }
 
@@ -263,11 +264,12 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
             sa.filt.rank_override = g_tuning.filter_rank;
             sa.filt.test_mode = g_tuning.filter_test_mode;
             sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
+            sa.write_scores = scores != nullptr;   // nobody asked for the scores: do not spend HBM writes on them
         }
         hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
         const sv::SelectArgs sel = make_select_args(s, w, workspace, sc, idx, count);
-        e = filter ? sv::launch_select_filtered(sel, sa.filt, hs) : sv::launch_select(sel, hs);
+        e = filter ? sv::launch_select_filtered(sel, sa, hs) : sv::launch_select(sel, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     } else if (count && (idx || s->k == 0)) {
         // nothing can be kept (k == 0 or no visual rows): the kept sets are empty, count = 0

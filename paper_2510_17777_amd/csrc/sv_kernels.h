@@ -42,6 +42,8 @@ struct ScoreArgs {
     int64_t k_sb, k_sh, k_sn;
     int32_t rows_per_block;   // tuning; rounded up to the kernel's granule by the launcher
     int32_t stream_loads;     // 1: non-temporal K loads
+    int32_t write_scores;     // candidate filter on: 0 = the scores themselves are not stored (the selection
+                              // recomputes a row's scores in the rare case it needs them all)
     FilterArgs filt;          // filt.tiles == nullptr: no candidate emission
 };
 
@@ -90,7 +92,9 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
 // until the row has at most max_tiles tiles; 0 if that is impossible.
 int filter_tile_rows(int dtype, int D, int requested, int n_vis_max, int max_tiles);
 int presample_rows();                                                  // rows sampled per (b, g)
-hipError_t launch_select_filtered(const SelectArgs& a, const FilterArgs& f, hipStream_t stream);
+// sc: the scoring arguments of the same call (sc.filt = the candidate records; sc.scores = a.scores, which
+// holds the scores if sc.write_scores and serves as scratch for a row's recomputed scores otherwise).
+hipError_t launch_select_filtered(const SelectArgs& a, const ScoreArgs& sc, hipStream_t stream);
 
 // Scratch the selection needs for rows too long for one workgroup (0 for short rows).
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);

@@ -29,13 +29,11 @@
 // 13 us on the long-video shape, of which 4.5 us is the price of any kernel boundary.
 // The record store by one wavefront after a barrier costs about 5 % of the kernel;
 // small scattered stores straight from the passes cost 8 %.
-#include "sv_device.h"
-#include "sv_kernels.h"
+#include "sv_score_device.h"
 
 namespace sv {
 namespace {
 
-constexpr int kScoreUnroll = 8;   // independent row loads in flight per lane
 constexpr int kScoreWaves = 4;    // wavefronts per workgroup
 constexpr int kScoreThreads = kScoreWaves * kWave;
 constexpr int kFilterMaxTileRows = 512;   // rows of one scoring workgroup when it emits candidates
@@ -56,29 +54,6 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {   // integer finaliser, 
 __device__ __forceinline__ int sample_rank(int n, int kb) {
     const float m = (float)kSample * (float)kb / (float)n;
     return (int)ceilf(m + 5.f * sqrtf(m) + 4.f);
-}
-
-__device__ __forceinline__ int live_rows_of(const ScoreArgs& a, int b) {
-    int n = a.n_vis_max;
-    if (a.vis_len) {
-        const int v = a.vis_len[b];
-        n = v < 0 ? 0 : (v < n ? v : n);
-    }
-    return n;
-}
-
-// Summed query of group g, the EPL dims of chunk c.
-template <typename T>
-__device__ __forceinline__ void summed_query(const ScoreArgs& a, int b, int g, int c, float (&qs)[Chunk<T>::kElems]) {
-    constexpr int EPL = Chunk<T>::kElems;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) qs[i] = 0.f;
-    const T* qp = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)g * a.G * a.q_sh + c * EPL;
-    for (int h = 0; h < a.G; ++h) {
-        const Chunk<T> qc = load_chunk(qp + (int64_t)h * a.q_sh);
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) qs[i] += qc.at(i);
-    }
 }
 
 __device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, float t_lo) {
@@ -222,37 +197,10 @@ void score_kernel(const ScoreArgs a) {
     const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
 
     for (int r0 = row_begin + wave * WAVE_ROWS; r0 < row_end; r0 += BLOCK_ROWS) {
-        float acc[U];
-        Chunk<T> kc[U];
-        if (r0 + WAVE_ROWS <= n) {   // wave-uniform: every row of this pass is live
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const T* p = kbase + (int64_t)(r0 + u * RPW + grp) * a.k_sn;
-                kc[u] = kStream ? load_chunk_stream(p) : load_chunk(p);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = r0 + u * RPW + grp;
-                kc[u] = row < n ? load_chunk(kbase + (int64_t)row * a.k_sn) : zero_chunk<T>();
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) s = fmaf(kc[u].at(i), qs[i], s);
-            acc[u] = group_sum<LPR>(s);
-        }
-        // Lane c of row-group grp stores the row of load u == c: a wavefront writes
-        // WAVE_ROWS consecutive floats with one instruction.
-        float o = acc[0];
-#pragma unroll
-        for (int u = 1; u < U; ++u) o = (c == u) ? acc[u] : o;
+        const float val = score_pass<T, D, kStream>(a, kbase, qs, r0, n, c, grp);
         const int row = r0 + c * RPW + grp;
-        const float val = row < n ? o * a.scale : -INFINITY;
         if (c < U && row < row_end) {
-            srow[row] = val;
+            if (!kFilter || a.write_scores) srow[row] = val;
             if (kFilter) s_val[row - row_begin] = val;
         }
     }

@@ -32,8 +32,7 @@
 //     barriers) and no global atomic is used: a returning device-scope atomic costs
 //     microseconds here.  Every kernel issues all its global loads up front, because
 //     one dependent round trip through memory costs more than the arithmetic.
-#include "sv_device.h"
-#include "sv_kernels.h"
+#include "sv_score_device.h"
 
 #include <cfloat>
 #include <cmath>
@@ -381,8 +380,10 @@ struct FilteredShared {
     uint32_t n_at_or_above;
 };
 
-__global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const SelectArgs a, const FilterArgs f) {
+template <typename T, int D>
+__global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const SelectArgs a, const ScoreArgs sc) {
     constexpr int NT = kSingleThreads;
+    const FilterArgs& f = sc.filt;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     FilteredShared& sh = *reinterpret_cast<FilteredShared*>(smem_raw);
     const int g = blockIdx.x, b = blockIdx.y;
@@ -429,8 +430,18 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     __syncthreads();
     const uint32_t m = sh.tile_off[kFiltMaxTiles];   // candidates of the row
 
-    if (m < (uint32_t)kb || m > (uint32_t)kFiltCap) {   // block-uniform: the filter missed, take the whole row
-        radix_select_row<NT>(sh.sel.rx, a.scores + unit * a.n_vis_max, out, n, kb, tid, lane, wave);
+    // Whole-row selection for a row the filter missed.  If the scoring launch did not store the scores,
+    // this workgroup computes the row's scores first (slow: one compute unit streams the row's keys).
+    auto select_whole_row = [&]() {
+        float* row_scores = sc.scores + unit * a.n_vis_max;
+        if (!sc.write_scores) {
+            score_row_by_workgroup<T, D>(sc, b, g, row_scores);
+            __syncthreads();
+        }
+        radix_select_row<NT>(sh.sel.rx, row_scores, out, n, kb, tid, lane, wave);
+    };
+    if (m < (uint32_t)kb || m > (uint32_t)kFiltCap) {   // block-uniform: too few or too many candidates
+        select_whole_row();
         return;
     }
 #pragma unroll
@@ -468,7 +479,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         if (lane == kWave - 1 && c > 0) atomicAdd(&sh.n_at_or_above, c);
         __syncthreads();
         if (sh.n_at_or_above < (uint32_t)kb) {
-            radix_select_row<NT>(sh.sel.rx, a.scores + unit * a.n_vis_max, out, n, kb, tid, lane, wave);
+            select_whole_row();
             return;
         }
     }
@@ -868,15 +879,29 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     return f;
 }
 
-hipError_t launch_select_filtered(const SelectArgs& a, const FilterArgs& f, hipStream_t stream) {
-    if (a.B == 0 || a.Hkv == 0) return hipSuccess;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_filtered_kernel),
+namespace {
+template <typename T, int D>
+hipError_t launch_select_filtered_typed(const SelectArgs& a, const ScoreArgs& sc, hipStream_t stream) {
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_filtered_kernel<T, D>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                                        (int)sizeof(FilteredShared));
     if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
-    hipLaunchKernelGGL(select_filtered_kernel, grid, block, sizeof(FilteredShared), stream, a, f);
+    hipLaunchKernelGGL((select_filtered_kernel<T, D>), grid, block, sizeof(FilteredShared), stream, a, sc);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_select_filtered(const SelectArgs& a, const ScoreArgs& sc, hipStream_t stream) {
+    if (a.B == 0 || a.Hkv == 0) return hipSuccess;
+    if (sc.dtype == 0) {
+        if (sc.D == 128) return launch_select_filtered_typed<_Float16, 128>(a, sc, stream);
+        if (sc.D == 64) return launch_select_filtered_typed<_Float16, 64>(a, sc, stream);
+    } else {
+        if (sc.D == 128) return launch_select_filtered_typed<float, 128>(a, sc, stream);
+        if (sc.D == 64) return launch_select_filtered_typed<float, 64>(a, sc, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 size_t select_workspace_bytes(int B, int Hkv, int n_vis_max) {

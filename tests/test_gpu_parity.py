@@ -213,6 +213,11 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
             else:
                 for key in ("scores", "idx", "count", "out", "lse"):
                     assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode)
+            # without a scores buffer the scoring launch stores no scores at all; a row whose candidates
+            # do not suffice is then re-scored by the selection itself
+            r2 = run_step(inp, k, vis_len=vis_len, dev=base["dev"], with_scores=False)
+            for key in ("idx", "count", "out", "lse"):
+                assert np.array_equal(r2[key], base[key]), (key, filt, rank, rows, mode, "no scores buffer")
     finally:
         sv.sv_set_tuning("select_filter", -1)
         sv.sv_set_tuning("filter_rank", 0)
@@ -231,6 +236,8 @@ def test_filtered_selection_degenerate_rows():
     r = run_step(inp, k, vis_len=vis_len)
     assert _exact_sets(r, k, vis_len)
     assert np.array_equal(r["idx"][0, 0], np.arange(k))
+    r2 = run_step(inp, k, vis_len=vis_len, dev=r["dev"], with_scores=False)
+    assert np.array_equal(r2["idx"], r["idx"]) and np.array_equal(r2["out"], r["out"])
     assert_step_matches(inp, k, vis_len=vis_len, label="filtered degenerate")
 
 
