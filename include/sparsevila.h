@@ -178,8 +178,9 @@ const char *sv_strerror(sv_status status);
  *   "filter_test_mode"      0; 1 / 2 make every third tile of the scoring kernel ignore the threshold and hand
  *                           over none / all of its scores (tests of the selection's consistency check)
  * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
- * Process-wide; not thread-safe against concurrent calls.  Results never depend on
- * the knobs beyond fp32 summation order in step 3.
+ * Process-wide; not thread-safe against concurrent calls.  scores, idx and count never depend on
+ * the knobs; out and lse depend on them only through fp32 summation order in step 3 and, for
+ * "attn_mfma", through the rounding of the softmax weights to fp16 on the matrix-core path.
  */
 sv_status sv_set_tuning(const char *name, int32_t value);
 int32_t sv_get_tuning(const char *name);

@@ -156,7 +156,7 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
     a.chunk = g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
     a.use_mfma = (s->dtype == SV_F16) && (g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma);
-    if (a.use_mfma) a.chunk = sv::attn_mfma_chunk();   // the attn_chunk knob shapes the vector path only
+    if (a.use_mfma) a.chunk = sv::attn_mfma_chunk(s->head_dim);   // the attn_chunk knob shapes the vector path only
     const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
     a.n_chunks = (int32_t)((t_max + a.chunk - 1) / a.chunk);
     return a;

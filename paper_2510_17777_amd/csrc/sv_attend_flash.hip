@@ -1,0 +1,259 @@
+// Step 3 for fp16 caches with head_dim 128: chunk attention with BOTH contractions on the
+// matrix cores and every wavefront streaming through several batches of tokens.
+//
+// Why this shape (measured on the long-video workload, 202 MB of gathered K/V rows per step):
+// a kernel in which every wavefront fetched its 64 tokens, computed, and ended ran as two
+// chip-wide rounds of load-then-compute, the memory system idle while the wavefronts
+// computed (53 us, 3.8 TB/s); the fp32 FMAs of p*V alone were 8 us of it.  Here
+//   * a wavefront owns kBatches batches of 32 tokens and walks through them; the K rows of
+//     the next batch are requested as soon as the logits of the current one are done, the V
+//     rows of the next batch as soon as the current p*V is done, so rows are in flight while
+//     the wavefront computes;
+//   * logits: v_mfma_f32_16x16x32_f16, A = 16 (zero-padded) query heads x 32 dims, B = 32
+//     dims x 16 tokens (the same 8 consecutive dims of a row on both sides);
+//   * p*V: the same instruction, A = 16 heads x 32 tokens (p rounded to fp16, through LDS),
+//     B = 32 tokens x 16 dims.  A lane of B must supply 8 TOKENS of one dim; the value rows
+//     arrive as 8 DIMS of one token per lane.  No transpose is needed: lane (g4, c) of the
+//     value loads holds dims 8c..8c+7 of tokens 4u+g4 (u = load number 0..7), so for MFMA
+//     number j it packs the j-th half of its eight loads -- tokens {4u+g4} are the lane's 8
+//     contraction indices, dim 8c+j its output column -- and the p operand is stored in LDS
+//     in that same token order.  Eight MFMAs (j = 0..7) cover the 128 dims;
+//   * softmax statistics run per wavefront over its batches (running maximum m, running sum
+//     l, accumulators rescaled when m grows); l is summed from the rounded p, so the weights
+//     that multiply V sum to exactly l.  Rounding p to fp16 perturbs each weight by at most
+//     2^-11 relative: the output moves by far less than the 2e-3 bound of fp16 caches.
+// At the end the four wavefronts of a workgroup merge (m, l, acc) through LDS with the
+// log-sum-exp rule and write one partial result per (head, chunk).
+#include "sv_attend_common.h"
+
+namespace sv {
+namespace {
+
+constexpr int kD = 128;
+constexpr int kBatchTokens = 32;
+constexpr int kBatches = 4;                                     // batches per wavefront
+constexpr int kFlashChunk = kAttnWaves * kBatches * kBatchTokens;   // tokens per workgroup
+constexpr int kKB = kD / 32;                                    // logit MFMAs per 16 tokens
+constexpr int kVLoads = 8;                                      // value loads per lane per batch (4 tokens each)
+
+__device__ __forceinline__ float row16_max(float x) {
+    x = fmaxf(x, dpp_move<kDppQuadXor1>(x));
+    x = fmaxf(x, dpp_move<kDppQuadXor2>(x));
+    x = fmaxf(x, dpp_move<kDppRowHalfMirror>(x));
+    x = fmaxf(x, dpp_move<kDppRowMirror>(x));
+    return x;
+}
+
+template <int GB>
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
+    using T = _Float16;
+    __shared__ __align__(16) T s_p[kAttnWaves][16][kBatchTokens];   // p of the current batch, A-operand order
+    __shared__ __align__(16) T s_q[16][kD];                         // the (zero-padded) query rows
+    __shared__ float s_acc[kAttnWaves][GB][kD];
+    __shared__ float s_m[kAttnWaves][GB], s_l[kAttnWaves][GB];
+
+    const int s = blockIdx.x;
+    const int g = blockIdx.y / hblk, hb = blockIdx.y % hblk;
+    const int b = blockIdx.z;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const TokenList tokens = token_list(a, b, unit);
+    const int t0 = s * kFlashChunk;
+    if (t0 >= tokens.len) return;   // block-uniform
+
+    const int h_first = g * a.G + hb * (hblk > 1 ? kHeadBlock : 0);
+    const int g_valid = min(GB, a.G - hb * (hblk > 1 ? kHeadBlock : 0));
+    const T* ktxt = static_cast<const T*>(a.k_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
+    const T* vtxt = static_cast<const T*>(a.v_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
+    const T* kvis = static_cast<const T*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const T* vvis = static_cast<const T*>(a.v_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const int row = lane & 15, quad = lane >> 4;   // MFMA coordinates of this lane
+
+    // Where the wavefront's tokens live: batch j covers tokens t0 + (4j + wave) * 32 + [0, 32);
+    // >= 0: text row, < 0: -(visual row) - 1.  Requested two batches ahead of their use.
+    auto load_code = [&](int j) -> int {
+        const int t = t0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
+        int c = 0;
+        if (j < kBatches && t < tokens.len) {
+            if (t < tokens.nt) {
+                c = t;
+            } else {
+                int r = tokens.idx_row[t - tokens.nt];
+                r = r < 0 ? 0 : (r < a.n_vis_max ? r : a.n_vis_max - 1);   // a faulty idx must not fault the GPU
+                c = -r - 1;
+            }
+        }
+        return c;
+    };
+    int code_cur = load_code(0), code_next = load_code(1);
+    // query rows -> LDS (zero rows for the padding heads); read back per batch as the A operand
+    for (int i = threadIdx.x; i < 16 * (kD / 8); i += kAttnThreads) {
+        const int h = i / (kD / 8), c8 = i % (kD / 8);
+        half8_t v = 0;
+        if (h < g_valid)
+            v = *reinterpret_cast<const half8_t*>(static_cast<const T*>(a.q) + (int64_t)b * a.q_sb +
+                                                  (int64_t)(h_first + h) * a.q_sh + c8 * 8);
+        *reinterpret_cast<half8_t*>(&s_q[h][c8 * 8]) = v;
+    }
+    __syncthreads();
+
+    auto row_ptr = [&](int c, const T* txt, const T* vis) -> const T* {
+        return c >= 0 ? txt + (int64_t)c * a.txt_sn : vis + (int64_t)(-c - 1) * a.vis_sn;
+    };
+    auto batch_live = [&](int j) -> int {   // live tokens of batch j of this wavefront (0 = none)
+        const int base = t0 + (j * kAttnWaves + wave) * kBatchTokens;
+        return max(0, min(kBatchTokens, tokens.len - base));
+    };
+    half8_t kf[2][kKB];     // K rows: lane (row, quad) holds dims 8*quad + 32*kb .. +8 of tokens row, 16 + row
+    half8_t vf[kVLoads];    // V rows: lane (quad, row) holds dims 8*row .. +8 of tokens 4u + quad
+    auto load_k = [&](int j, int code) {
+        const int n_live = batch_live(j);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int tl = tt * 16 + row;
+            const int c = __shfl(code, tl, kWave);
+#pragma unroll
+            for (int kb = 0; kb < kKB; ++kb) kf[tt][kb] = 0;
+            if (tl < n_live) {
+                const T* p = row_ptr(c, ktxt, kvis) + quad * 8;
+#pragma unroll
+                for (int kb = 0; kb < kKB; ++kb) kf[tt][kb] = *reinterpret_cast<const half8_t*>(p + 32 * kb);
+            }
+        }
+    };
+    auto load_v = [&](int j, int code) {
+        const int n_live = batch_live(j);
+#pragma unroll
+        for (int u = 0; u < kVLoads; ++u) {
+            const int tl = 4 * u + quad;
+            const int c = __shfl(code, tl, kWave);
+            vf[u] = 0;
+            if (tl < n_live) vf[u] = *reinterpret_cast<const half8_t*>(row_ptr(c, vtxt, vvis) + row * 8);
+        }
+    };
+
+    float4_t acc[8];        // acc[j][r] = out[head 4*quad + r][dim 8*row + j], not normalised
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = {0.f, 0.f, 0.f, 0.f};
+    float m_run[4], l_run[4];   // of heads 4*quad + r, equal in the 16 lanes of a quad
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; }
+
+    if (batch_live(0) > 0) { load_k(0, code_cur); load_v(0, code_cur); }
+#pragma unroll 1
+    for (int j = 0; j < kBatches; ++j) {
+        const int n_live = batch_live(j);
+        if (n_live == 0) break;   // wave-uniform; later batches are empty too
+        const int code_after = load_code(j + 2);
+        const bool more = j + 1 < kBatches && batch_live(j + 1) > 0;
+        // ---- logits of the 32 tokens: lane (row, quad) gets heads 4*quad + r of tokens row and 16 + row
+        float4_t lg[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            float4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < kKB; ++kb) {
+                const half8_t qa = *reinterpret_cast<const half8_t*>(&s_q[row][quad * 8 + 32 * kb]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa, kf[tt][kb], sacc, 0, 0, 0);
+            }
+            const bool live = (tt * 16 + row) < n_live;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lg[tt][r] = live ? sacc[r] * a.scale : -INFINITY;
+        }
+        if (more) load_k(j + 1, code_next);   // K registers are free again
+        // ---- running softmax statistics; p (fp16) to LDS in the order of the p*V contraction index
+        float alpha[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float mb = row16_max(fmaxf(lg[0][r], lg[1][r]));
+            const float m_new = fmaxf(m_run[r], mb);   // finite: the batch has a live token
+            alpha[r] = __expf(m_run[r] - m_new);       // 0 on the first batch
+            m_run[r] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                const T p16 = (T)__expf(lg[tt][r] - m_new);
+                psum += (float)p16;
+                // token t = 16*tt + row is contraction index 8*(t % 4) + t / 4 of its batch
+                s_p[wave][4 * quad + r][8 * (row & 3) + 4 * tt + (row >> 2)] = p16;
+            }
+            l_run[r] = fmaf(l_run[r], alpha[r], group_sum<16>(psum));
+        }
+        __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+        const half8_t pa = *reinterpret_cast<const half8_t*>(&s_p[wave][row][8 * quad]);
+        __builtin_amdgcn_wave_barrier();
+        // ---- acc = acc * alpha + p * V
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            half8_t vb;
+#pragma unroll
+            for (int u = 0; u < kVLoads; ++u) vb[u] = vf[u][jj];
+            float4_t c4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c4[r] = acc[jj][r] * alpha[r];
+            acc[jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, vb, c4, 0, 0, 0);
+        }
+        if (more) load_v(j + 1, code_next);   // V registers are free again
+        code_cur = code_next;
+        code_next = code_after;
+    }
+    (void)code_cur;
+
+    // ---- the wavefront's result to LDS: rows of the valid heads only
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int h = 4 * quad + r;
+        if (h < GB) {
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) s_acc[wave][h][8 * row + jj] = acc[jj][r];
+            if (row == 0) { s_m[wave][h] = m_run[r]; s_l[wave][h] = l_run[r]; }
+        }
+    }
+    __syncthreads();
+
+    // ---- merge the four wavefronts: one partial result per (head, chunk)
+    const int S = a.n_chunks;
+    for (int o = threadIdx.x; o < GB * kD; o += kAttnThreads) {
+        const int h = o / kD, d = o % kD;
+        if (h >= g_valid) continue;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) m = fmaxf(m, s_m[w][h]);
+        float x = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) {
+            const float mw = s_m[w][h];
+            const float e = mw == -INFINITY ? 0.f : __expf(mw - m);
+            x = fmaf(e, s_acc[w][h][d], x);
+            l = fmaf(e, s_l[w][h], l);
+        }
+        const int64_t ph = ((int64_t)b * a.Hq + h_first + h) * S + s;
+        a.part_acc[ph * kD + d] = x;
+        if (d == 0) { a.part_ml[ph * 2] = m; a.part_ml[ph * 2 + 1] = l; }
+    }
+}
+
+template <int GB>
+hipError_t launch_one(const AttnArgs& a, int hblk, hipStream_t stream) {
+    dim3 grid((unsigned)a.n_chunks, (unsigned)(a.Hkv * hblk), (unsigned)a.B), block(kAttnThreads);
+    hipLaunchKernelGGL((attn_partial_flash_kernel<GB>), grid, block, 0, stream, a, hblk);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int attn_flash_chunk() { return kFlashChunk; }
+
+hipError_t launch_attn_partial_flash(const AttnArgs& a, hipStream_t stream) {
+    if (a.chunk != kFlashChunk || a.D != kD) return hipErrorInvalidValue;
+    const int G = a.G;
+    if (G == 1) return launch_one<1>(a, 1, stream);
+    if (G == 2) return launch_one<2>(a, 1, stream);
+    if (G <= 4) return launch_one<4>(a, 1, stream);
+    if (G == 7) return launch_one<7>(a, 1, stream);
+    if (G <= 8) return launch_one<8>(a, 1, stream);
+    return launch_one<8>(a, (G + kHeadBlock - 1) / kHeadBlock, stream);
+}
+
+}  // namespace sv

@@ -256,11 +256,11 @@ hipError_t launch_dim(const AttnArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-int attn_mfma_chunk() { return kNW * kWaveTokens; }
+int attn_mfma_chunk(int D) { return D == 128 ? attn_flash_chunk() : kNW * kWaveTokens; }
 
 hipError_t launch_attn_partial_mfma(const AttnArgs& a, hipStream_t stream) {
-    if (a.chunk != attn_mfma_chunk()) return hipErrorInvalidValue;
-    if (a.D == 128) return launch_dim<128>(a, stream);
+    if (a.D == 128) return launch_attn_partial_flash(a, stream);
+    if (a.chunk != kNW * kWaveTokens) return hipErrorInvalidValue;
     if (a.D == 64) return launch_dim<64>(a, stream);
     return hipErrorInvalidValue;
 }

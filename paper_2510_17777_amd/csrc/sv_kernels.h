@@ -102,8 +102,8 @@ size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 // Plain copy of `bytes` (multiple of 16) device bytes; calibration aid for traffic counters.
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
-// Tokens per workgroup of the matrix-core attention kernel (fixed by its register layout).
-int attn_mfma_chunk();
+// Tokens per workgroup of the matrix-core attention kernels (fixed by their register layouts).
+int attn_mfma_chunk(int D);
 
 // Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
 int score_row_granule(int dtype, int D);

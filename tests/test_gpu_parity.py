@@ -324,7 +324,8 @@ def test_tuning_knobs_change_launch_shape_not_results():
             r = run_step(inp, w.k, dev=base["dev"])
             assert np.array_equal(r["scores"], base["scores"])
             assert np.array_equal(r["idx"], base["idx"])
-            assert np.abs(r["out"] - base["out"]).max() <= 1e-5
+            # the matrix-core path rounds the softmax weights to fp16 before p*V, the vector path does not
+            assert np.abs(r["out"] - base["out"]).max() <= 5e-4
     finally:
         sv.sv_set_tuning("score_rows_per_block", 0)
         sv.sv_set_tuning("attn_chunk", 0)
