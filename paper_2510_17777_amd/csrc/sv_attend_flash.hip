@@ -118,7 +118,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             if (tl < n_live) {
                 const T* p = row_ptr(c, ktxt, kvis) + quad * 8;
 #pragma unroll
-                for (int kb = 0; kb < kKB; ++kb) kf[tt][kb] = *reinterpret_cast<const half8_t*>(p + 32 * kb);
+                for (int kb = 0; kb < kKB; ++kb)   // rows are used once per step: do not displace reusable lines
+                    kf[tt][kb] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(p + 32 * kb));
             }
         }
     };
@@ -129,7 +130,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             const int tl = 4 * u + quad;
             const int c = __shfl(code, tl, kWave);
             vf[u] = 0;
-            if (tl < n_live) vf[u] = *reinterpret_cast<const half8_t*>(row_ptr(c, vtxt, vvis) + row * 8);
+            if (tl < n_live)
+                vf[u] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(row_ptr(c, vtxt, vvis) + row * 8));
         }
     };
 
