@@ -90,7 +90,8 @@ struct Workspace {
 Workspace plan_workspace(const sv_shape* s) {
     Workspace w{};
     const size_t B = (size_t)s->batch, Hq = (size_t)s->n_q_heads, Hkv = (size_t)s->n_kv_heads;
-    const size_t S = ((size_t)s->n_txt_max + (size_t)kept_max(s) + kMinChunk - 1) / kMinChunk;
+    // slots of a split token list (text chunks, then visual chunks); never fewer than the joint list needs
+    const size_t S = ((size_t)s->n_txt_max + kMinChunk - 1) / kMinChunk + ((size_t)kept_max(s) + kMinChunk - 1) / kMinChunk;
     w.scores_off = 0;
     w.scores_bytes = align_up(B * Hkv * (size_t)s->n_vis_max * sizeof(float));
     w.acc_off = w.scores_off + w.scores_bytes;
@@ -159,6 +160,11 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     if (a.use_mfma) a.chunk = sv::attn_mfma_chunk(s->head_dim);   // the attn_chunk knob shapes the vector path only
     const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
     a.n_chunks = (int32_t)((t_max + a.chunk - 1) / a.chunk);
+    a.split_base = -1;
+    if (a.use_mfma && s->head_dim == 128) {   // that kernel gives text and visual tokens chunks of their own
+        a.split_base = (s->n_txt_max + a.chunk - 1) / a.chunk;
+        a.n_chunks = a.split_base + (kept_max(s) + a.chunk - 1) / a.chunk;
+    }
     return a;
 }
 

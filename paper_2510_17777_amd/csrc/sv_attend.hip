@@ -205,7 +205,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_combine_kernel(const AttnAr
     const int64_t unit = (int64_t)b * a.Hkv + g;
     const TokenList tokens = token_list(a, b, unit);
     const int S = a.n_chunks;
-    const int Sb = (tokens.len + a.chunk - 1) / a.chunk;
+    // live slots: joint list -> the first ceil(len / chunk); split list -> the first ceil(nt / chunk)
+    // of the text range and the first ceil(kept / chunk) of the visual range
+    const bool split = a.split_base >= 0;
+    const int Sb_txt = split ? (tokens.nt + a.chunk - 1) / a.chunk : 0;
+    const int Sb = split ? Sb_txt + (tokens.len - tokens.nt + a.chunk - 1) / a.chunk
+                         : (tokens.len + a.chunk - 1) / a.chunk;
+    const int skip = split ? a.split_base - Sb_txt : 0;   // dead slots between the live text and visual ranges
+    auto slot_of = [&](int i) -> int { return i < Sb_txt ? i : i + skip; };
     const int64_t bh = (int64_t)b * a.Hq + h;
     if (Sb == 0) {
         if (tid < D) a.out[bh * D + tid] = 0.f;
@@ -225,15 +232,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_combine_kernel(const AttnAr
         mv[r] = -INFINITY;
         lv[r] = 0.f;
         if (sidx < Sb) {
-            av[r] = *reinterpret_cast<const float4_t*>(acc + (int64_t)sidx * D + c4);
-            mv[r] = ml[2 * sidx];
-            lv[r] = ml[2 * sidx + 1];
+            const int sl = slot_of(sidx);
+            av[r] = *reinterpret_cast<const float4_t*>(acc + (int64_t)sl * D + c4);
+            mv[r] = ml[2 * sl];
+            lv[r] = ml[2 * sl + 1];
         }
     }
     float m = -INFINITY;
 #pragma unroll
     for (int r = 0; r < R; ++r) m = fmaxf(m, mv[r]);
-    for (int sidx = grp + R * NG; sidx < Sb; sidx += NG) m = fmaxf(m, ml[2 * sidx]);
+    for (int sidx = grp + R * NG; sidx < Sb; sidx += NG) m = fmaxf(m, ml[2 * slot_of(sidx)]);
     m = wave_max(m);
     if (lane == 0) s_red[wave] = m;
     __syncthreads();
@@ -248,10 +256,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_combine_kernel(const AttnAr
         L = fmaf(w, lv[r], L);
     }
     for (int sidx = grp + R * NG; sidx < Sb; sidx += NG) {
-        const float ms = ml[2 * sidx];
+        const int sl = slot_of(sidx);
+        const float ms = ml[2 * sl];
         const float w = ms == -INFINITY ? 0.f : exp_for<T>(ms - m);
-        o += w * *reinterpret_cast<const float4_t*>(acc + (int64_t)sidx * D + c4);
-        L = fmaf(w, ml[2 * sidx + 1], L);
+        o += w * *reinterpret_cast<const float4_t*>(acc + (int64_t)sl * D + c4);
+        L = fmaf(w, ml[2 * sl + 1], L);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) s_part[grp][c4 + i] = o[i];

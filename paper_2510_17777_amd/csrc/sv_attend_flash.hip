@@ -22,6 +22,10 @@
 //     l, accumulators rescaled when m grows); l is summed from the rounded p, so the weights
 //     that multiply V sum to exactly l.  Rounding p to fp16 perturbs each weight by at most
 //     2^-11 relative: the output moves by far less than the 2e-3 bound of fp16 caches.
+//   * the text tokens and the kept visual tokens get chunks of their own (text first), so the
+//     rows a workgroup needs depend on idx alone; all loads are unconditional, on clamped rows
+//     (conditional loads made every wait a wait for everything), and a workgroup reaches its
+//     first K/V request after one trip through memory instead of three (lengths, idx, rows).
 // At the end the four wavefronts of a workgroup merge (m, l, acc) through LDS with the
 // log-sum-exp rule and write one partial result per (head, chunk).
 #include "sv_attend_common.h"
@@ -53,40 +57,63 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
     __shared__ float s_acc[kAttnWaves][GB][kD];
     __shared__ float s_m[kAttnWaves][GB], s_l[kAttnWaves][GB];
 
+    // Chunks [0, split_base) cover the text tokens, chunks [split_base, S) the kept visual tokens, so
+    // that which rows a workgroup needs depends on nothing but idx: every load below is issued
+    // unconditionally on clamped (valid) rows, and the lengths only mask the logits afterwards.
     const int s = blockIdx.x;
+    const bool is_txt = s < a.split_base;
     const int g = blockIdx.y / hblk, hb = blockIdx.y % hblk;
     const int b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    const TokenList tokens = token_list(a, b, unit);
-    const int t0 = s * kFlashChunk;
-    if (t0 >= tokens.len) return;   // block-uniform
+    const int p0 = (is_txt ? s : s - a.split_base) * kFlashChunk;   // first position of this chunk in its part
+    const int row = lane & 15, quad = lane >> 4;                    // MFMA coordinates of this lane
+    const int row_cap = is_txt ? a.n_txt_max : a.n_vis_max;         // >= 1 for any launched chunk
+
+    // Cache rows of the wavefront's tokens: batch j covers positions p0 + (4j + wave) * 32 + [0, 32).
+    int rowid[kBatches];
+    {
+        const int32_t* idx_row = a.idx + unit * a.k;
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) {
+            const int p = p0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
+            int r = p;
+            if (!is_txt) r = idx_row[min(p, a.k - 1)];   // slots past count hold -1: clamped below
+            rowid[j] = r < 0 ? 0 : (r < row_cap ? r : row_cap - 1);   // a faulty idx must not fault the GPU
+        }
+    }
+    // live positions of this part (the loads do not wait for it)
+    const int part_len = is_txt ? clamp_len(a.txt_len, b, a.n_txt_max)
+                                : ((a.k > 0 && a.count) ? clamp_len(a.count, (int)unit, a.k) : 0);
 
     const int h_first = g * a.G + hb * (hblk > 1 ? kHeadBlock : 0);
     const int g_valid = min(GB, a.G - hb * (hblk > 1 ? kHeadBlock : 0));
-    const T* ktxt = static_cast<const T*>(a.k_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
-    const T* vtxt = static_cast<const T*>(a.v_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
-    const T* kvis = static_cast<const T*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
-    const T* vvis = static_cast<const T*>(a.v_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
-    const int row = lane & 15, quad = lane >> 4;   // MFMA coordinates of this lane
+    const int64_t sn = is_txt ? a.txt_sn : a.vis_sn;
+    const int64_t base_off = is_txt ? (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh
+                                    : (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const T* kbase = static_cast<const T*>(is_txt ? a.k_txt : a.k_vis) + base_off;
+    const T* vbase = static_cast<const T*>(is_txt ? a.v_txt : a.v_vis) + base_off;
 
-    // Where the wavefront's tokens live: batch j covers tokens t0 + (4j + wave) * 32 + [0, 32);
-    // >= 0: text row, < 0: -(visual row) - 1.  Requested two batches ahead of their use.
-    auto load_code = [&](int j) -> int {
-        const int t = t0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
-        int c = 0;
-        if (j < kBatches && t < tokens.len) {
-            if (t < tokens.nt) {
-                c = t;
-            } else {
-                int r = tokens.idx_row[t - tokens.nt];
-                r = r < 0 ? 0 : (r < a.n_vis_max ? r : a.n_vis_max - 1);   // a faulty idx must not fault the GPU
-                c = -r - 1;
-            }
+    half8_t kf[2][kKB];     // K rows: lane (row, quad) holds dims 8*quad + 32*kb .. +8 of tokens row, 16 + row
+    half8_t vf[kVLoads];    // V rows: lane (quad, row) holds dims 8*row .. +8 of tokens 4u + quad
+    auto load_k = [&](int rows) {   // rows: lane l & 31 holds the cache row of token l of the batch
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const T* p = kbase + (int64_t)__shfl(rows, tt * 16 + row, kWave) * sn + quad * 8;
+#pragma unroll
+            for (int kb = 0; kb < kKB; ++kb)   // rows are used once per step: do not displace reusable lines
+                kf[tt][kb] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(p + 32 * kb));
         }
-        return c;
     };
-    int code_cur = load_code(0), code_next = load_code(1);
+    auto load_v = [&](int rows) {
+#pragma unroll
+        for (int u = 0; u < kVLoads; ++u)
+            vf[u] = __builtin_nontemporal_load(
+                reinterpret_cast<const half8_t*>(vbase + (int64_t)__shfl(rows, 4 * u + quad, kWave) * sn + row * 8));
+    };
+    load_k(rowid[0]);
+    load_v(rowid[0]);
+
     // query rows -> LDS (zero rows for the padding heads); read back per batch as the A operand
     for (int i = threadIdx.x; i < 16 * (kD / 8); i += kAttnThreads) {
         const int h = i / (kD / 8), c8 = i % (kD / 8);
@@ -96,44 +123,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
                                                   (int64_t)(h_first + h) * a.q_sh + c8 * 8);
         *reinterpret_cast<half8_t*>(&s_q[h][c8 * 8]) = v;
     }
+    if (p0 >= part_len) return;   // block-uniform: nothing of this part lives in this chunk
     __syncthreads();
-
-    auto row_ptr = [&](int c, const T* txt, const T* vis) -> const T* {
-        return c >= 0 ? txt + (int64_t)c * a.txt_sn : vis + (int64_t)(-c - 1) * a.vis_sn;
-    };
-    auto batch_live = [&](int j) -> int {   // live tokens of batch j of this wavefront (0 = none)
-        const int base = t0 + (j * kAttnWaves + wave) * kBatchTokens;
-        return max(0, min(kBatchTokens, tokens.len - base));
-    };
-    half8_t kf[2][kKB];     // K rows: lane (row, quad) holds dims 8*quad + 32*kb .. +8 of tokens row, 16 + row
-    half8_t vf[kVLoads];    // V rows: lane (quad, row) holds dims 8*row .. +8 of tokens 4u + quad
-    auto load_k = [&](int j, int code) {
-        const int n_live = batch_live(j);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const int tl = tt * 16 + row;
-            const int c = __shfl(code, tl, kWave);
-#pragma unroll
-            for (int kb = 0; kb < kKB; ++kb) kf[tt][kb] = 0;
-            if (tl < n_live) {
-                const T* p = row_ptr(c, ktxt, kvis) + quad * 8;
-#pragma unroll
-                for (int kb = 0; kb < kKB; ++kb)   // rows are used once per step: do not displace reusable lines
-                    kf[tt][kb] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(p + 32 * kb));
-            }
-        }
-    };
-    auto load_v = [&](int j, int code) {
-        const int n_live = batch_live(j);
-#pragma unroll
-        for (int u = 0; u < kVLoads; ++u) {
-            const int tl = 4 * u + quad;
-            const int c = __shfl(code, tl, kWave);
-            vf[u] = 0;
-            if (tl < n_live)
-                vf[u] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(row_ptr(c, vtxt, vvis) + row * 8));
-        }
-    };
 
     float4_t acc[8];        // acc[j][r] = out[head 4*quad + r][dim 8*row + j], not normalised
 #pragma unroll
@@ -142,13 +133,10 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; }
 
-    if (batch_live(0) > 0) { load_k(0, code_cur); load_v(0, code_cur); }
-#pragma unroll 1
+#pragma unroll
     for (int j = 0; j < kBatches; ++j) {
-        const int n_live = batch_live(j);
-        if (n_live == 0) break;   // wave-uniform; later batches are empty too
-        const int code_after = load_code(j + 2);
-        const bool more = j + 1 < kBatches && batch_live(j + 1) > 0;
+        const int n_live = part_len - (p0 + (j * kAttnWaves + wave) * kBatchTokens);   // may exceed 32
+        if (n_live <= 0) break;   // wave-uniform; later batches are empty too
         // ---- logits of the 32 tokens: lane (row, quad) gets heads 4*quad + r of tokens row and 16 + row
         float4_t lg[2];
 #pragma unroll
@@ -163,7 +151,7 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) lg[tt][r] = live ? sacc[r] * a.scale : -INFINITY;
         }
-        if (more) load_k(j + 1, code_next);   // K registers are free again
+        if (j + 1 < kBatches) load_k(rowid[j + 1]);   // K registers are free again
         // ---- running softmax statistics; p (fp16) to LDS in the order of the p*V contraction index
         float alpha[4];
 #pragma unroll
@@ -185,7 +173,7 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
         __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
         const half8_t pa = *reinterpret_cast<const half8_t*>(&s_p[wave][row][8 * quad]);
         __builtin_amdgcn_wave_barrier();
-        // ---- acc = acc * alpha + p * V
+        // ---- acc = acc * alpha + p * V   (p = 0 for the tokens past the end, whose rows are clamped copies)
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
             half8_t vb;
@@ -196,11 +184,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             for (int r = 0; r < 4; ++r) c4[r] = acc[jj][r] * alpha[r];
             acc[jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, vb, c4, 0, 0, 0);
         }
-        if (more) load_v(j + 1, code_next);   // V registers are free again
-        code_cur = code_next;
-        code_next = code_after;
+        if (j + 1 < kBatches) load_v(rowid[j + 1]);   // V registers are free again
     }
-    (void)code_cur;
 
     // ---- the wavefront's result to LDS: rows of the valid heads only
 #pragma unroll
@@ -230,7 +215,7 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             x = fmaf(e, s_acc[w][h][d], x);
             l = fmaf(e, s_l[w][h], l);
         }
-        const int64_t ph = ((int64_t)b * a.Hq + h_first + h) * S + s;
+        const int64_t ph = ((int64_t)b * a.Hq + h_first + h) * S + s;   // slot = chunk number
         a.part_acc[ph * kD + d] = x;
         if (d == 0) { a.part_ml[ph * 2] = m; a.part_ml[ph * 2 + 1] = l; }
     }
@@ -248,7 +233,7 @@ hipError_t launch_one(const AttnArgs& a, int hblk, hipStream_t stream) {
 int attn_flash_chunk() { return kFlashChunk; }
 
 hipError_t launch_attn_partial_flash(const AttnArgs& a, hipStream_t stream) {
-    if (a.chunk != kFlashChunk || a.D != kD) return hipErrorInvalidValue;
+    if (a.chunk != kFlashChunk || a.D != kD || a.split_base < 0 || a.split_base > a.n_chunks) return hipErrorInvalidValue;
     const int G = a.G;
     if (G == 1) return launch_one<1>(a, 1, stream);
     if (G == 2) return launch_one<2>(a, 1, stream);

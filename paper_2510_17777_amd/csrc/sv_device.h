@@ -72,31 +72,42 @@ __device__ __forceinline__ float group_sum(float x) {
     return x;
 }
 
+// Cross-row steps of the 64-lane reductions read one lane of each 16-lane row into a scalar
+// register (v_readlane) instead of going through the LDS crossbar (ds_bpermute): measured on
+// the selection kernel, a bpermute step costs over a hundred cycles when 16 wavefronts share a
+// compute unit.
+__device__ __forceinline__ float lane_value(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+
 __device__ __forceinline__ float wave_max(float x) {
     x = fmaxf(x, dpp_move<kDppQuadXor1>(x));
     x = fmaxf(x, dpp_move<kDppQuadXor2>(x));
     x = fmaxf(x, dpp_move<kDppRowHalfMirror>(x));
     x = fmaxf(x, dpp_move<kDppRowMirror>(x));
-    x = fmaxf(x, __shfl_xor(x, 16, kWave));
-    x = fmaxf(x, __shfl_xor(x, 32, kWave));
-    return x;
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float x) {
     x = group_sum<16>(x);
-    x += __shfl_xor(x, 16, kWave);
-    x += __shfl_xor(x, 32, kWave);
-    return x;
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 
-// Inclusive prefix sum over the 64 lanes.
+// Inclusive prefix sum over the 64 lanes: shifts inside each 16-lane row (lanes shifted in from
+// outside the row read 0), then the totals of the rows below.
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        uint32_t y = __shfl_up(x, d, kWave);
-        if (lane >= d) x += y;
-    }
-    return x;
+    constexpr int kRowShr = 0x110;   // row_shr:n is 0x110 + n
+#define SV_SCAN_STEP(n) x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowShr + n, 0xF, 0xF, true)
+    SV_SCAN_STEP(1);
+    SV_SCAN_STEP(2);
+    SV_SCAN_STEP(4);
+    SV_SCAN_STEP(8);
+#undef SV_SCAN_STEP
+    const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 15);
+    const uint32_t t1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 31);
+    const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 47);
+    const int r = lane >> 4;
+    return x + (r > 0 ? t0 : 0u) + (r > 1 ? t1 : 0u) + (r > 2 ? t2 : 0u);
 }
 
 // Monotone map float -> uint32: a < b  <=>  key(a) < key(b); +0 and -0 share a key.

@@ -10,7 +10,7 @@ namespace sv {
 // launch publish, per (b, g), a threshold t_lo (an order statistic of the scores of a small sample
 // of the row) that lies below the k-th largest score with overwhelming probability.  Every scoring
 // workgroup stores the (score bits, row) pairs of its tile with score >= t_lo, in row order: a
-// 512-byte primary record per tile ({count, t_lo used, 0, 0}, then the first 62 pairs; records of
+// 512-byte primary record per tile ({count, t_lo used, largest pair score, 0}, then the first 62 pairs; records of
 // consecutive tiles are adjacent) and, for fuller tiles, pair number f >= 62 at position f of the
 // tile's overflow rows.  The selection ranks those few candidates on chip.  t_lo is only a hint:
 // the selection checks on the device that the candidates determine the kept set (at least k of them
@@ -75,7 +75,10 @@ struct AttnArgs {
     int64_t txt_sb, txt_sh, txt_sn;
     int32_t chunk;            // tokens per workgroup
     int32_t use_mfma;         // fp16 caches: 1 = logits on the matrix cores, 0 = vector FMA path
-    int32_t n_chunks;         // S = ceil((n_txt_max + k) / chunk)
+    int32_t n_chunks;         // S: partial-result slots per query head
+    int32_t split_base;       // < 0: chunks cut the joint list (text, then kept visual tokens), S = ceil((n_txt_max +
+                              // k) / chunk); >= 0: chunks [0, split_base) cut the text tokens, chunks [split_base, S)
+                              // the kept visual tokens
 };
 
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);

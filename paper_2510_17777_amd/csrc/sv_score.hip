@@ -219,7 +219,7 @@ void score_kernel(const ScoreArgs a) {
             hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (a.filt.test_mode != 0 && tile % 3 == 1) t_lo = a.filt.test_mode == 1 ? INFINITY : -INFINITY;
-        // Record of this tile, 8-byte items: {count, t_lo used}, {0, 0}, then the first kFilterPrimary
+        // Record of this tile, 8-byte items: {count, t_lo used}, {largest pair score, 0}, then the first kFilterPrimary
         // pairs in row order; records of consecutive tiles are adjacent.  A tile with more pairs also
         // writes all of them to its overflow rows.  Every store covers whole 128-byte lines (the
         // tail of the last line is zero-filled): a partially written line costs a fetch of the rest.
@@ -229,21 +229,25 @@ void score_kernel(const ScoreArgs a) {
         const int tile_len = row_end - row_begin;
         const uint64_t lanes_below = (1ull << lane) - 1ull;
         uint32_t count = 0;
+        float top = -INFINITY;
         for (int r = lane; r - lane < tile_len; r += kWave) {   // wave-uniform trip count
             const float v = r < tile_len ? s_val[r] : -INFINITY;
             const bool is_cand = r < tile_len && v >= t_lo && v > -INFINITY;
+            if (is_cand) top = fmaxf(top, v);
             const uint64_t cand_lanes = __ballot(is_cand);
             if (is_cand)
                 s_pair[count + (uint32_t)__popcll(cand_lanes & lanes_below)] =
                     make_uint2(__float_as_uint(v), (uint32_t)(row_begin + r));
             count += (uint32_t)__popcll(cand_lanes);
         }
+        top = wave_max(top);
         __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
         {
             const uint32_t items = min(count + 2u, (uint32_t)kFilterPrimary + 2u);
             if ((uint32_t)lane < ((items + 15u) & ~15u)) {
                 uint2 v = make_uint2(0u, 0u);
                 if (lane == 0) v = make_uint2(count, __float_as_uint(t_lo));
+                else if (lane == 1) v = make_uint2(__float_as_uint(top), 0u);
                 else if (lane >= 2 && (uint32_t)lane < items) v = s_pair[lane - 2];
                 rec[lane] = v;
             }

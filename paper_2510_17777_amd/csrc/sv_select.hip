@@ -200,17 +200,28 @@ __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* _
 }
 
 // Exact ranking of the threshold bin's members held in LDS: finds the member with rank
-// need-1 in (score descending, index ascending) order.  Threads stride over members.
+// need-1 in (score descending, index ascending) order.  Threads stride over members; the
+// members are read eight at a time so that a pass costs one LDS round trip, not eight.
 template <int NT>
 __device__ __forceinline__ void rank_candidates(const uint32_t* cand_key, const int32_t* cand_idx, uint32_t n_cand,
                                                 uint32_t need, uint32_t* thr_key, int32_t* thr_idx, int tid) {
+    constexpr uint32_t R = 8;
     for (uint32_t c = tid; c < n_cand; c += NT) {
         const uint32_t my_key = cand_key[c];
         const int32_t my_idx = cand_idx[c];
         uint32_t rank = 0;
-        for (uint32_t u = 0; u < n_cand; ++u) {
-            const uint32_t ok = cand_key[u];
-            rank += (ok > my_key || (ok == my_key && cand_idx[u] < my_idx)) ? 1u : 0u;
+        for (uint32_t u0 = 0; u0 < n_cand; u0 += R) {
+            uint32_t ok[R];
+            int32_t oi[R];
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r) {
+                const uint32_t u = min(u0 + r, n_cand - 1);
+                ok[r] = cand_key[u];
+                oi[r] = cand_idx[u];
+            }
+#pragma unroll
+            for (uint32_t r = 0; r < R; ++r)
+                rank += (u0 + r < n_cand && (ok[r] > my_key || (ok[r] == my_key && oi[r] < my_idx))) ? 1u : 0u;
         }
         if (rank == need - 1) { *thr_key = my_key; *thr_idx = my_idx; }
     }
@@ -245,10 +256,13 @@ struct SingleShared {
 // Exact top-kb of the n <= ITEMS*1024 scores at s (global or LDS) by one 1024-lane workgroup,
 // scores in registers; out[0..kb) receives the kept positions (renamed through `map` when given)
 // in ascending order.  Requires 0 < kb < n.
+// With have_range the caller vouches that lo_hint <= every score and supplies an upper value for the
+// binning (scores above it share the top bin); the workgroup then skips its own min/max pass.
 template <int ITEMS>
 __device__ __forceinline__ void select_block(SingleShared& sh, const float* __restrict__ s, int32_t* __restrict__ out,
                                              int n, int kb, int tid, int lane, int wave,
-                                             const int32_t* map = nullptr) {
+                                             const int32_t* map = nullptr, bool have_range = false,
+                                             float lo_hint = 0.f, float hi_hint = 0.f) {
     constexpr int NT = kSingleThreads, NW = NT / kWave;
     const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
     const int j0 = wave * seg + lane;
@@ -259,17 +273,24 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
     for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? s[j0 + i * kWave] : 0.f;
 
     float lo = FLT_MAX, hi = -FLT_MAX;
+    if (!have_range) {   // block-uniform
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i)
-        if (i < my_items) { const float v = clamp_finite(vals[i]); lo = fminf(lo, v); hi = fmaxf(hi, v); }
-    lo = wave_min_f(lo);
-    hi = wave_max(hi);
-    if (lane == 0) { sh.wave_min[wave] = lo; sh.wave_max[wave] = hi; }
+        for (int i = 0; i < ITEMS; ++i)
+            if (i < my_items) { const float v = clamp_finite(vals[i]); lo = fminf(lo, v); hi = fmaxf(hi, v); }
+        lo = wave_min_f(lo);
+        hi = wave_max(hi);
+        if (lane == 0) { sh.wave_min[wave] = lo; sh.wave_max[wave] = hi; }
+    }
     for (int i = tid; i < kBins; i += NT) sh.rx.hist[i] = 0;
     if (tid == 0) { sh.n_cand = 0; sh.thr_key = 0; sh.thr_idx = -1; }
     __syncthreads();
+    if (have_range) {
+        lo = clamp_finite(lo_hint);
+        hi = clamp_finite(hi_hint);
+    } else {
 #pragma unroll
-    for (int w = 0; w < NW; ++w) { lo = fminf(lo, sh.wave_min[w]); hi = fmaxf(hi, sh.wave_max[w]); }
+        for (int w = 0; w < NW; ++w) { lo = fminf(lo, sh.wave_min[w]); hi = fmaxf(hi, sh.wave_max[w]); }
+    }
     const float inv = (float)kBins / (hi - lo);
     const bool spread = hi > lo && inv > 0.f && inv <= FLT_MAX;   // block-uniform
 
@@ -374,9 +395,10 @@ struct FilteredShared {
     int32_t c_row[kFiltCap];
     uint32_t tile_cnt[kFiltMaxTiles];
     float tile_tlo[kFiltMaxTiles];          // the threshold each tile used
+    float tile_top[kFiltMaxTiles];          // the largest candidate score of each tile
     uint32_t tile_off[kFiltMaxTiles + 1];   // exclusive prefix sums of the tile counts
     uint32_t wave_tot[16];
-    float tlo_min[4], tlo_max[4];
+    float tlo_min[4], tlo_max[4], top_max[4];
     uint32_t n_at_or_above;
 };
 
@@ -413,6 +435,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
             const bool live = w < live_tiles * kFiltRec16;
             sh.tile_cnt[w / kFiltRec16] = live ? min(word[u].x, (uint32_t)f.tile_rows) : 0u;
             sh.tile_tlo[w / kFiltRec16] = live ? __uint_as_float(word[u].y) : 0.f;
+            sh.tile_top[w / kFiltRec16] = live ? __uint_as_float(word[u].z) : -INFINITY;
         }
     }
     if (tid == 0) sh.n_at_or_above = 0;
@@ -422,7 +445,8 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         const float t = sh.tile_tlo[tid];
         const float lo = wave_min_f(tid < live_tiles ? t : INFINITY);
         const float hi = wave_max(tid < live_tiles ? t : -INFINITY);
-        if (lane == 0) { sh.tlo_min[wave] = lo; sh.tlo_max[wave] = hi; }
+        const float top = wave_max(tid < live_tiles ? sh.tile_top[tid] : -INFINITY);
+        if (lane == 0) { sh.tlo_min[wave] = lo; sh.tlo_max[wave] = hi; sh.top_max[wave] = top; }
     }
     const uint32_t incl = block_inclusive_scan<NT>(my_count, sh.wave_tot, lane, wave);
     if (tid < kFiltMaxTiles) sh.tile_off[tid] = incl - my_count;
@@ -487,7 +511,10 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         for (uint32_t i = tid; i < m; i += NT) out[i] = sh.c_row[i];
         return;
     }
-    select_block<kFiltItems>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row);
+    // every candidate is >= its tile's threshold >= t_min, and none exceeds the largest tile maximum
+    const float top = fmaxf(fmaxf(sh.top_max[0], sh.top_max[1]), fmaxf(sh.top_max[2], sh.top_max[3]));
+    const bool have_range = t_min > -INFINITY && top < INFINITY && top > t_min;
+    select_block<kFiltItems>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
 }
 
 // ------------------------------------------------------------------ multi-part shape
