@@ -6,9 +6,9 @@ that is all 28 independent layers folded into the batch dimension (one launch pe
 stage).  Inputs are synthetic, seeded, and resident in HBM before timing starts.
 
 Prints ONE JSON line.  Besides the step latency it carries
-  roofline      the scoring kernel (it moves ~88 % of the step's algorithmic bytes):
-                bytes of visual K per launch / its mean duration measured with HIP
-                events on the launch stream, against the 8 TB/s HBM peak;
+  roofline      the scoring kernel as sv_decode_step launches it (it moves ~88 % of the
+                step's algorithmic bytes): bytes of visual K per launch / its mean duration
+                measured with HIP events on the launch stream, against the 8 TB/s HBM peak;
   cpu_baseline  the CPU oracle (plain C, fp64, OpenMP over independent units) timed on
                 a bounded sample of the same inputs on this host's cores;
   parity        index-set rule statistics (boundary tie counts) and output error of the
@@ -122,15 +122,20 @@ def main():
     wall = time.perf_counter() - t0
     us_per_step = wall / args.steps * 1e6
 
-    # The scoring kernel alone, bracketed by events on the stream it is launched on.
+    # The dominant kernel alone: the scoring launch exactly as the step issues it (the "step_stages"
+    # knob makes sv_decode_step return after it), bracketed by events on the stream it is launched on.
     stream = torch.cuda.current_stream()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for _ in range(args.steps)]
-    for i in range(args.steps):
-        evs[i][0].record(stream)
-        sv.sv_score_visual(shape, queries[i % len(queries)], d["k_vis"], buf.scores, stream)
-        evs[i][1].record(stream)
-    torch.cuda.synchronize()
+    sv.sv_set_tuning("step_stages", 1)
+    try:
+        for i in range(args.steps):
+            evs[i][0].record(stream)
+            step(i)
+            evs[i][1].record(stream)
+        torch.cuda.synchronize()
+    finally:
+        sv.sv_set_tuning("step_stages", 3)
     score_us = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
 
     # Leave the buffers holding the result of a step with query 0 for the parity report.

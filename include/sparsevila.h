@@ -177,6 +177,8 @@ const char *sv_strerror(sv_status status);
  *                           few or too many candidates makes the row fall back to the full selection)
  *   "filter_test_mode"      0; 1 / 2 make every third tile of the scoring kernel ignore the threshold and hand
  *                           over none / all of its scores (tests of the selection's consistency check)
+ *   "step_stages"           measurement aid: sv_decode_step returns after its first 1 (scoring launch) or 2
+ *                           (scoring and selection) stages instead of all 3; the later outputs stay unwritten
  * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
  * Process-wide; not thread-safe against concurrent calls.  scores, idx and count never depend on
  * the knobs; out and lse depend on them only through fp32 summation order in step 3 and, for

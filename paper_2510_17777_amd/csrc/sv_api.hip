@@ -24,6 +24,7 @@ struct Tuning {
     int32_t select_filter = -1;         // -1 = default
     int32_t filter_rank = 0;            // 0 = derived from k / n
     int32_t filter_test_mode = 0;
+    int32_t step_stages = 3;            // measurement aid: sv_decode_step stops after this many stages
 };
 Tuning g_tuning;
 std::atomic<uint32_t> g_epoch{0x5eed0001u};   // tags the threshold words of one sv_decode_step call
@@ -274,6 +275,7 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
         }
         hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
+        if (g_tuning.step_stages < 2) return SV_OK;
         const sv::SelectArgs sel = make_select_args(s, w, workspace, sc, idx, count);
         e = filter ? sv::launch_select_filtered(sel, sa, hs) : sv::launch_select(sel, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
@@ -282,6 +284,7 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
         hipError_t e = sv::launch_select(make_select_args(s, w, workspace, scores, idx, count), hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     }
+    if (g_tuning.step_stages < 3) return SV_OK;
     const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
     return from_hip(sv::launch_attend(a, hs));
 }
@@ -342,6 +345,11 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.filter_test_mode = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "step_stages")) {
+        if (value < 1 || value > 3) return SV_ERR_SHAPE;
+        g_tuning.step_stages = value;
+        return SV_OK;
+    }
     return SV_ERR_SHAPE;
 }
 
@@ -357,6 +365,7 @@ int32_t sv_get_tuning(const char* name) {
         return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
     if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;
     if (!std::strcmp(name, "filter_test_mode")) return g_tuning.filter_test_mode;
+    if (!std::strcmp(name, "step_stages")) return g_tuning.step_stages;
     return -1;
 }
 
