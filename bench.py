@@ -43,6 +43,65 @@ def measured_traffic(cfg: int):
     return None
 
 
+def time_variants(sv, torch, w, d, shape, buf, reps):
+    """Event-timed variants around the step (all on the workload's own tensors, idx/count as the step left them):
+    gathered attention per decoded token, packing + attention on the packed rows (the paper's once-per-round
+    retrieval, section 3.2), dense attention over the whole cache (the baseline of the paper's kernel-level
+    comparison, section 4.5), and the whole step for a sweep of keep ratios."""
+    dev = d["q"].device
+    stream = torch.cuda.current_stream()
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        return round(float(np.median([a.elapsed_time(b) * 1e3 for a, b in evs])), 2)
+
+    out = {}
+    out["attn_gathered_us"] = timed(lambda: sv.sv_sparse_decode_attn(
+        shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], buf.idx, buf.count, buf.out, buf.lse,
+        buf.workspace))
+    B, Hkv, D, k = shape.batch, shape.n_kv_heads, shape.head_dim, shape.k
+    k_pack = torch.empty((B, Hkv, k, D), dtype=d["k_vis"].dtype, device=dev)
+    v_pack = torch.empty_like(k_pack)
+    out["pack_us"] = timed(lambda: sv.sv_pack_selected(shape, d["k_vis"], d["v_vis"], buf.idx, buf.count,
+                                                       k_pack, v_pack))
+    pshape = sv.make_shape(d["q"], k_pack, d["k_txt"], k, txt_len=shape.txt_len)
+    pbuf = sv.DecodeBuffers(pshape, dev, with_scores=False)
+    out["attn_packed_us"] = timed(lambda: sv.sv_sparse_decode_attn(
+        pshape, d["q"], k_pack, v_pack, d["k_txt"], d["v_txt"], None, buf.count, pbuf.out, pbuf.lse, pbuf.workspace))
+    out["packed_equals_gathered_max_abs"] = float((pbuf.out - buf.out).abs().max())
+    if shape.vis_len is None:   # dense baseline and sweep: uniform visual length only
+        Nv = shape.n_vis_max
+        dshape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], Nv, txt_len=shape.txt_len)
+        dbuf = sv.DecodeBuffers(dshape, dev, with_scores=False)
+        dbuf.count.fill_(Nv)
+        out["attn_dense_us"] = timed(lambda: sv.sv_sparse_decode_attn(
+            dshape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], None, dbuf.count, dbuf.out, dbuf.lse,
+            dbuf.workspace))
+        del dbuf
+        sweep = []
+        for keep in (0.5, 0.25, 0.10, 0.05, 0.02):
+            kk = max(1, int(round(Nv * keep)))
+            s2 = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], kk, txt_len=shape.txt_len)
+            b2 = sv.DecodeBuffers(s2, dev, with_scores=False)
+            step_us = timed(lambda: sv.sv_decode_step(s2, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"],
+                                                      None, b2.idx, b2.count, b2.out, b2.lse, b2.workspace))
+            attn_us = timed(lambda: sv.sv_sparse_decode_attn(s2, d["q"], d["k_vis"], d["v_vis"], d["k_txt"],
+                                                             d["v_txt"], b2.idx, b2.count, b2.out, b2.lse,
+                                                             b2.workspace))
+            sweep.append({"keep": keep, "k": kk, "step_us": step_us, "attn_us": attn_us,
+                          "dense_attn_over_sparse_attn": round(out["attn_dense_us"] / attn_us, 2)})
+            del b2
+        out["sweep"] = sweep
+    return out
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +116,10 @@ def parse_args():
                          "to learn what FETCH_SIZE / WRITE_SIZE report for a known size)")
     ap.add_argument("--keep-scores", action="store_true",
                     help="hand sv_decode_step a scores buffer (it then also stores all 22 MB of scores per step)")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time, on the same inputs, the paper's retrieve-once use (pack the kept rows, then "
+                         "attention on the packed buffers), the dense baseline and a sweep of keep ratios; adds a "
+                         "\"variants\" object to the JSON line")
     ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
                     help="launch-shape knob for sweeps, e.g. --set attn_chunk=256")
     return ap.parse_args()
@@ -166,6 +229,9 @@ def main():
                      "mean_us": round(float(score_us.mean()), 2), "median_us": round(float(np.median(score_us)), 2)},
         "input_gen_s": round(t_gen, 1),
     }
+
+    if args.variants:
+        result["variants"] = time_variants(sv, torch, w, d, shape, buf, args.steps)
 
     if args.oracle_layers > 0:
         import oracle

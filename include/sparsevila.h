@@ -131,7 +131,9 @@ sv_status sv_topk_select(const sv_shape *shape, const float *scores,
  * The caller appends the current token's own K/V to the text segment before the
  * call; there is no mask and no rotary embedding inside.  idx entries must lie
  * in [0, vis_len[b]); count[b,g] <= k.  With k == 0, idx and count may be NULL
- * (text-only attention).  A (b,g) with no token at all yields out = 0 and
+ * (text-only attention).  With k > 0 and idx == NULL the visual segment is taken as
+ * PACKED: its rows 0..count[b,g) are the kept tokens (see sv_pack_selected; pass the
+ * packed buffers as k_vis/v_vis with n_vis_max = k).  A (b,g) with no token at all yields out = 0 and
  * lse = -inf.  lse may be NULL.  Accumulation is fp32; T is processed in
  * chunks whose partial results are merged by a second pass.
  */
@@ -141,6 +143,21 @@ sv_status sv_sparse_decode_attn(const sv_shape *shape, const void *q,
                                 const int32_t *idx, const int32_t *count,
                                 float *out, float *lse,
                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Packing (section 3.2: the selected visual KV entries are packed into a contiguous
+ * region, so that the attention of the tokens decoded afterwards reads no irregular
+ * pattern).  k_pack/v_pack are dense DEVICE buffers [B, Hkv, k, D] of the shape's dtype:
+ *   k_pack[b,g,i,:] = k_vis[b,g,idx[b,g,i],:],  v_pack likewise,  for i < count[b,g];
+ * rows count[b,g] <= i < k are zero-filled.  A byte-exact copy.  The paper's use, one
+ * retrieval per conversation round: sv_score_visual + sv_topk_select + sv_pack_selected
+ * once, then per decoded token sv_sparse_decode_attn on the packed buffers (shape with
+ * n_vis_max = k and contiguous visual strides, idx = NULL, the same count).
+ * Only the visual fields, k and dtype of the shape are used; k == 0 does nothing.
+ */
+sv_status sv_pack_selected(const sv_shape *shape, const void *k_vis, const void *v_vis,
+                           const int32_t *idx, const int32_t *count,
+                           void *k_pack, void *v_pack, void *stream);
 
 /*
  * Steps 1 -> 2 -> 3 on one stream.  scores may be NULL (the workspace then

@@ -170,3 +170,23 @@ def decode_step(q, k_vis, v_vis, k_txt, v_txt, k: int, vis_len=None, txt_len=Non
     if rc:
         raise ValueError(f"svo_decode_step failed: {rc}")
     return dict(scores=scores, idx=idx, count=cnt, out=out, lse=lse, wsum=wsum)
+
+
+def pack_selected(k_vis, v_vis, idx, count):
+    """Packing of the kept rows (paper section 3.2: the selected visual KV entries are packed into a
+    contiguous region), written out as its definition with plain loops:
+    k_pack[b,g,i,:] = k_vis[b,g,idx[b,g,i],:] for i < count[b,g], zero rows after that."""
+    k_vis, v_vis = _c(k_vis), _c(v_vis)
+    idx, count = _c(idx, np.int32), _c(count, np.int32)
+    B, Hkv, Nv, D = k_vis.shape
+    k = idx.shape[2]
+    k_pack = np.zeros((B, Hkv, k, D), dtype=k_vis.dtype)
+    v_pack = np.zeros((B, Hkv, k, D), dtype=v_vis.dtype)
+    for b in range(B):
+        for g in range(Hkv):
+            for i in range(int(count[b, g])):
+                j = int(idx[b, g, i])
+                assert 0 <= j < Nv
+                k_pack[b, g, i, :] = k_vis[b, g, j, :]
+                v_pack[b, g, i, :] = v_vis[b, g, j, :]
+    return k_pack, v_pack

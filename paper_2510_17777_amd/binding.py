@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.sv_sparse_decode_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sv_decode_step.restype = ctypes.c_int
     lib.sv_decode_step.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sv_pack_selected.restype = ctypes.c_int
+    lib.sv_pack_selected.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.sv_copy_bytes.restype = ctypes.c_int
     lib.sv_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.sv_strerror.restype = ctypes.c_char_p
@@ -205,6 +207,11 @@ def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, cou
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
         _stream(stream)), "sv_decode_step")
+
+
+def sv_pack_selected(shape: Shape, k_vis, v_vis, idx, count, k_pack, v_pack, stream=None) -> None:
+    _check(load_library().sv_pack_selected(ctypes.byref(shape.c), _ptr(k_vis), _ptr(v_vis), _ptr(idx), _ptr(count),
+                                           _ptr(k_pack), _ptr(v_pack), _stream(stream)), "sv_pack_selected")
 
 
 def sv_copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None) -> None:

@@ -172,9 +172,10 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
 sv_status check_attn_pointers(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
                               const void* k_txt, const void* v_txt, const int32_t* idx,
                               const int32_t* count, const float* out) {
+    (void)idx;   // NULL with k > 0: the visual segment is packed
     if (!q || !out) return SV_ERR_NULL;
     const bool has_vis = kept_max(s) > 0;
-    if (has_vis && (!k_vis || !v_vis || !idx || !count)) return SV_ERR_NULL;
+    if (has_vis && (!k_vis || !v_vis || !count)) return SV_ERR_NULL;   // idx == NULL: packed visual segment
     if (s->n_txt_max > 0 && (!k_txt || !v_txt)) return SV_ERR_NULL;
     if (!aligned16(q)) return SV_ERR_ALIGN;
     if (has_vis && (!aligned16(k_vis) || !aligned16(v_vis))) return SV_ERR_ALIGN;
@@ -287,6 +288,23 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
     if (g_tuning.step_stages < 3) return SV_OK;
     const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
     return from_hip(sv::launch_attend(a, hs));
+}
+
+sv_status sv_pack_selected(const sv_shape* s, const void* k_vis, const void* v_vis, const int32_t* idx,
+                           const int32_t* count, void* k_pack, void* v_pack, void* stream) {
+    sv_status st = check_shape(s, kNeedVis);
+    if (st != SV_OK) return st;
+    if (s->k == 0) return SV_OK;
+    if (!idx || !count || !k_pack || !v_pack) return SV_ERR_NULL;
+    if (s->n_vis_max == 0) return SV_ERR_SHAPE;
+    if (!k_vis || !v_vis) return SV_ERR_NULL;
+    if (!aligned16(k_vis) || !aligned16(v_vis) || !aligned16(k_pack) || !aligned16(v_pack)) return SV_ERR_ALIGN;
+    sv::PackArgs a{};
+    a.k_vis = k_vis; a.v_vis = v_vis; a.idx = idx; a.count = count; a.k_pack = k_pack; a.v_pack = v_pack;
+    a.B = s->batch; a.Hkv = s->n_kv_heads; a.n_vis_max = s->n_vis_max; a.k = s->k;
+    a.elem = elem_size(s->dtype); a.row_bytes = s->head_dim * a.elem;
+    a.vis_sb = s->kv_vis_stride_b; a.vis_sh = s->kv_vis_stride_h; a.vis_sn = s->kv_vis_stride_n;
+    return from_hip(sv::launch_pack(a, static_cast<hipStream_t>(stream)));
 }
 
 sv_status sv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {

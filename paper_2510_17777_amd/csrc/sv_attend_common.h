@@ -36,7 +36,7 @@ struct TokenList {
     __device__ __forceinline__ int64_t offset(int t, bool& is_txt) const {
         is_txt = t < nt;
         if (is_txt) return (int64_t)t * txt_sn;
-        int j = idx_row[t - nt];
+        int j = idx_row ? idx_row[t - nt] : t - nt;   // no idx: the visual segment is packed
         j = j < 0 ? 0 : (j < n_vis_max ? j : n_vis_max - 1);   // a faulty idx must not fault the GPU
         return (int64_t)j * vis_sn;
     }

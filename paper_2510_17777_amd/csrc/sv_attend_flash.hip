@@ -78,7 +78,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
         for (int j = 0; j < kBatches; ++j) {
             const int p = p0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
             int r = p;
-            if (!is_txt) r = idx_row[min(p, a.k - 1)];   // slots past count hold -1: clamped below
+            if (!is_txt && a.idx) r = idx_row[min(p, a.k - 1)];   // slots past count hold -1: clamped below;
+                                                                    // no idx: the visual segment is packed
             rowid[j] = r < 0 ? 0 : (r < row_cap ? r : row_cap - 1);   // a faulty idx must not fault the GPU
         }
     }

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kNT) void attn_partial_mfma_kernel(const AttnArgs a
                 if (t < tokens.nt) {
                     my_code = t;
                 } else {
-                    int j = tokens.idx_row[t - tokens.nt];
+                    int j = tokens.idx_row ? tokens.idx_row[t - tokens.nt] : t - tokens.nt;
                     j = j < 0 ? 0 : (j < a.n_vis_max ? j : a.n_vis_max - 1);   // a faulty idx must not fault the GPU
                     my_code = -j - 1;
                 }

@@ -60,7 +60,7 @@ struct AttnArgs {
     const void* q;
     const void* k_vis; const void* v_vis;
     const void* k_txt; const void* v_txt;
-    const int32_t* idx;       // [B, Hkv, k] or nullptr when k == 0
+    const int32_t* idx;       // [B, Hkv, k]; nullptr: k == 0, or the visual segment is packed (token i is row i)
     const int32_t* count;     // [B, Hkv]    or nullptr when k == 0
     const int32_t* txt_len;   // device [B] or nullptr
     float* part_acc;          // [B, Hq, S, D]  un-normalised chunk outputs
@@ -81,7 +81,20 @@ struct AttnArgs {
                               // the kept visual tokens
 };
 
+struct PackArgs {
+    const void* k_vis; const void* v_vis;
+    const int32_t* idx;       // [B, Hkv, k]
+    const int32_t* count;     // [B, Hkv]
+    void* k_pack; void* v_pack;   // dense [B, Hkv, k, D]
+    int32_t B, Hkv, n_vis_max, k;
+    int32_t elem;             // bytes per element
+    int32_t row_bytes;        // D * elem, a multiple of 16 that divides 4096
+    int64_t vis_sb, vis_sh, vis_sn;   // element strides of the source
+    int32_t rows_per_block;   // set by the launcher
+};
+
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
+hipError_t launch_pack(const PackArgs& a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials + combine
 

@@ -36,7 +36,7 @@ def good_shape(**kw) -> SvShape:
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("sv_score_visual", "sv_topk_select", "sv_sparse_decode_attn", "sv_decode_step",
-                 "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
+                 "sv_pack_selected", "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
         assert must in names
 
 
@@ -118,7 +118,7 @@ def test_null_and_misaligned_pointers_are_rejected():
     assert lib.sv_topk_select(sp, FAKE, FAKE, None, None, 0, None) == E_NULL
     assert lib.sv_topk_select(sp, None, FAKE, FAKE, None, 0, None) == E_NULL
     args = [FAKE] * 9
-    for missing in (0, 1, 2, 3, 4, 5, 6, 7):          # q, k_vis, v_vis, k_txt, v_txt, idx, count, out
+    for missing in (0, 1, 2, 3, 4, 6, 7):             # q, k_vis, v_vis, k_txt, v_txt, (idx: NULL = packed), count, out
         a = list(args)
         a[missing] = None
         a[8] = None                                    # lse is optional
@@ -126,6 +126,14 @@ def test_null_and_misaligned_pointers_are_rejected():
     a = [FAKE] * 8 + [None]
     a[2] = FAKE + 4
     assert lib.sv_sparse_decode_attn(sp, *a, FAKE, 1 << 40, None) == E_ALIGN
+    pk = [FAKE] * 6                                    # k_vis, v_vis, idx, count, k_pack, v_pack
+    for missing in range(6):
+        a = list(pk)
+        a[missing] = None
+        assert lib.sv_pack_selected(sp, *a, None) == E_NULL, missing
+    a = list(pk)
+    a[4] = FAKE + 8
+    assert lib.sv_pack_selected(sp, *a, None) == E_ALIGN
 
 
 def test_workspace_is_checked():

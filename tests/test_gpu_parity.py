@@ -332,3 +332,39 @@ def test_tuning_knobs_change_launch_shape_not_results():
         sv.sv_set_tuning("score_stream_loads", -1)
         sv.sv_set_tuning("attn_mfma", -1)
 
+
+
+# ------------------------------------------------------------------ packing (retrieve once per round, decode many tokens)
+@pytest.mark.parametrize("dtype,D,G", [(np.float16, 128, 7), (np.float16, 64, 4), (np.float32, 128, 2), (np.float32, 64, 1)])
+def test_pack_selected_is_a_byte_exact_gather_and_packed_attention_matches(dtype, D, G):
+    """sv_pack_selected against the oracle's definition (bit-exact: a copy), then the paper's use of it:
+    sv_sparse_decode_attn on the packed buffers with idx = NULL for several fresh queries, each against
+    the oracle's attention over the full cache with the same kept set."""
+    import paper_2510_17777_amd as sv
+    Hkv, B, Nv, Nt, k = 2, 3, 3000, 150, 333
+    inp = rand_inputs(55 + D + G, B, Hkv * G, Hkv, D, Nv, Nt, dtype)
+    vis_len = np.array([Nv, 200, 0], np.int32)
+    r = run_step(inp, k, vis_len=vis_len)
+    want_k, want_v = oracle.pack_selected(inp["k_vis"], inp["v_vis"], r["idx"], r["count"])
+    d, buf, shape = r["dev"], r["buf"], r["shape"]
+    tdt = torch.float16 if dtype == np.float16 else torch.float32
+    k_pack = torch.full((B, Hkv, k, D), 7, dtype=tdt, device="cuda:0")
+    v_pack = torch.full((B, Hkv, k, D), 7, dtype=tdt, device="cuda:0")
+    sv.sv_pack_selected(shape, d["k_vis"], d["v_vis"], buf.idx, buf.count, k_pack, v_pack)
+    torch.cuda.synchronize()
+    assert np.array_equal(k_pack.cpu().numpy().view(np.uint8), want_k.view(np.uint8))
+    assert np.array_equal(v_pack.cpu().numpy().view(np.uint8), want_v.view(np.uint8))
+    pshape = sv.make_shape(d["q"], k_pack, d["k_txt"], k)          # visual segment = the packed rows, n_vis_max = k
+    pbuf = sv.DecodeBuffers(pshape, "cuda:0")
+    rng = np.random.default_rng(9)
+    tol = out_tolerance(dtype)
+    for _ in range(3):                                             # tokens decoded after the retrieval
+        qn = rng.standard_normal(inp["q"].shape, dtype=np.float32).astype(dtype)
+        qd = torch.from_numpy(qn).to("cuda:0")
+        sv.sv_sparse_decode_attn(pshape, qd, k_pack, v_pack, d["k_txt"], d["v_txt"], None, buf.count,
+                                 pbuf.out, pbuf.lse, pbuf.workspace)
+        torch.cuda.synchronize()
+        oa, ol, _ = oracle.sparse_decode_attn(qn, inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"],
+                                              r["idx"], r["count"])
+        assert np.abs(pbuf.out.cpu().numpy() - oa).max() <= tol
+        assert np.abs(pbuf.lse.cpu().numpy() - ol).max() <= tol

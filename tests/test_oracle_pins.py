@@ -362,3 +362,26 @@ def test_sparse_step_differs_from_dense_and_keeps_exactly_the_selected_rows():
         import scipy.special
         w = scipy.special.softmax(keys @ c["q"][0, h].astype(np.float64) / 4.0)
         np.testing.assert_allclose(r["out"][0, h], w @ vals, atol=1e-13)
+
+
+# ------------------------------------------------------------------ packing (section 3.2: contiguous packed region)
+def test_packing_is_numpy_take_and_attention_over_the_packed_rows_is_unchanged():
+    """Pins of oracle.pack_selected: (1) it equals numpy's take_along_axis (a library gather) with
+    zero rows past count; (2) attention over the packed segment with the identity index list equals
+    attention over the full cache with idx -- the statement that packing changes the layout only."""
+    rng = np.random.default_rng(314)
+    B, Hq, Hkv, D, Nv, Nt, k = 2, 6, 2, 64, 97, 13, 20
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    q, kv, vv, kt, vt = f(B, Hq, D), f(B, Hkv, Nv, D), f(B, Hkv, Nv, D), f(B, Hkv, Nt, D), f(B, Hkv, Nt, D)
+    vis_len = np.array([Nv, 11], np.int32)
+    st = oracle.decode_step(q, kv, vv, kt, vt, k, vis_len=vis_len)
+    idx, cnt = st["idx"], st["count"]
+    assert list(cnt[:, 0]) == [20, 11]
+    kp, vp = oracle.pack_selected(kv, vv, idx, cnt)
+    safe = np.where(idx < 0, 0, idx)
+    live = (np.arange(k)[None, None, :] < cnt[:, :, None])[..., None]
+    assert np.array_equal(kp, np.where(live, np.take_along_axis(kv, safe[..., None], axis=2), 0))
+    assert np.array_equal(vp, np.where(live, np.take_along_axis(vv, safe[..., None], axis=2), 0))
+    ident = np.broadcast_to(np.arange(k, dtype=np.int32), (B, Hkv, k)).copy()
+    out_p, lse_p, _ = oracle.sparse_decode_attn(q, kp, vp, kt, vt, ident, cnt)
+    assert np.abs(out_p - st["out"]).max() < 1e-13 and np.abs(lse_p - st["lse"]).max() < 1e-13
