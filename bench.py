@@ -76,6 +76,27 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
     out["attn_packed_us"] = timed(lambda: sv.sv_sparse_decode_attn(
         pshape, d["q"], k_pack, v_pack, d["k_txt"], d["v_txt"], None, buf.count, pbuf.out, pbuf.lse, pbuf.workspace))
     out["packed_equals_gathered_max_abs"] = float((pbuf.out - buf.out).abs().max())
+    if d["q"].dtype == torch.float16 and shape.n_txt_max >= 32:
+        # once-per-round retrieval with a 32-token question (attention mass), then the unchanged selection
+        Tq = 32
+        g = torch.Generator(device=dev)
+        g.manual_seed(20251017)
+        qm = torch.randn((B, Tq, shape.n_q_heads, D), device=dev, dtype=torch.float32, generator=g).to(torch.float16)
+        mscores = torch.empty((B, Hkv, shape.n_vis_max), dtype=torch.float32, device=dev)
+        mws = sv.sv_score_visual_mass(shape, qm, d["k_vis"], d["k_txt"], mscores)
+        out["retrieval_mass_32tok_us"] = timed(lambda: sv.sv_score_visual_mass(shape, qm, d["k_vis"], d["k_txt"],
+                                                                               mscores, None, mws))
+        rows = Tq * (shape.n_q_heads // Hkv)
+        keys = int(shape.n_vis_max if shape.vis_len is None else shape.vis_len.sum().item() / B)
+        flop = 2.0 * 2 * B * Hkv * rows * (keys + shape.n_txt_max) * D      # two passes of QK^T
+        out["retrieval_mass_TFLOPs"] = round(flop / (out["retrieval_mass_32tok_us"] * 1e-6) / 1e12, 1)
+        out["retrieval_mass_Gexp_per_s"] = round(2.0 * B * Hkv * rows * keys / (out["retrieval_mass_32tok_us"] * 1e-6) / 1e9, 1)
+        out["select_after_mass_us"] = timed(lambda: sv.sv_topk_select(shape, mscores, buf.idx, buf.count, buf.workspace))
+        # leave idx/count as the step produced them for whatever follows
+        sv.sv_decode_step(shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], None, buf.idx, buf.count,
+                          buf.out, buf.lse, buf.workspace)
+        torch.cuda.synchronize()
+        del qm, mscores, mws
     if shape.vis_len is None:   # dense baseline and sweep: uniform visual length only
         Nv = shape.n_vis_max
         dshape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], Nv, txt_len=shape.txt_len)

@@ -145,6 +145,33 @@ sv_status sv_sparse_decode_attn(const sv_shape *shape, const void *q,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Step 1 as the paper runs it, once per conversation round, with the whole question as the
+ * query (section 3.2, "Query-Aware Token Selection": the aggregate attention strength
+ * between the query embeddings and the visual entries of the KV cache; section 3.1,
+ * "Efficient Implementation": softmax normalisation and salience accumulation are streamed,
+ * the attention matrix is never formed).  q_multi holds the n_query_tokens tokens of the
+ * question, [B, Tq, Hq, D] fp16 addressed with q_stride_b, q_stride_t (ELEMENTS, a multiple
+ * of 8) and q_stride_h.  The question's tokens are the LAST Tq rows of the text segment
+ * (query token i is text row txt_len[b] - Tq + i); row (i, h) attends, as in the model, to
+ * the text rows up to and including its own and to every visual row j < vis_len[b], with one
+ * softmax over all of them, logits scale * <q, key>.  Then
+ *   scores[b,g,j] = sum_{i < Tq} sum_{h in group g} softmax_(i,h)[j]     (attention mass),
+ * -inf for vis_len[b] <= j < n_vis_max, and lse[b,i,h] (optional output, [B, Tq, Hq]) is the
+ * log of the row's normaliser.  The scores feed sv_topk_select unchanged.  fp16 only
+ * (SV_ERR_DTYPE otherwise); Tq * (Hq / Hkv) <= 256 (SV_ERR_SHAPE otherwise; the mass is
+ * additive over groups of query tokens).  k is ignored.  The workspace must hold
+ * sv_mass_workspace_bytes(shape, Tq) bytes.
+ * For the sum-of-logits aggregate of a multi-token query no separate call is needed: the sum
+ * is linear, so sv_score_visual on a shape whose query heads are the Tq * Hq rows (grouped
+ * per kv head) gives it.
+ */
+size_t sv_mass_workspace_bytes(const sv_shape *shape, int32_t n_query_tokens);
+sv_status sv_score_visual_mass(const sv_shape *shape, const void *q_multi, int32_t n_query_tokens,
+                               int64_t q_stride_t, const void *k_vis, const void *k_txt,
+                               float *scores, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Packing (section 3.2: the selected visual KV entries are packed into a contiguous
  * region, so that the attention of the tokens decoded afterwards reads no irregular
  * pattern).  k_pack/v_pack are dense DEVICE buffers [B, Hkv, k, D] of the shape's dtype:

@@ -190,3 +190,42 @@ def pack_selected(k_vis, v_vis, idx, count):
                 k_pack[b, g, i, :] = k_vis[b, g, j, :]
                 v_pack[b, g, i, :] = v_vis[b, g, j, :]
     return k_pack, v_pack
+
+
+def score_visual_mass(q_multi, k_vis, k_txt, vis_len=None, txt_len=None, scale: Optional[float] = None):
+    """Attention mass of a multi-token query on every visual key (paper section 3.2, "Query-Aware Token
+    Selection": aggregate attention strength between the query embeddings and the visual entries of the
+    KV cache), written out as its definition in float64 with the attention matrix formed explicitly:
+    row (i, h) -- query token i (text row txt_len - Tq + i), head h -- takes one softmax over the text
+    rows up to and including its own and all live visual rows; mass[b,g,j] is the sum of the rows'
+    probabilities of visual key j over the query tokens and the heads of group g.
+    Returns (mass [B,Hkv,Nv] float64 with -inf past vis_len, lse [B,Tq,Hq] float64)."""
+    q = _c(q_multi).astype(np.float64)
+    kv = _c(k_vis).astype(np.float64)
+    kt = _c(k_txt).astype(np.float64)
+    B, Tq, Hq, D = q.shape
+    _, Hkv, Nv, _ = kv.shape
+    Nt = kt.shape[2]
+    G = Hq // Hkv
+    sc = default_scale(D) if scale is None else scale
+    vl = np.full(B, Nv) if vis_len is None else np.asarray(vis_len)
+    tl = np.full(B, Nt) if txt_len is None else np.asarray(txt_len)
+    mass = np.full((B, Hkv, Nv), -np.inf)
+    lse = np.full((B, Tq, Hq), np.inf)
+    for b in range(B):
+        nv, nt = int(vl[b]), int(tl[b])
+        mass[b, :, :nv] = 0.0
+        for i in range(Tq):
+            n_seen_txt = min(max(nt - Tq + i + 1, 0), nt)
+            for h in range(Hq):
+                g = h // G
+                logit_t = sc * (kt[b, g, :n_seen_txt] @ q[b, i, h])
+                logit_v = sc * (kv[b, g, :nv] @ q[b, i, h])
+                allv = np.concatenate([logit_t, logit_v])
+                if allv.size == 0:
+                    continue
+                m = allv.max()
+                z = np.exp(allv - m).sum()
+                lse[b, i, h] = m + np.log(z)
+                mass[b, g, :nv] += np.exp(logit_v - m) / z
+    return mass, lse

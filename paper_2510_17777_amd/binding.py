@@ -69,6 +69,10 @@ def load_library() -> ctypes.CDLL:
     lib.sv_sparse_decode_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sv_decode_step.restype = ctypes.c_int
     lib.sv_decode_step.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sv_mass_workspace_bytes.restype = sz
+    lib.sv_mass_workspace_bytes.argtypes = [P, i32]
+    lib.sv_score_visual_mass.restype = ctypes.c_int
+    lib.sv_score_visual_mass.argtypes = [P, vp, i32, ctypes.c_int64, vp, vp, vp, vp, vp, sz, vp]
     lib.sv_pack_selected.restype = ctypes.c_int
     lib.sv_pack_selected.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.sv_copy_bytes.restype = ctypes.c_int
@@ -207,6 +211,18 @@ def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, cou
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
         _stream(stream)), "sv_decode_step")
+
+
+def sv_score_visual_mass(shape: Shape, q_multi, k_vis, k_txt, scores, lse=None, workspace=None, stream=None):
+    """q_multi [B, Tq, Hq, D] (any strides with D contiguous); shape built from q_multi[:, 0]."""
+    Tq = q_multi.shape[1]
+    if workspace is None:
+        nbytes = int(load_library().sv_mass_workspace_bytes(ctypes.byref(shape.c), Tq))
+        workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q_multi.device)
+    _check(load_library().sv_score_visual_mass(
+        ctypes.byref(shape.c), _ptr(q_multi), Tq, q_multi.stride(1), _ptr(k_vis), _ptr(k_txt), _ptr(scores),
+        _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)), "sv_score_visual_mass")
+    return workspace
 
 
 def sv_pack_selected(shape: Shape, k_vis, v_vis, idx, count, k_pack, v_pack, stream=None) -> None:

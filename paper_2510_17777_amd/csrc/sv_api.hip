@@ -290,6 +290,43 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
     return from_hip(sv::launch_attend(a, hs));
 }
 
+size_t sv_mass_workspace_bytes(const sv_shape* s, int32_t n_query_tokens) {
+    if (check_shape(s, 0) != SV_OK || n_query_tokens < 1) return 0;
+    const size_t lse = align_up((size_t)s->batch * n_query_tokens * s->n_q_heads * sizeof(float));
+    const size_t part = align_up(sv::mass_workspace_bytes(s->batch, s->n_kv_heads, s->n_txt_max, s->n_vis_max));
+    return lse + part + kAlign;
+}
+
+sv_status sv_score_visual_mass(const sv_shape* s, const void* q_multi, int32_t n_query_tokens, int64_t q_stride_t,
+                               const void* k_vis, const void* k_txt, float* scores, float* lse, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    if (st != SV_OK) return st;
+    if (s->dtype != SV_F16) return SV_ERR_DTYPE;
+    const int G = s->n_q_heads / s->n_kv_heads;
+    if (n_query_tokens < 1 || (int64_t)n_query_tokens * G > sv::mass_max_rows()) return SV_ERR_SHAPE;
+    if (q_stride_t < 0 || (q_stride_t * 2) % 16) return q_stride_t < 0 ? SV_ERR_SHAPE : SV_ERR_ALIGN;
+    if (s->n_vis_max == 0) return SV_OK;
+    if (!q_multi || !k_vis || !scores || (s->n_txt_max > 0 && !k_txt)) return SV_ERR_NULL;
+    if (!aligned16(q_multi) || !aligned16(k_vis) || (s->n_txt_max > 0 && !aligned16(k_txt))) return SV_ERR_ALIGN;
+    const size_t lse_bytes = align_up((size_t)s->batch * n_query_tokens * s->n_q_heads * sizeof(float));
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign ||
+        workspace_bytes < sv_mass_workspace_bytes(s, n_query_tokens))
+        return SV_ERR_WORKSPACE;
+    sv::MassArgs a{};
+    a.q = q_multi; a.k_vis = k_vis; a.k_txt = k_txt; a.vis_len = s->vis_len; a.txt_len = s->txt_len;
+    a.scores = scores;
+    a.lse = lse ? lse : reinterpret_cast<float*>(workspace);
+    a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + lse_bytes);
+    a.B = s->batch; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads; a.G = G; a.D = s->head_dim;
+    a.Tq = n_query_tokens; a.n_vis_max = s->n_vis_max; a.n_txt_max = s->n_txt_max;
+    a.scale = effective_scale(s);
+    a.q_sb = s->q_stride_b; a.q_st = q_stride_t; a.q_sh = s->q_stride_h;
+    a.vis_sb = s->kv_vis_stride_b; a.vis_sh = s->kv_vis_stride_h; a.vis_sn = s->kv_vis_stride_n;
+    a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
+    return from_hip(sv::launch_mass(a, static_cast<hipStream_t>(stream)));
+}
+
 sv_status sv_pack_selected(const sv_shape* s, const void* k_vis, const void* v_vis, const int32_t* idx,
                            const int32_t* count, void* k_pack, void* v_pack, void* stream) {
     sv_status st = check_shape(s, kNeedVis);

@@ -93,6 +93,25 @@ struct PackArgs {
     int32_t rows_per_block;   // set by the launcher
 };
 
+// Attention-mass retrieval scores of a multi-token query (sv_score_visual_mass).
+struct MassArgs {
+    const void* q;            // [B, Tq, Hq, D] through q_sb, q_st, q_sh (fp16)
+    const void* k_vis; const void* k_txt;
+    const int32_t* vis_len; const int32_t* txt_len;
+    float* scores;            // [B, Hkv, n_vis_max]
+    float* lse;               // [B, Tq, Hq]
+    float* part;              // mass_workspace_bytes() bytes: per key block (max, sum) of every query row
+    int32_t B, Hq, Hkv, G, D, Tq, n_vis_max, n_txt_max;
+    float scale;
+    int64_t q_sb, q_st, q_sh;
+    int64_t vis_sb, vis_sh, vis_sn;
+    int64_t txt_sb, txt_sh, txt_sn;
+    int32_t n_stat_blocks;    // set by the launcher
+};
+hipError_t launch_mass(const MassArgs& a, hipStream_t stream);
+size_t mass_workspace_bytes(int B, int Hkv, int n_txt_max, int n_vis_max);
+int mass_max_rows();   // most query rows (tokens x heads of a group) the kernels hold
+
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
 hipError_t launch_pack(const PackArgs& a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);

@@ -36,7 +36,7 @@ def good_shape(**kw) -> SvShape:
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("sv_score_visual", "sv_topk_select", "sv_sparse_decode_attn", "sv_decode_step",
-                 "sv_pack_selected", "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
+                 "sv_pack_selected", "sv_score_visual_mass", "sv_mass_workspace_bytes", "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
         assert must in names
 
 

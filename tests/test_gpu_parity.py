@@ -368,3 +368,50 @@ def test_pack_selected_is_a_byte_exact_gather_and_packed_attention_matches(dtype
                                               r["idx"], r["count"])
         assert np.abs(pbuf.out.cpu().numpy() - oa).max() <= tol
         assert np.abs(pbuf.lse.cpu().numpy() - ol).max() <= tol
+
+
+# ------------------------------------------------------------------ attention-mass retrieval with the whole question
+@pytest.mark.parametrize("D,G,Tq,Nv,Nt", [(128, 7, 32, 5000, 300), (64, 4, 9, 777, 40), (128, 1, 1, 300, 1),
+                                          (128, 8, 32, 1030, 33), (64, 2, 17, 2049, 600)])
+def test_attention_mass_scores_match_the_oracle(D, G, Tq, Nv, Nt):
+    """sv_score_visual_mass against the oracle's explicit attention matrix: per element within the fp32
+    bound below, lse within 1e-4, then the top-k set chosen from the GPU's masses bit-exact against a
+    sort of those masses and inside the tie band of the oracle's.  Ragged lengths, a question longer
+    than the text segment's live rows, and an empty sequence included.
+    Tolerance: a logit carries <= ~2e-5 absolute error (fp32 dot of length D, |logit| <~ 10), lse the
+    same, so each probability is off by <= ~1e-4 relative; the mass of a key sums Tq*G of them."""
+    import paper_2510_17777_amd as sv
+    Hkv, B = 2, 3
+    rng = np.random.default_rng(1000 + D + G + Tq)
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    qm, kv, kt = f(B, Tq, Hkv * G, D), f(B, Hkv, Nv, D), f(B, Hkv, Nt, D)
+    vis_len = np.array([Nv, Nv // 2, 0], np.int32)
+    txt_len = np.array([Nt, min(Nt, max(Tq - 3, 0)), Nt], np.int32)
+    for a in (kv,):
+        for b in range(B):
+            a[b, :, vis_len[b]:] = 1e4
+    want, want_lse = oracle.score_visual_mass(qm, kv, kt, vis_len=vis_len, txt_len=txt_len)
+    dq, dkv, dkt = (torch.from_numpy(x).to("cuda:0") for x in (qm, kv, kt))
+    k = max(1, Nv // 10)
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, k, vis_len=vis_len, txt_len=txt_len)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, Tq, Hkv * G), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, lse)
+    torch.cuda.synchronize()
+    got, got_lse = scores.cpu().numpy(), lse.cpu().numpy()
+    live = np.isfinite(want)
+    assert np.array_equal(np.isneginf(got), ~live)
+    err = np.abs(got.astype(np.float64) - want)[live]
+    bound = (2e-4 * want + 1e-9)[live]
+    assert np.all(err <= bound), f"mass error {err.max():.3e} (rel {np.max(err / want[live]):.3e})"
+    fin = np.isfinite(want_lse)
+    assert np.array_equal(np.isfinite(got_lse), fin)
+    assert np.abs(got_lse - want_lse)[fin].max(initial=0.0) <= 1e-4
+    # the masses feed the unchanged selection
+    buf = sv.DecodeBuffers(shape, "cuda:0")
+    sv.sv_topk_select(shape, scores, buf.idx, buf.count, buf.workspace)
+    torch.cuda.synchronize()
+    idx, cnt = buf.idx.cpu().numpy(), buf.count.cpu().numpy()
+    want_idx, want_cnt = oracle.topk_select(got.astype(np.float64), k, vis_len)
+    assert np.array_equal(cnt, want_cnt) and np.array_equal(idx, want_idx)
+    assert check_index_sets(want, k, vis_len, idx, cnt).ok

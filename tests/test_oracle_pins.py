@@ -385,3 +385,82 @@ def test_packing_is_numpy_take_and_attention_over_the_packed_rows_is_unchanged()
     ident = np.broadcast_to(np.arange(k, dtype=np.int32), (B, Hkv, k)).copy()
     out_p, lse_p, _ = oracle.sparse_decode_attn(q, kp, vp, kt, vt, ident, cnt)
     assert np.abs(out_p - st["out"]).max() < 1e-13 and np.abs(lse_p - st["lse"]).max() < 1e-13
+
+
+# ------------------------------------------------------------------ attention-mass retrieval (multi-token query)
+def _mass_case(seed, B=2, Tq=5, Hq=6, Hkv=2, D=16, Nv=37, Nt=11):
+    rng = np.random.default_rng(seed)
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    return f(B, Tq, Hq, D), f(B, Hkv, Nv, D), f(B, Hkv, Nt, D)
+
+
+def test_mass_equals_column_sums_of_the_library_softmax_of_the_masked_attention_matrix():
+    """The attention matrix written out, masked causally over the question's own tokens, pushed through
+    scipy's softmax / logsumexp (library routines), summed over rows: the oracle must agree."""
+    from scipy.special import logsumexp, softmax
+    qm, kv, kt = _mass_case(1)
+    B, Tq, Hq, D = qm.shape
+    Hkv, Nv, Nt = kv.shape[1], kv.shape[2], kt.shape[2]
+    G = Hq // Hkv
+    mass, lse = oracle.score_visual_mass(qm, kv, kt)
+    sc = 1.0 / np.sqrt(D)
+    for b in range(B):
+        for g in range(Hkv):
+            keys = np.concatenate([kt[b, g], kv[b, g]]).astype(np.float64)              # [Nt + Nv, D]
+            rows = qm[b, :, g * G:(g + 1) * G].astype(np.float64).reshape(Tq * G, D)    # row = i * G + hh
+            logits = sc * rows @ keys.T
+            tok = np.repeat(np.arange(Tq), G)[:, None]
+            col = np.arange(Nt + Nv)[None, :]
+            logits = np.where((col < Nt) & (col > Nt - Tq + tok), -np.inf, logits)      # text after the row's own
+            p = softmax(logits, axis=1)
+            assert np.allclose(mass[b, g], p[:, Nt:].sum(axis=0), rtol=1e-12, atol=1e-15)
+            assert np.allclose(lse[b, :, g * G:(g + 1) * G].reshape(-1), logsumexp(logits, axis=1), rtol=1e-12)
+
+
+def test_mass_conserves_probability_and_respects_lengths():
+    """Every row spends probability 1: visual mass + text mass = Tq * G per kv head (text mass recomputed
+    here from lse); rows past vis_len get -inf and change nothing."""
+    qm, kv, kt = _mass_case(2)
+    B, Tq, Hq, D = qm.shape
+    Hkv, Nv, Nt = kv.shape[1], kv.shape[2], kt.shape[2]
+    G = Hq // Hkv
+    vis_len, txt_len = np.array([Nv, 20], np.int32), np.array([Nt, 7], np.int32)
+    mass, lse = oracle.score_visual_mass(qm, kv, kt, vis_len=vis_len, txt_len=txt_len)
+    assert np.all(np.isneginf(mass[1, :, 20:])) and np.all(np.isfinite(mass[1, :, :20]))
+    sc = 1.0 / np.sqrt(D)
+    for b in range(B):
+        nt = int(txt_len[b])
+        for g in range(Hkv):
+            text_mass = 0.0
+            for i in range(Tq):
+                for h in range(g * G, (g + 1) * G):
+                    seen = max(nt - Tq + i + 1, 0)
+                    lt = sc * kt[b, g, :seen].astype(np.float64) @ qm[b, i, h].astype(np.float64)
+                    text_mass += np.exp(lt - lse[b, i, h]).sum()
+            vis_mass = mass[b, g, :vis_len[b]].sum()
+            assert abs(vis_mass + text_mass - Tq * G) < 1e-10
+    kv2 = kv.copy()
+    kv2[1, :, 20:] = 1e4                                   # padding rows are never read
+    mass2, _ = oracle.score_visual_mass(qm, kv2, kt, vis_len=vis_len, txt_len=txt_len)
+    assert np.array_equal(mass2, mass)
+
+
+def test_mass_of_one_token_one_head_ranks_like_the_logit_and_matches_attention_weights():
+    """Tq = 1, G = 1: the mass is the decode step's own softmax weight, so (a) it orders the visual keys
+    exactly like the scaled-logit score of step 1, and (b) sum_j mass_j * V_j + text part reproduces the
+    oracle's dense attention output (ties the new function to the already pinned attention)."""
+    rng = np.random.default_rng(3)
+    B, H, D, Nv, Nt = 1, 2, 16, 30, 6
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    q, kv, vv, kt, vt = f(B, H, D), f(B, H, Nv, D), f(B, H, Nv, D), f(B, H, Nt, D), f(B, H, Nt, D)
+    mass, lse = oracle.score_visual_mass(q[:, None], kv, kt)
+    logit = oracle.score_visual(q, kv)
+    for h in range(H):
+        assert np.array_equal(np.argsort(-mass[0, h], kind="stable"), np.argsort(-logit[0, h], kind="stable"))
+    dense = oracle.decode_step(q, kv, vv, kt, vt, Nv)
+    assert np.allclose(lse[:, 0], dense["lse"], rtol=1e-12)
+    sc = 1.0 / np.sqrt(D)
+    for h in range(H):
+        wt = np.exp(sc * kt[0, h].astype(np.float64) @ q[0, h].astype(np.float64) - lse[0, 0, h])
+        out = wt @ vt[0, h].astype(np.float64) + mass[0, h] @ vv[0, h].astype(np.float64)
+        assert np.allclose(out, dense["out"][0, h], rtol=1e-10, atol=1e-12)
