@@ -415,3 +415,30 @@ def test_attention_mass_scores_match_the_oracle(D, G, Tq, Nv, Nt):
     want_idx, want_cnt = oracle.topk_select(got.astype(np.float64), k, vis_len)
     assert np.array_equal(cnt, want_cnt) and np.array_equal(idx, want_idx)
     assert check_index_sets(want, k, vis_len, idx, cnt).ok
+
+
+def test_query_agnostic_salience_of_an_encoder_layer_by_the_same_mass_kernel():
+    """Section 3.1 (prefill): for encoders without a summary token the salience of visual token j is the
+    attention it receives averaged over all tokens, computed without forming the N x N matrix.  That is the
+    column mass of softmax(Q K^T) with the visual tokens' own queries and no text: sv_score_visual_mass
+    on chunks of <= 256 query rows, the masses added.  Checked against the explicit matrix (numpy/scipy)."""
+    from scipy.special import softmax
+    import paper_2510_17777_amd as sv
+    B, H, N, D = 2, 4, 729, 64                      # one 27 x 27 patch grid, multi-head attention (G = 1)
+    rng = np.random.default_rng(2025)
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    q, k = f(B, N, H, D), f(B, H, N, D)
+    dq, dk = torch.from_numpy(q).to("cuda:0"), torch.from_numpy(k).to("cuda:0")
+    total = torch.zeros((B, H, N), dtype=torch.float32, device="cuda:0")
+    part = torch.empty_like(total)
+    for i0 in range(0, N, 256):
+        chunk = dq[:, i0:i0 + 256]
+        shape = sv.make_shape(chunk[:, 0], dk, None, 1)
+        sv.sv_score_visual_mass(shape, chunk, dk, None, part)
+        total += part
+    torch.cuda.synchronize()
+    got = total.cpu().numpy() / N
+    logits = np.einsum("bihd,bhjd->bhij", q.astype(np.float64), k.astype(np.float64)) / np.sqrt(D)
+    want = softmax(logits, axis=-1).mean(axis=2)
+    assert np.abs(got - want).max() <= 2e-4 * want.max()
+    assert abs(got.sum(axis=-1) - 1.0).max() <= 1e-4   # every query row spends probability 1
