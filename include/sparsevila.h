@@ -214,6 +214,9 @@ const char *sv_strerror(sv_status status);
  *   "attn_chunk"            tokens per attention workgroup, multiple of 64 in 64..1024, 0 = default
  *   "score_stream_loads"    1 = non-temporal loads of visual K, 0 = plain loads, -1 = default
  *   "attn_mfma"             fp16 caches: 1 = logits on the matrix cores, 0 = vector FMA, -1 = default
+ *   "attn_batches"          fp16 caches with head_dim 128 on the matrix cores: 32-token batches each wavefront
+ *                           walks through (a workgroup covers 128 times as many tokens), 1..8; 0 = chosen per
+ *                           call from the shape so that the workgroups fill the chip in whole rounds
  *   "select_filter"         sv_decode_step on long rows: 1 = the scoring kernel hands the selection only the
  *                           scores above a sampled threshold, 0 = the selection re-reads every score, -1 = default
  *   "filter_rank"           which order statistic of the 512-row sample is that threshold, 1..448; 0 = derived

@@ -21,6 +21,7 @@ struct Tuning {
     int32_t attn_chunk = 0;
     int32_t score_stream_loads = -1;    // -1 = default
     int32_t attn_mfma = -1;             // -1 = default
+    int32_t attn_batches = 0;           // 0 = planned per launch
     int32_t select_filter = -1;         // -1 = default
     int32_t filter_rank = 0;            // 0 = derived from k / n
     int32_t filter_test_mode = 0;
@@ -158,13 +159,17 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
     a.chunk = g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
     a.use_mfma = (s->dtype == SV_F16) && (g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma);
-    if (a.use_mfma) a.chunk = sv::attn_mfma_chunk(s->head_dim);   // the attn_chunk knob shapes the vector path only
+    if (a.use_mfma) a.chunk = sv::attn_mfma_chunk();   // the attn_chunk knob shapes the vector path only
+    a.chunk_vis = a.chunk;
     const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
     a.n_chunks = (int32_t)((t_max + a.chunk - 1) / a.chunk);
     a.split_base = -1;
     if (a.use_mfma && s->head_dim == 128) {   // that kernel gives text and visual tokens chunks of their own
+        const int hblk = a.G > 8 ? (a.G + 7) / 8 : 1;
+        sv::attn_flash_plan((int64_t)a.B * a.Hkv * hblk, s->n_txt_max, kept_max(s), g_tuning.attn_batches, &a.chunk,
+                            &a.chunk_vis);
         a.split_base = (s->n_txt_max + a.chunk - 1) / a.chunk;
-        a.n_chunks = a.split_base + (kept_max(s) + a.chunk - 1) / a.chunk;
+        a.n_chunks = a.split_base + (kept_max(s) + a.chunk_vis - 1) / a.chunk_vis;
     }
     return a;
 }
@@ -385,6 +390,11 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.attn_mfma = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "attn_batches")) {
+        if (value < 0 || value > 8) return SV_ERR_SHAPE;
+        g_tuning.attn_batches = value;
+        return SV_OK;
+    }
     if (!std::strcmp(name, "select_filter")) {
         if (value < -1 || value > 1) return SV_ERR_SHAPE;
         g_tuning.select_filter = value;
@@ -416,6 +426,7 @@ int32_t sv_get_tuning(const char* name) {
     if (!std::strcmp(name, "score_stream_loads"))
         return g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
     if (!std::strcmp(name, "attn_mfma")) return g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma;
+    if (!std::strcmp(name, "attn_batches")) return g_tuning.attn_batches;
     if (!std::strcmp(name, "select_filter"))
         return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
     if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;

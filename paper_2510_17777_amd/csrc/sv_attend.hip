@@ -206,10 +206,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_combine_kernel(const AttnAr
     const TokenList tokens = token_list(a, b, unit);
     const int S = a.n_chunks;
     // live slots: joint list -> the first ceil(len / chunk); split list -> the first ceil(nt / chunk)
-    // of the text range and the first ceil(kept / chunk) of the visual range
+    // of the text range and the first ceil(kept / chunk_vis) of the visual range
     const bool split = a.split_base >= 0;
     const int Sb_txt = split ? (tokens.nt + a.chunk - 1) / a.chunk : 0;
-    const int Sb = split ? Sb_txt + (tokens.len - tokens.nt + a.chunk - 1) / a.chunk
+    const int Sb = split ? Sb_txt + (tokens.len - tokens.nt + a.chunk_vis - 1) / a.chunk_vis
                          : (tokens.len + a.chunk - 1) / a.chunk;
     const int skip = split ? a.split_base - Sb_txt : 0;   // dead slots between the live text and visual ranges
     auto slot_of = [&](int i) -> int { return i < Sb_txt ? i : i + skip; };

@@ -58,6 +58,5 @@ __device__ __forceinline__ TokenList token_list(const AttnArgs& a, int b, int64_
 // and p*V through the matrix cores with wavefronts streaming over batches (sv_attend_flash.hip).
 hipError_t launch_attn_partial_mfma(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_partial_flash(const AttnArgs& a, hipStream_t stream);
-int attn_flash_chunk();
 
 }  // namespace sv

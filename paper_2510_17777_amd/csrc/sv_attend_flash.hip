@@ -5,7 +5,7 @@
 // a kernel in which every wavefront fetched its 64 tokens, computed, and ended ran as two
 // chip-wide rounds of load-then-compute, the memory system idle while the wavefronts
 // computed (53 us, 3.8 TB/s); the fp32 FMAs of p*V alone were 8 us of it.  Here
-//   * a wavefront owns kBatches batches of 32 tokens and walks through them; the K rows of
+//   * a wavefront owns 1..8 batches of 32 tokens (chosen per launch) and walks through them; the K rows of
 //     the next batch are requested as soon as the logits of the current one are done, the V
 //     rows of the next batch as soon as the current p*V is done, so rows are in flight while
 //     the wavefront computes;
@@ -28,6 +28,8 @@
 //     first K/V request after one trip through memory instead of three (lengths, idx, rows).
 // At the end the four wavefronts of a workgroup merge (m, l, acc) through LDS with the
 // log-sum-exp rule and write one partial result per (head, chunk).
+#include <atomic>
+
 #include "sv_attend_common.h"
 
 namespace sv {
@@ -35,8 +37,8 @@ namespace {
 
 constexpr int kD = 128;
 constexpr int kBatchTokens = 32;
-constexpr int kBatches = 4;                                     // batches per wavefront
-constexpr int kFlashChunk = kAttnWaves * kBatches * kBatchTokens;   // tokens per workgroup
+constexpr int kGroupTokens = kAttnWaves * kBatchTokens;         // one batch of every wavefront of a workgroup
+constexpr int kMaxBatches = 8;                                  // batches per wavefront: 1..8, chosen per launch
 constexpr int kKB = kD / 32;                                    // logit MFMAs per 16 tokens
 constexpr int kVLoads = 8;                                      // value loads per lane per batch (4 tokens each)
 
@@ -66,23 +68,22 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
     const int b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    const int p0 = (is_txt ? s : s - a.split_base) * kFlashChunk;   // first position of this chunk in its part
+    const int nb = (is_txt ? a.chunk : a.chunk_vis) / kGroupTokens;   // batches per wavefront
+    const int p0 = (is_txt ? s * a.chunk : (s - a.split_base) * a.chunk_vis);   // first position of this chunk in its part
     const int row = lane & 15, quad = lane >> 4;                    // MFMA coordinates of this lane
     const int row_cap = is_txt ? a.n_txt_max : a.n_vis_max;         // >= 1 for any launched chunk
 
     // Cache rows of the wavefront's tokens: batch j covers positions p0 + (4j + wave) * 32 + [0, 32).
-    int rowid[kBatches];
-    {
-        const int32_t* idx_row = a.idx + unit * a.k;
-#pragma unroll
-        for (int j = 0; j < kBatches; ++j) {
-            const int p = p0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
-            int r = p;
-            if (!is_txt && a.idx) r = idx_row[min(p, a.k - 1)];   // slots past count hold -1: clamped below;
-                                                                    // no idx: the visual segment is packed
-            rowid[j] = r < 0 ? 0 : (r < row_cap ? r : row_cap - 1);   // a faulty idx must not fault the GPU
-        }
-    }
+    // The rows of batch j + 2 are looked up while batch j is worked on.
+    const int32_t* idx_row = a.idx + unit * a.k;
+    auto rows_of = [&](int j) -> int {
+        const int p = p0 + (j * kAttnWaves + wave) * kBatchTokens + (lane & 31);
+        int r = p;
+        if (!is_txt && a.idx) r = idx_row[min(p, a.k - 1)];   // slots past count hold -1: clamped below;
+                                                                // no idx: the visual segment is packed
+        return r < 0 ? 0 : (r < row_cap ? r : row_cap - 1);     // a faulty idx must not fault the GPU
+    };
+    int rows_cur = rows_of(0), rows_next = rows_of(1);
     // live positions of this part (the loads do not wait for it)
     const int part_len = is_txt ? clamp_len(a.txt_len, b, a.n_txt_max)
                                 : ((a.k > 0 && a.count) ? clamp_len(a.count, (int)unit, a.k) : 0);
@@ -112,8 +113,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             vf[u] = __builtin_nontemporal_load(
                 reinterpret_cast<const half8_t*>(vbase + (int64_t)__shfl(rows, 4 * u + quad, kWave) * sn + row * 8));
     };
-    load_k(rowid[0]);
-    load_v(rowid[0]);
+    load_k(rows_cur);
+    load_v(rows_cur);
 
     // query rows -> LDS (zero rows for the padding heads); read back per batch as the A operand
     for (int i = threadIdx.x; i < 16 * (kD / 8); i += kAttnThreads) {
@@ -134,8 +135,10 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; }
 
-#pragma unroll
-    for (int j = 0; j < kBatches; ++j) {
+#pragma unroll   // straight-line code per batch: the loads of batch j + 1 are scheduled into the work on batch j
+    for (int j = 0; j < kMaxBatches; ++j) {
+        if (j >= nb) break;   // block-uniform
+        const int rows_after = rows_of(j + 2);
         const int n_live = part_len - (p0 + (j * kAttnWaves + wave) * kBatchTokens);   // may exceed 32
         if (n_live <= 0) break;   // wave-uniform; later batches are empty too
         // ---- logits of the 32 tokens: lane (row, quad) gets heads 4*quad + r of tokens row and 16 + row
@@ -152,7 +155,7 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) lg[tt][r] = live ? sacc[r] * a.scale : -INFINITY;
         }
-        if (j + 1 < kBatches) load_k(rowid[j + 1]);   // K registers are free again
+        if (j + 1 < nb) load_k(rows_next);   // K registers are free again
         // ---- running softmax statistics; p (fp16) to LDS in the order of the p*V contraction index
         float alpha[4];
 #pragma unroll
@@ -185,7 +188,8 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
             for (int r = 0; r < 4; ++r) c4[r] = acc[jj][r] * alpha[r];
             acc[jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, vb, c4, 0, 0, 0);
         }
-        if (j + 1 < kBatches) load_v(rowid[j + 1]);   // V registers are free again
+        if (j + 1 < nb) load_v(rows_next);   // V registers are free again
+        rows_next = rows_after;
     }
 
     // ---- the wavefront's result to LDS: rows of the valid heads only
@@ -231,10 +235,51 @@ hipError_t launch_one(const AttnArgs& a, int hblk, hipStream_t stream) {
 
 }  // namespace
 
-int attn_flash_chunk() { return kFlashChunk; }
+// Tokens per workgroup for the text range and for the visual range: a multiple of kGroupTokens (every
+// wavefront of a workgroup gets the same number of 32-token batches, 1..kMaxBatches).
+// The registers of the kernel allow three workgroups per compute unit.  A launch runs in
+// ceil(workgroups / (3 * compute units)) rounds, a round lasting about as long as its longest
+// workgroup: its batches plus about one batch-time to reach the first rows (lengths, idx, rows).  The
+// plan minimises rounds * (batches + 1): one round that fills most of the chip beats a full round and a
+// nearly empty one (long-video shape: 4 text + 5 visual batches, 672 workgroups, 41.7 us, against
+// 4 + 4, 784 workgroups of which 16 wait for a free slot, 43.5 us).
+void attn_flash_plan(int64_t units, int n_txt, int n_kept, int forced_batches, int* chunk_txt, int* chunk_vis) {
+    if (forced_batches > 0) {
+        const int nb = forced_batches < kMaxBatches ? forced_batches : kMaxBatches;
+        *chunk_txt = *chunk_vis = nb * kGroupTokens;
+        return;
+    }
+    static std::atomic<int> cached_cus{0};
+    int cus = cached_cus.load(std::memory_order_relaxed);
+    if (cus <= 0) {   // all devices of a node are alike; a failed query falls back to the MI355X count
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cached_cus.store(cus, std::memory_order_relaxed);
+    }
+    const int64_t slots = 3 * (int64_t)cus;
+    int64_t best_cost = -1;
+    int best_t = 1, best_v = 1;
+    for (int bt = 1; bt <= kMaxBatches; ++bt) {
+        for (int bv = 1; bv <= kMaxBatches; ++bv) {
+            const int64_t ct = ((int64_t)n_txt + bt * kGroupTokens - 1) / (bt * kGroupTokens);
+            const int64_t cv = ((int64_t)n_kept + bv * kGroupTokens - 1) / (bv * kGroupTokens);
+            const int64_t wgs = units * (ct + cv);
+            const int64_t rounds = (wgs + slots - 1) / slots;
+            const int longest = (n_txt > 0 && bt > bv) || n_kept == 0 ? bt : bv;
+            const int64_t cost = (rounds * (longest + 1)) * 32 + bt + bv;   // ties: the shorter workgroups
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_t = bt; best_v = bv; }
+        }
+    }
+    *chunk_txt = best_t * kGroupTokens;
+    *chunk_vis = best_v * kGroupTokens;
+}
 
 hipError_t launch_attn_partial_flash(const AttnArgs& a, hipStream_t stream) {
-    if (a.chunk != kFlashChunk || a.D != kD || a.split_base < 0 || a.split_base > a.n_chunks) return hipErrorInvalidValue;
+    auto bad_chunk = [](int c) { return c < kGroupTokens || c > kMaxBatches * kGroupTokens || c % kGroupTokens; };
+    if (bad_chunk(a.chunk) || bad_chunk(a.chunk_vis) || a.D != kD || a.split_base < 0 || a.split_base > a.n_chunks)
+        return hipErrorInvalidValue;
     const int G = a.G;
     if (G == 1) return launch_one<1>(a, 1, stream);
     if (G == 2) return launch_one<2>(a, 1, stream);

@@ -256,7 +256,7 @@ hipError_t launch_dim(const AttnArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-int attn_mfma_chunk(int D) { return D == 128 ? attn_flash_chunk() : kNW * kWaveTokens; }
+int attn_mfma_chunk() { return kNW * kWaveTokens; }
 
 hipError_t launch_attn_partial_mfma(const AttnArgs& a, hipStream_t stream) {
     if (a.D == 128) return launch_attn_partial_flash(a, stream);

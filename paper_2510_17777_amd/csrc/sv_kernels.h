@@ -79,6 +79,7 @@ struct AttnArgs {
     int32_t split_base;       // < 0: chunks cut the joint list (text, then kept visual tokens), S = ceil((n_txt_max +
                               // k) / chunk); >= 0: chunks [0, split_base) cut the text tokens, chunks [split_base, S)
                               // the kept visual tokens
+    int32_t chunk_vis;        // split lists: tokens per workgroup of the visual range (`chunk` is that of the text range)
 };
 
 struct PackArgs {
@@ -137,8 +138,12 @@ size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 // Plain copy of `bytes` (multiple of 16) device bytes; calibration aid for traffic counters.
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
-// Tokens per workgroup of the matrix-core attention kernels (fixed by their register layouts).
-int attn_mfma_chunk(int D);
+// Tokens per workgroup of the matrix-core attention kernel for head_dim 64 (fixed by its register layout).
+int attn_mfma_chunk();
+// head_dim 128: tokens per workgroup of the text range and of the visual range, for `units` = B * Hkv *
+// (head blocks) and the longest text / kept lengths; forced_batches 1..8 overrides the plan (32-token
+// batches per wavefront, both ranges), 0 = plan.
+void attn_flash_plan(int64_t units, int n_txt, int n_kept, int forced_batches, int* chunk_txt, int* chunk_vis);
 
 // Row granule of the scoring kernel for a dtype/head_dim (rows one workgroup pass covers).
 int score_row_granule(int dtype, int D);
