@@ -253,24 +253,34 @@ struct SingleShared {
     int32_t thr_idx;
 };
 
-// Exact top-kb of the n <= ITEMS*1024 scores at s (global or LDS) by one 1024-lane workgroup,
-// scores in registers; out[0..kb) receives the kept positions (renamed through `map` when given)
-// in ascending order.  Requires 0 < kb < n.
+// Exact top-kb of the n <= ITEMS*1024 scores at s (global or LDS) by one 1024-lane workgroup;
+// out[0..kb) receives the kept positions (renamed through `map` when given) in ascending order.
+// Requires 0 < kb < n.  Lane t owns the ITEMS consecutive positions from t*ITEMS on, so that thread
+// order is position order: the output slot of a lane's first kept score is one prefix sum over the
+// lanes' kept counts away, and a score's bin is computed once and kept in a register.
+// kVec: s and map are 16-byte aligned LDS arrays with ITEMS*1024 readable entries (vector reads).
 // With have_range the caller vouches that lo_hint <= every score and supplies an upper value for the
 // binning (scores above it share the top bin); the workgroup then skips its own min/max pass.
-template <int ITEMS>
+template <int ITEMS, bool kVec>
 __device__ __forceinline__ void select_block(SingleShared& sh, const float* __restrict__ s, int32_t* __restrict__ out,
                                              int n, int kb, int tid, int lane, int wave,
                                              const int32_t* map = nullptr, bool have_range = false,
                                              float lo_hint = 0.f, float hi_hint = 0.f) {
     constexpr int NT = kSingleThreads, NW = NT / kWave;
-    const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
-    const int j0 = wave * seg + lane;
-    const int range_end = min(n, wave * seg + seg);
-    const int my_items = j0 < range_end ? (range_end - j0 + kWave - 1) / kWave : 0;
+    static_assert(!kVec || ITEMS % 4 == 0, "vector reads take four entries");
+    const int j0 = tid * ITEMS;
+    const int my_items = min(max(n - j0, 0), ITEMS);
     float vals[ITEMS];
+    if (kVec) {
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? s[j0 + i * kWave] : 0.f;
+        for (int i = 0; i < ITEMS; i += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(s + j0 + i);
+            vals[i] = v.x; vals[i + 1] = v.y; vals[i + 2] = v.z; vals[i + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? s[j0 + i] : 0.f;
+    }
 
     float lo = FLT_MAX, hi = -FLT_MAX;
     if (!have_range) {   // block-uniform
@@ -296,9 +306,15 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
 
     bool done = false;
     if (spread) {
+        int bin[ITEMS];
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i)
-            if (i < my_items) atomicAdd(&sh.rx.hist[value_bin<kBins>(vals[i], lo, inv)], 1u);
+        for (int i = 0; i < ITEMS; ++i) {
+            bin[i] = -1;   // below every bin: never kept, never a candidate
+            if (i < my_items) {
+                bin[i] = value_bin<kBins>(vals[i], lo, inv);
+                atomicAdd(&sh.rx.hist[bin[i]], 1u);
+            }
+        }
         __syncthreads();
         const ThresholdBin tb =
             find_threshold_bin<NT, kBins>(sh.rx.hist, (uint32_t)kb, sh.rx.wave_tot, &sh.rx.tb, tid, lane, wave);
@@ -310,11 +326,11 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
             if (need < tb.in_bin) {
 #pragma unroll
                 for (int i = 0; i < ITEMS; ++i)
-                    if (i < my_items && value_bin<kBins>(vals[i], lo, inv) == tbin) {
+                    if (bin[i] == tbin) {
                         const uint32_t slot = atomicAdd(&sh.n_cand, 1u);
                         if (slot < (uint32_t)kMaxCand) {
                             sh.cand_key[slot] = score_key(vals[i]);
-                            sh.cand_idx[slot] = j0 + i * kWave;
+                            sh.cand_idx[slot] = j0 + i;
                         }
                     }
                 __syncthreads();
@@ -323,34 +339,33 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
                 thr_key = sh.thr_key;
                 thr_idx = sh.thr_idx;
             }
-            uint32_t keep_bits = 0, n_keep = 0;
+            uint32_t keep_bits = 0;
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i) {
-                bool keep = false;
-                if (i < my_items) {
-                    const int bin = value_bin<kBins>(vals[i], lo, inv);
+                bool keep = bin[i] > tbin;
+                if (bin[i] == tbin) {
                     const uint32_t key = score_key(vals[i]);
-                    keep = bin != tbin ? bin > tbin : (key > thr_key || (key == thr_key && (j0 + i * kWave) <= thr_idx));
+                    keep = key > thr_key || (key == thr_key && (j0 + i) <= thr_idx);
                 }
                 keep_bits |= keep ? (1u << i) : 0u;
-                n_keep += (uint32_t)__popcll(__ballot(keep));
             }
-            if (lane == 0) sh.rx.wave_tot2[wave] = n_keep;
-            __syncthreads();
-            uint32_t pos = 0;
+            const uint32_t n_keep = (uint32_t)__popc(keep_bits);
+            uint32_t pos = block_inclusive_scan<NT>(n_keep, sh.rx.wave_tot2, lane, wave) - n_keep;
+            if (keep_bits) {
+                int32_t name[ITEMS];
+                if (map && kVec) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) pos += (w < wave) ? sh.rx.wave_tot2[w] : 0u;
-            const uint64_t lane_lt = (1ull << lane) - 1ull;
+                    for (int i = 0; i < ITEMS; i += 4) {
+                        const int4 v = *reinterpret_cast<const int4*>(map + j0 + i);
+                        name[i] = v.x; name[i + 1] = v.y; name[i + 2] = v.z; name[i + 3] = v.w;
+                    }
+                } else {
 #pragma unroll
-            for (int i = 0; i < ITEMS; ++i) {
-                const bool keep = (keep_bits >> i) & 1u;
-                const uint64_t ballot = __ballot(keep);
-                const uint32_t slot = pos + (uint32_t)__popcll(ballot & lane_lt);
-                if (keep && slot < (uint32_t)kb) {
-                    const int j = j0 + i * kWave;
-                    out[slot] = map ? map[j] : j;
+                    for (int i = 0; i < ITEMS; ++i) name[i] = (map && i < my_items) ? map[j0 + i] : j0 + i;
                 }
-                pos += (uint32_t)__popcll(ballot);
+#pragma unroll
+                for (int i = 0; i < ITEMS; ++i)
+                    if (((keep_bits >> i) & 1u) && pos < (uint32_t)kb) out[pos++] = name[i];   // pos < kb holds
             }
             done = true;
         }
@@ -370,8 +385,8 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
     const int n = live_rows(a.vis_len, b, a.n_vis_max);
     const int kb = a.k < n ? a.k : n;
     if (emit_trivial<kSingleThreads>(a, unit, n, kb, 0, 1, tid)) return;
-    select_block<kSingleMaxN / kSingleThreads>(sh, a.scores + unit * a.n_vis_max, a.idx + unit * a.k, n, kb, tid,
-                                               lane, wave);
+    select_block<kSingleMaxN / kSingleThreads, false>(sh, a.scores + unit * a.n_vis_max, a.idx + unit * a.k, n, kb,
+                                                      tid, lane, wave);
 }
 
 // ------------------------------------------------------------------ candidate-filtered shape
@@ -391,8 +406,8 @@ constexpr int kFiltLoads = kFiltMaxTiles * kFiltRec16 / kSingleThreads;
 
 struct FilteredShared {
     SingleShared sel;
-    float c_score[kFiltCap];
-    int32_t c_row[kFiltCap];
+    alignas(16) float c_score[kFiltCap];
+    alignas(16) int32_t c_row[kFiltCap];
     uint32_t tile_cnt[kFiltMaxTiles];
     float tile_tlo[kFiltMaxTiles];          // the threshold each tile used
     float tile_top[kFiltMaxTiles];          // the largest candidate score of each tile
@@ -514,7 +529,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     // every candidate is >= its tile's threshold >= t_min, and none exceeds the largest tile maximum
     const float top = fmaxf(fmaxf(sh.top_max[0], sh.top_max[1]), fmaxf(sh.top_max[2], sh.top_max[3]));
     const bool have_range = t_min > -INFINITY && top < INFINITY && top > t_min;
-    select_block<kFiltItems>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
+    select_block<kFiltItems, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
 }
 
 // ------------------------------------------------------------------ multi-part shape
