@@ -11,18 +11,25 @@
 //
 // Two streaming passes over the keys, both with the logits on the matrix cores
 // (v_mfma_f32_16x16x32_f16: A = 16 query rows x 32 dims, B = 32 dims x 16 keys):
-//   pass 1 (mass_rowstat_kernel)   per key block, the running maximum and sum of exponentials of
-//          every query row -- each lane keeps them for the key columns it sees and they are
-//          merged across lanes once per block -- then mass_lse_kernel merges the blocks into
-//          lse[b,i,h] = log sum_keys exp(logit);
+//   pass 1 (mass_rowstat_kernel)   per key block, a reference value and the sum of exponentials
+//          relative to it for every query row -- each lane keeps them for the key columns it sees
+//          and they are merged across lanes once per block -- then mass_lse_kernel merges the
+//          blocks into lse[b,i,h] = log sum_keys exp(logit);
 //   pass 2 (mass_colsum_kernel)    p = exp(logit - lse) for every (row, visual key), summed over
 //          the rows: each lane sums the rows it holds, lanes and wavefronts are merged once per
 //          block of 256 keys.
-// The R = Tq * G query rows of a (b, g) are cut into tiles of 16; wavefront w of a workgroup
-// holds tiles w, w+4, w+8, w+12 in registers for the whole kernel (R <= 256), all four
-// wavefronts stream the same keys.  The work is a contraction plus one exponential per
-// (row, key): bound by the exponential and matrix pipes, not by HBM (at Tq = 32, G = 7 the
-// 1.44 GB of keys are re-read twice while 2.5e9 exponentials are taken).
+// The R = Tq * G query rows of a (b, g) are cut into tiles of 16; a wavefront of a workgroup
+// holds up to four of them in registers for the whole kernel (R <= 256), and all four wavefronts
+// work on the same keys.  The keys come through LDS in stages of 64: wavefront w fetches key tile w
+// of the next stage into registers while the current stage is used, and stores it to the other
+// LDS buffer afterwards (one barrier per stage), so a key line crosses the memory system once per
+// workgroup and a whole stage of compute hides its latency.  (Each wavefront fetching every key
+// tile itself, one tile ahead, was bound by that latency: 2 us per 16 keys.)
+// The work is a contraction plus one exponential per (row, key) and pass: bound by the
+// exponential and matrix pipes, not by HBM.  Everything runs in base 2 (scale * log2(e) folded into
+// one multiply-add before v_exp_f32).  Pass 1 keeps a reference per (lane, row) that is raised only
+// when a logit exceeds it by more than 2^8: the usual case is one multiply-add, one exponential and
+// one add per element, and the sums stay far from overflow.
 #include "sv_device.h"
 #include "sv_kernels.h"
 
@@ -36,6 +43,10 @@ constexpr int kTilesPerWave = kMaxRowTiles / kMassWaves;
 constexpr int kStatBlockKeys = 1024;              // keys per workgroup in pass 1
 constexpr int kColBlockKeys = 256;                // keys per sub-block in pass 2 (their masses sit in registers)
 constexpr int kColSubBlocks = 4;                  // sub-blocks per workgroup: the query tiles are loaded once for 1024 keys
+constexpr int kStageKeys = 16 * kMassWaves;       // keys per LDS stage: one key tile per wavefront
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRaiseAbove = 8.f;                // pass 1: a reference is raised when a logit tops it by 2^8
 
 __device__ __forceinline__ int live_len(const int32_t* p, int i, int cap) {
     if (!p) return cap;
@@ -43,24 +54,35 @@ __device__ __forceinline__ int live_len(const int32_t* p, int i, int cap) {
     return v < 0 ? 0 : (v < cap ? v : cap);
 }
 
-// The A operands of this wavefront: row tile t holds rows 16t + (lane & 15); lane (row, quad) supplies
+// The row tiles of a wavefront: tile slot t of wavefront w is row tile (w + rot) % 4 + 4t, where rot
+// differs from workgroup to workgroup so that the SIMDs of a compute unit get equal shares when the
+// last row tiles are missing.
+__device__ __forceinline__ int row_tile_of(int wave, int rot, int t) { return ((wave + rot) & (kMassWaves - 1)) + t * kMassWaves; }
+// How many of the wavefront's tile slots hold rows below R (the live slots come first); wave-uniform.
+__device__ __forceinline__ int live_tiles_of(int wave, int rot, int R) {
+    const int tiles = (R + 15) / 16, first = (wave + rot) & (kMassWaves - 1);
+    const int n = tiles > first ? (tiles - first + kMassWaves - 1) / kMassWaves : 0;
+    return __builtin_amdgcn_readfirstlane(n);
+}
+
+// The A operands of this wavefront: a row tile holds rows 16*tile + (lane & 15); lane (row, quad) supplies
 // dims 8*quad + 32*kb .. +8.  Row r is query token r / G, head g*G + r % G; rows >= R are zero.
 template <int KB>
-__device__ __forceinline__ void load_query_tiles(const MassArgs& a, int b, int g, int wave, int lane,
+__device__ __forceinline__ void load_query_tiles(const MassArgs& a, int b, int g, int wave, int rot, int lane,
                                                  half8_t (&qa)[kTilesPerWave][KB]) {
     const int row = lane & 15, quad = lane >> 4;
     const int R = a.Tq * a.G;
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t) {
-        const int r = (wave + t * kMassWaves) * 16 + row;
+    for (int t = 0; t < kTilesPerWave; ++t) {   // unconditional loads on a clamped row: no load waits for a branch
+        const int r = row_tile_of(wave, rot, t) * 16 + row;
+        const int rc = min(r, R - 1);
+        const int i = rc / a.G, hh = rc - i * a.G;
+        const _Float16* p = static_cast<const _Float16*>(a.q) + (int64_t)b * a.q_sb + (int64_t)i * a.q_st +
+                            (int64_t)(g * a.G + hh) * a.q_sh + quad * 8;
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) qa[t][kb] = 0;
-        if (r < R) {
-            const int i = r / a.G, hh = r - i * a.G;
-            const _Float16* p = static_cast<const _Float16*>(a.q) + (int64_t)b * a.q_sb + (int64_t)i * a.q_st +
-                                (int64_t)(g * a.G + hh) * a.q_sh + quad * 8;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) qa[t][kb] = *reinterpret_cast<const half8_t*>(p + 32 * kb);
+        for (int kb = 0; kb < KB; ++kb) {
+            const half8_t v = *reinterpret_cast<const half8_t*>(p + 32 * kb);
+            qa[t][kb] = r < R ? v : half8_t(0);
         }
     }
 }
@@ -74,96 +96,215 @@ __device__ __forceinline__ void load_key_tile(const _Float16* base, int64_t sn, 
     for (int kb = 0; kb < KB; ++kb) kf[kb] = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(p + 32 * kb));
 }
 
-// ---- pass 1: per key block, (max, sum exp) of every query row over the block's keys ----
+// One LDS stage: [key tile][kb][lane], the operand words in the lane order they are fetched and used in.
+template <int KB>
+struct KeyStage { half8_t w[kMassWaves][KB][kWave]; };
+
+template <int KB>
+__device__ __forceinline__ void read_key_tile(const KeyStage<KB>& st, int kt, int lane, half8_t (&kf)[KB]) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) kf[kb] = st.w[kt][kb][lane];
+}
+
+// Logits of the first NTL row tiles of this wavefront against one key tile: lane (row, quad) gets rows
+// 4*quad + rr of each row tile at key column `row`.  The chains of the row tiles are interleaved so that
+// consecutive matrix instructions do not depend on each other.
+template <int KB, int NTL>
+__device__ __forceinline__ void tile_logits(const half8_t (&qa)[kTilesPerWave][KB], const half8_t (&kf)[KB],
+                                            float4_t (&sv)[kTilesPerWave]) {
+#pragma unroll
+    for (int t = 0; t < NTL; ++t) sv[t] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int t = 0; t < NTL; ++t) sv[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], sv[t], 0, 0, 0);
+}
+
+// The loads of the query tiles must not count as outstanding inside the key loops: the wait inserted
+// for them there would also wait for the keys fetched one stage ahead.
+__device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+// ---- pass 1: per key block, (reference, sum exp) of every query row over the block's keys ----
 // Key list of a (b, g): text rows [0, nt), then visual rows [0, nv).  Query token i sits at text row
 // nt - Tq + i and sees the text rows up to itself.
+
+// A stage of 64 live visual keys, every row sees all of them.  kInit: nothing was seen before, the first
+// key tile sets the references.  The logits of key tile k + 1 are issued before those of tile k are used.
+template <int KB, int NTL, bool kInit>
+__device__ __forceinline__ void rowstat_plain_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
+                                                    float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
+    half8_t kf[2][KB];
+    float4_t sv[2][kTilesPerWave];
+    read_key_tile<KB>(st, 0, lane, kf[0]);
+    tile_logits<KB, NTL>(qa, kf[0], sv[0]);
+#pragma unroll
+    for (int kt = 0; kt < kMassWaves; ++kt) {
+        if (kt + 1 < kMassWaves) {
+            read_key_tile<KB>(st, kt + 1, lane, kf[(kt + 1) & 1]);
+            tile_logits<KB, NTL>(qa, kf[(kt + 1) & 1], sv[(kt + 1) & 1]);
+        }
+        float4_t(&y)[kTilesPerWave] = sv[kt & 1];
+        if (kInit && kt == 0) {
+#pragma unroll
+            for (int t = 0; t < NTL; ++t)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    ref[t][rr] = y[t][rr] * c2;
+                    l[t][rr] = 1.f;
+                }
+            continue;
+        }
+        float top = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                y[t][rr] = fmaf(y[t][rr], c2, -ref[t][rr]);   // logit - ref, base 2
+                top = fmaxf(top, y[t][rr]);
+            }
+        if (__ballot(top > kRaiseAbove) != 0ull) {   // rare: some reference is raised to the logit that tops it
+#pragma unroll
+            for (int t = 0; t < NTL; ++t)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    if (y[t][rr] > kRaiseAbove) {
+                        l[t][rr] *= __builtin_amdgcn_exp2f(-y[t][rr]);
+                        ref[t][rr] += y[t][rr];
+                        y[t][rr] = 0.f;
+                    }
+        }
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) l[t][rr] += __builtin_amdgcn_exp2f(y[t][rr]);
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(kMassThreads) void mass_rowstat_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
+    __shared__ KeyStage<KB> stage[2];
     const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int row = lane & 15, quad = lane >> 4;
+    const int rot = blk & (kMassWaves - 1);
     const int nt = live_len(a.txt_len, b, a.n_txt_max), nv = live_len(a.vis_len, b, a.n_vis_max);
     const int n_keys = nt + nv;
     const int key0 = blk * kStatBlockKeys;
     const int R = a.Tq * a.G;
+    const int ntl = live_tiles_of(wave, rot, R);   // wave-uniform
+    const float c2 = a.scale * kLog2e;
     const int64_t unit = (int64_t)b * a.Hkv + g;
     float* part = a.part + ((unit * a.n_stat_blocks + blk) * (int64_t)(kMaxRowTiles * 16)) * 2;
 
     half8_t qa[kTilesPerWave][KB];
-    load_query_tiles<KB>(a, b, g, wave, lane, qa);
-    // per lane: running max and sum of the 4 rows (4*quad + rr) of each of its tiles over the key columns it sees
-    float m[kTilesPerWave][4], l[kTilesPerWave][4];
+    load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
+    // per lane, for the 4 rows (4*quad + rr) of each of its tiles, over the key columns it sees, in base 2:
+    // a reference value ref (the largest logit met, or up to 8 below it) and l = sum 2^(logit - ref)
+    float ref[kTilesPerWave][4], l[kTilesPerWave][4];
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            m[t][rr] = -INFINITY;
+            ref[t][rr] = -INFINITY;
             l[t][rr] = 0.f;
         }
     const _Float16* ktxt = static_cast<const _Float16*>(a.k_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
     const _Float16* kvis = static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
 
     const int k_end = min(key0 + kStatBlockKeys, n_keys);
-    auto load_tile = [&](int k0, half8_t (&kf)[KB]) {   // clamped rows: dead columns are masked at use
-        const int kc = min(k0 + row, n_keys - 1);
-        if (kc < nt) load_key_tile<KB>(ktxt, a.txt_sn, kc, quad, kf);
-        else load_key_tile<KB>(kvis, a.vis_sn, kc - nt, quad, kf);
+    half8_t kfetch[KB];
+    auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns
+        const int kc = min(s0 + wave * 16 + row, n_keys - 1);   // are masked at use
+        if (kc < nt) load_key_tile<KB>(ktxt, a.txt_sn, kc, quad, kfetch);
+        else load_key_tile<KB>(kvis, a.vis_sn, kc - nt, quad, kfetch);
     };
-    auto consume_tile = [&](int k0, const half8_t (&kf)[KB]) {
-        const int key = k0 + row;               // this lane's key column
-        const bool plain = k0 >= nt && k0 + 16 <= n_keys;   // wave-uniform: visual keys, all live, seen by every row
+    auto put = [&](KeyStage<KB>& st) {
 #pragma unroll
-        for (int t = 0; t < kTilesPerWave; ++t) {
-            if ((wave + t * kMassWaves) * 16 >= R) break;   // wave-uniform
-            float4_t s = {0.f, 0.f, 0.f, 0.f};
+        for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
+    };
+    // text tiles, ragged tiles, and visual tiles met before every reference is set: masked, exact running maximum
+    auto masked_tile = [&](int k0, const KeyStage<KB>& st, int kt) {
+        half8_t kf[KB];
+        read_key_tile<KB>(st, kt, lane, kf);
+        const int key = k0 + row;   // this lane's key column
+        float4_t sv[kTilesPerWave];
+        tile_logits<KB, kTilesPerWave>(qa, kf, sv);   // rows past R are zero rows: computed, never stored
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) s = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], s, 0, 0, 0);
+        for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                float x = s[rr] * a.scale;
-                if (!plain) {   // text tiles and the ragged last tile: query token i sits at text row nt - Tq + i
-                    const int r = (wave + t * kMassWaves) * 16 + 4 * quad + rr;
-                    const int last_txt = nt - a.Tq + (r < R ? r / a.G : 0);
-                    const bool seen = key < n_keys && (key >= nt || key <= last_txt);
-                    x = seen ? x : -INFINITY;
-                }
-                const float mn = fmaxf(m[t][rr], x);
+                const int r = row_tile_of(wave, rot, t) * 16 + 4 * quad + rr;
+                const int last_txt = nt - a.Tq + (r < R ? r / a.G : 0);   // query token i sits at text row nt - Tq + i
+                const bool seen = key < n_keys && (key >= nt || key <= last_txt);
+                const float x = seen ? sv[t][rr] * c2 : -INFINITY;
+                const float mn = fmaxf(ref[t][rr], x);
                 if (mn > -INFINITY) {   // something seen so far
-                    l[t][rr] = l[t][rr] * __expf(m[t][rr] - mn) + __expf(x - mn);
-                    m[t][rr] = mn;
+                    l[t][rr] = l[t][rr] * __builtin_amdgcn_exp2f(ref[t][rr] - mn) + __builtin_amdgcn_exp2f(x - mn);
+                    ref[t][rr] = mn;
                 }
             }
-        }
     };
-    if (key0 < k_end) {
-        half8_t kf0[KB], kf1[KB];
-        load_tile(key0, kf0);
-        for (int k0 = key0; k0 < k_end; k0 += 32) {
-            if (k0 + 16 < k_end) load_tile(k0 + 16, kf1);
-            consume_tile(k0, kf0);
-            if (k0 + 16 < k_end) {
-                if (k0 + 32 < k_end) load_tile(k0 + 32, kf0);
-                consume_tile(k0 + 16, kf1);
+    if (key0 < k_end) {   // block-uniform
+        fetch(key0);
+        wait_for_loads();
+        put(stage[0]);
+        __syncthreads();
+        int cur = 0;
+        bool ref_ready = false;   // block-uniform: every reference is finite
+        for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
+            const bool more = s0 + kStageKeys < k_end;   // block-uniform
+            if (more) fetch(s0 + kStageKeys);
+            const bool plain = s0 >= nt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
+            if (plain && (ref_ready || s0 == key0)) {
+                const KeyStage<KB>& st = stage[cur];
+                if (ref_ready) {
+                    switch (ntl) {
+                        case 4: rowstat_plain_stage<KB, 4, false>(st, lane, qa, c2, ref, l); break;
+                        case 3: rowstat_plain_stage<KB, 3, false>(st, lane, qa, c2, ref, l); break;
+                        case 2: rowstat_plain_stage<KB, 2, false>(st, lane, qa, c2, ref, l); break;
+                        case 1: rowstat_plain_stage<KB, 1, false>(st, lane, qa, c2, ref, l); break;
+                        default: break;
+                    }
+                } else {   // first stage of the block: nothing seen so far
+                    switch (ntl) {
+                        case 4: rowstat_plain_stage<KB, 4, true>(st, lane, qa, c2, ref, l); break;
+                        case 3: rowstat_plain_stage<KB, 3, true>(st, lane, qa, c2, ref, l); break;
+                        case 2: rowstat_plain_stage<KB, 2, true>(st, lane, qa, c2, ref, l); break;
+                        case 1: rowstat_plain_stage<KB, 1, true>(st, lane, qa, c2, ref, l); break;
+                        default: break;
+                    }
+                }
+                ref_ready = true;
+            } else {
+#pragma unroll 1
+                for (int kt = 0; kt < kMassWaves; ++kt)
+                    if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);
+                if (plain) ref_ready = true;   // every row saw these 64 keys
             }
+            if (more) put(stage[cur ^ 1]);
+            __syncthreads();
+            cur ^= 1;
         }
     }
     // merge the 16 key columns of a row (the lanes of a 16-lane row hold the same rows), store per block
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
-        const int tile = wave + t * kMassWaves;
+        const int tile = row_tile_of(wave, rot, t);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            float mx = m[t][rr];
+            const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the plain stages leave dead tiles untouched,
+            const float lmine = t < ntl ? l[t][rr] : 0.f;          // the masked ones compute them: drop both
+            float mx = mine;
             mx = fmaxf(mx, dpp_move<kDppQuadXor1>(mx));
             mx = fmaxf(mx, dpp_move<kDppQuadXor2>(mx));
             mx = fmaxf(mx, dpp_move<kDppRowHalfMirror>(mx));
             mx = fmaxf(mx, dpp_move<kDppRowMirror>(mx));
-            const float e = m[t][rr] > -INFINITY ? __expf(m[t][rr] - mx) : 0.f;
-            const float lt = group_sum<16>(l[t][rr] * e);
+            const float e = mine > -INFINITY ? __builtin_amdgcn_exp2f(mine - mx) : 0.f;
+            const float lt = group_sum<16>(lmine * e);
             if (row == 0) {
                 const int r = tile * 16 + 4 * quad + rr;
-                part[r * 2] = mx;
+                part[r * 2] = mx * kLn2;   // natural-log units from here on
                 part[r * 2 + 1] = lt;
             }
         }
@@ -192,63 +333,101 @@ __global__ __launch_bounds__(256) void mass_lse_kernel(const MassArgs a) {
 }
 
 // ---- pass 2: mass of every visual key ----
+// One stage: col[k] = sum over the wavefront's live rows of 2^(logit - lse) at key column 16k + row.  Key
+// tiles past the live keys hold copies of the last live row: computed, dropped when the masses are stored.
+template <int KB, int NTL>
+__device__ __forceinline__ void colsum_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
+                                             float c2, const float (&lse2)[kTilesPerWave][4], float* col) {
+    half8_t kf[2][KB];
+    float4_t sv[2][kTilesPerWave];
+    read_key_tile<KB>(st, 0, lane, kf[0]);
+    tile_logits<KB, NTL>(qa, kf[0], sv[0]);
+#pragma unroll
+    for (int kt = 0; kt < kMassWaves; ++kt) {
+        if (kt + 1 < kMassWaves) {
+            read_key_tile<KB>(st, kt + 1, lane, kf[(kt + 1) & 1]);
+            tile_logits<KB, NTL>(qa, kf[(kt + 1) & 1], sv[(kt + 1) & 1]);
+        }
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) acc += __builtin_amdgcn_exp2f(fmaf(sv[kt & 1][t][rr], c2, -lse2[t][rr]));
+        col[kt] = acc;
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(kMassThreads) void mass_colsum_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
-    constexpr int KT = kColBlockKeys / 16;   // key tiles per block
+    constexpr int KT = kColBlockKeys / 16;   // key tiles per sub-block
+    __shared__ KeyStage<KB> stage[2];
     __shared__ float s_col[kMassWaves][kColBlockKeys];
     const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int row = lane & 15, quad = lane >> 4;
+    const int rot = blk & (kMassWaves - 1);
     const int nv = live_len(a.vis_len, b, a.n_vis_max);
     const int key0 = blk * kColBlockKeys * kColSubBlocks;
     const int R = a.Tq * a.G;
+    const int ntl = live_tiles_of(wave, rot, R);   // wave-uniform
+    const float c2 = a.scale * kLog2e;
     const int64_t unit = (int64_t)b * a.Hkv + g;
     float* out = a.scores + unit * a.n_vis_max;
 
     half8_t qa[kTilesPerWave][KB];
-    load_query_tiles<KB>(a, b, g, wave, lane, qa);
-    float lse[kTilesPerWave][4];   // of rows 4*quad + rr of each tile; +inf for the padding rows: p = 0
+    load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
+    float lse2[kTilesPerWave][4];   // base 2, of rows 4*quad + rr of each tile; +inf for the padding rows: p = 0
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const int r = (wave + t * kMassWaves) * 16 + 4 * quad + rr;
-            lse[t][rr] = INFINITY;
-            if (r < R) {
-                const int i = r / a.G, hh = r - i * a.G;
-                lse[t][rr] = a.lse[((int64_t)b * a.Tq + i) * a.Hq + g * a.G + hh];
-            }
+            const int r = row_tile_of(wave, rot, t) * 16 + 4 * quad + rr;
+            const int rc = min(r, R - 1);
+            const int i = rc / a.G, hh = rc - i * a.G;
+            const float v = a.lse[((int64_t)b * a.Tq + i) * a.Hq + g * a.G + hh];   // unconditional, clamped row
+            lse2[t][rr] = r < R ? v * kLog2e : INFINITY;
         }
     const _Float16* kvis = static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const int k_end = min(key0 + kColBlockKeys * kColSubBlocks, nv);   // live keys of this workgroup end here
 
+    half8_t kfetch[KB];
+    auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns dropped below
+        load_key_tile<KB>(kvis, a.vis_sn, min(s0 + wave * 16 + row, nv - 1), quad, kfetch);
+    };
+    auto put = [&](KeyStage<KB>& st) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
+    };
+    int cur = 0;
+    if (key0 < k_end) fetch(key0);   // block-uniform
+    wait_for_loads();
+    if (key0 < k_end) put(stage[0]);
+    __syncthreads();
     for (int sub = 0; sub < kColSubBlocks; ++sub) {
         const int sub0 = key0 + sub * kColBlockKeys;
         if (sub0 >= a.n_vis_max) break;   // block-uniform
         float col[KT];   // per lane: mass of key column (16*kt + row) from the rows this lane holds
-        if (sub0 < nv) {   // block-uniform
-            half8_t kf[2][KB];
-            load_key_tile<KB>(kvis, a.vis_sn, min(sub0 + row, nv - 1), quad, kf[0]);
 #pragma unroll
-            for (int kt = 0; kt < KT; ++kt) {
-                col[kt] = 0.f;
-                if (kt + 1 < KT)   // next tile in flight while this one is used; rows clamped, dead columns dropped below
-                    load_key_tile<KB>(kvis, a.vis_sn, min(sub0 + (kt + 1) * 16 + row, nv - 1), quad, kf[(kt + 1) & 1]);
-                if (sub0 + kt * 16 >= nv) continue;   // wave-uniform: tile past the live keys
+        for (int kt = 0; kt < KT; ++kt) col[kt] = 0.f;
+        if (sub0 < k_end) {   // block-uniform
 #pragma unroll
-                for (int t = 0; t < kTilesPerWave; ++t) {
-                    if ((wave + t * kMassWaves) * 16 >= R) break;   // wave-uniform
-                    float4_t s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-                        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kt & 1][kb], s, 0, 0, 0);
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) col[kt] += __expf(s[rr] * a.scale - lse[t][rr]);
+            for (int st = 0; st < kColBlockKeys / kStageKeys; ++st) {
+                const int s0 = sub0 + st * kStageKeys;
+                if (s0 >= k_end) break;   // block-uniform
+                const bool more = s0 + kStageKeys < k_end;
+                if (more) fetch(s0 + kStageKeys);
+                switch (ntl) {
+                    case 4: colsum_stage<KB, 4>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
+                    case 3: colsum_stage<KB, 3>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
+                    case 2: colsum_stage<KB, 2>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
+                    case 1: colsum_stage<KB, 1>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
+                    default: break;
                 }
+                if (more) put(stage[cur ^ 1]);
+                __syncthreads();
+                cur ^= 1;
             }
-        } else {
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt) col[kt] = 0.f;
         }
         // the four quads of a wavefront hold different rows of the same key columns: add them, then the wavefronts
 #pragma unroll
