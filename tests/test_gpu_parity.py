@@ -184,7 +184,8 @@ def _exact_sets(r, k, vis_len):
 
 
 @pytest.mark.parametrize("dtype,D,G,Nv,k", [(np.float16, 128, 7, 20000, 1000), (np.float16, 64, 2, 9001, 450),
-                                           (np.float32, 128, 1, 6000, 300), (np.float32, 64, 4, 12345, 100)])
+                                           (np.float32, 128, 1, 6000, 300), (np.float32, 64, 4, 12345, 100),
+                                           (np.float16, 64, 1, 70001, 1500)])   # > 256 tiles of 256 rows: wider tiles
 def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     """Long rows inside sv_decode_step: the sampled threshold + candidate slots + on-chip ranking must
     give exactly the set a full sort of the GPU's own scores gives -- with the filter on, with the
