@@ -34,6 +34,7 @@
 //     one dependent round trip through memory costs more than the arithmetic.
 #include "sv_score_device.h"
 
+#include <atomic>
 #include <cfloat>
 #include <cmath>
 
@@ -397,8 +398,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
 // LDS; then the same on-chip selection as for a short row runs on them, positions renamed to the
 // original rows.  If fewer than k_b candidates exist (t_lo was too high) or more than fit, the
 // workgroup selects from the full score row.
-constexpr int kFiltCap = 8192;                       // candidates ranked on chip
-constexpr int kFiltItems = kFiltCap / kSingleThreads;
+constexpr int kFiltCap = 16384;                      // candidates ranked on chip (their scores and rows fill most of the LDS)
 constexpr int kFiltMaxTiles = 256;
 constexpr int kFiltPrimary = kFilterRecordPairs;     // pairs in a primary record
 constexpr int kFiltRec16 = kFiltPrimary / 2 + 1;     // 16-byte words per primary record
@@ -529,7 +529,11 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     // every candidate is >= its tile's threshold >= t_min, and none exceeds the largest tile maximum
     const float top = fmaxf(fmaxf(sh.top_max[0], sh.top_max[1]), fmaxf(sh.top_max[2], sh.top_max[3]));
     const bool have_range = t_min > -INFINITY && top < INFINITY && top > t_min;
-    select_block<kFiltItems, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
+    if (m <= (uint32_t)(8 * NT))   // block-uniform: the usual case keeps eight candidates per lane
+        select_block<8, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
+    else
+        select_block<kFiltCap / NT, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min,
+                                          top);
 }
 
 // ------------------------------------------------------------------ multi-part shape
@@ -924,10 +928,19 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
 namespace {
 template <typename T, int D>
 hipError_t launch_select_filtered_typed(const SelectArgs& a, const ScoreArgs& sc, hipStream_t stream) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_filtered_kernel<T, D>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       (int)sizeof(FilteredShared));
-    if (attr != hipSuccess) return attr;
+    // the kernel's LDS exceeds the default limit: raised once per device (the attribute belongs to the
+    // device's copy of the kernel)
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> raised[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!raised[dev].load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(select_filtered_kernel<T, D>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    (int)sizeof(FilteredShared));
+        if (attr != hipSuccess) return attr;
+        raised[dev].store(true, std::memory_order_release);
+    }
     dim3 grid((unsigned)a.Hkv, (unsigned)a.B), block(kSingleThreads);
     hipLaunchKernelGGL((select_filtered_kernel<T, D>), grid, block, sizeof(FilteredShared), stream, a, sc);
     return hipGetLastError();
