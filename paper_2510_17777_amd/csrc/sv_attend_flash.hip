@@ -54,9 +54,10 @@ template <int GB>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
     using T = _Float16;
-    __shared__ __align__(16) T s_p[kAttnWaves][16][kBatchTokens];   // p of the current batch, A-operand order
-    __shared__ __align__(16) T s_q[16][kD];                         // the (zero-padded) query rows
-    __shared__ float s_acc[kAttnWaves][GB][kD];
+    // Row strides padded by 16 bytes: the 16 rows a wavefront reads at once then start in different banks.
+    __shared__ __align__(16) T s_p[kAttnWaves][16][kBatchTokens + 8];   // p of the current batch, A-operand order
+    __shared__ __align__(16) T s_q[16][kD + 8];                         // the (zero-padded) query rows
+    __shared__ __align__(16) float s_acc[kAttnWaves][GB][kD];
     __shared__ float s_m[kAttnWaves][GB], s_l[kAttnWaves][GB];
 
     // Chunks [0, split_base) cover the text tokens, chunks [split_base, S) the kept visual tokens, so
@@ -197,8 +198,10 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
     for (int r = 0; r < 4; ++r) {
         const int h = 4 * quad + r;
         if (h < GB) {
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) s_acc[wave][h][8 * row + jj] = acc[jj][r];
+            const float4_t lo = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+            const float4_t hi = {acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
+            *reinterpret_cast<float4_t*>(&s_acc[wave][h][8 * row]) = lo;       // the lane's 8 consecutive dims
+            *reinterpret_cast<float4_t*>(&s_acc[wave][h][8 * row + 4]) = hi;
             if (row == 0) { s_m[wave][h] = m_run[r]; s_l[wave][h] = l_run[r]; }
         }
     }
