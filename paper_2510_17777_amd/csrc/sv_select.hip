@@ -427,22 +427,22 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    const int n = live_rows(a.vis_len, b, a.n_vis_max);
-    const int kb = a.k < n ? a.k : n;
-    if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
-    int32_t* __restrict__ out = a.idx + unit * a.k;
-
-    const int live_tiles = (n + f.tile_rows - 1) / f.tile_rows;   // <= kFiltMaxTiles (checked by the host)
+    // one trip: word (tid + u*NT) of the row's block of records, requested before the row's length is
+    // known (records of tiles past the live rows hold stale words, ignored below)
     const uint4* recs = f.tiles + unit * f.n_tiles * kFiltRec16;
     const uint2* ovf = f.overflow + unit * f.n_tiles * f.tile_rows;
-    // one trip: word (tid + u*NT) of the row's block of records
     uint4 word[kFiltLoads];
 #pragma unroll
     for (int u = 0; u < kFiltLoads; ++u) {
         const int w = tid + u * NT;
         word[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (w < live_tiles * kFiltRec16) word[u] = recs[w];
+        if (w < f.n_tiles * kFiltRec16) word[u] = recs[w];
     }
+    const int n = live_rows(a.vis_len, b, a.n_vis_max);
+    const int kb = a.k < n ? a.k : n;
+    if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
+    int32_t* __restrict__ out = a.idx + unit * a.k;
+    const int live_tiles = (n + f.tile_rows - 1) / f.tile_rows;   // <= kFiltMaxTiles (checked by the host)
 #pragma unroll
     for (int u = 0; u < kFiltLoads; ++u) {
         const int w = tid + u * NT;
@@ -498,8 +498,40 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
                 sh.c_score[off + e + 1] = __uint_as_float(word[u].z);
                 sh.c_row[off + e + 1] = (int32_t)word[u].w;
             }
-            // the rare fuller tile: its remaining pairs from the overflow rows (which hold all its pairs)
-            for (uint32_t x = kFiltPrimary + (q - 1); x < cnt; x += kFiltRec16 - 1) {
+        }
+    }
+    // The fuller tiles: their remaining pairs from the overflow rows (which hold all pairs of such a tile).
+    // Lane q of a tile's 31 takes pairs 62 + (q - 1) + 31 i.  The loads of i < 2 (tiles of up to 124
+    // candidates) are all issued before any is used: one more trip through memory, not one per tile.
+    constexpr uint32_t kStride = kFiltRec16 - 1;
+    uint2 ov[kFiltLoads][2];
+#pragma unroll
+    for (int u = 0; u < kFiltLoads; ++u) {
+        const int w = tid + u * NT;
+        const int tile = w / kFiltRec16, q = w % kFiltRec16;
+        const uint32_t cnt = (tile < live_tiles && q > 0) ? sh.tile_cnt[tile] : 0u;
+#pragma unroll
+        for (uint32_t i = 0; i < 2; ++i) {
+            const uint32_t x = kFiltPrimary + (q - 1) + i * kStride;
+            ov[u][i] = make_uint2(0u, 0u);
+            if (x < cnt) ov[u][i] = ovf[(int64_t)tile * f.tile_rows + x];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kFiltLoads; ++u) {
+        const int w = tid + u * NT;
+        const int tile = w / kFiltRec16, q = w % kFiltRec16;
+        if (tile < live_tiles && q > 0) {
+            const uint32_t off = sh.tile_off[tile], cnt = sh.tile_cnt[tile];
+#pragma unroll
+            for (uint32_t i = 0; i < 2; ++i) {
+                const uint32_t x = kFiltPrimary + (q - 1) + i * kStride;
+                if (x < cnt) {
+                    sh.c_score[off + x] = __uint_as_float(ov[u][i].x);
+                    sh.c_row[off + x] = (int32_t)ov[u][i].y;
+                }
+            }
+            for (uint32_t x = kFiltPrimary + (q - 1) + 2 * kStride; x < cnt; x += kStride) {   // rare: > 124 candidates
                 const uint2 v = ovf[(int64_t)tile * f.tile_rows + x];
                 sh.c_score[off + x] = __uint_as_float(v.x);
                 sh.c_row[off + x] = (int32_t)v.y;
