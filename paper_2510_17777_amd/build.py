@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -18,6 +19,8 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     # packed fp32 VALU forms are kept off for every kernel of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # per-kernel register / scratch / LDS remarks: parsed below, not printed
+    "-Rpass-analysis=kernel-resource-usage",
 ]
 
 
@@ -29,7 +32,24 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
     # the host pass does not know the packed-fp32 feature name; that warning is expected
     noise = "is not a recognized feature for this target"
-    msgs = [l for l in r.stderr.splitlines() if l.strip() and noise not in l]
+    msgs, kernel, in_remark = [], "?", False
+    for line in r.stderr.splitlines():
+        if in_remark and re.match(r"^\s*\d*\s*\|", line):
+            continue   # the source lines quoted under a remark
+        in_remark = False
+        if "[-Rpass-analysis=kernel-resource-usage]" in line:
+            in_remark = True
+            # No kernel of the library may spill to scratch memory: a kernel that does pays for it at
+            # every launch (and so did the launch after it, when it was measured).
+            text = line.split("remark:", 1)[-1].strip()
+            if text.startswith("Function Name:"):
+                kernel = text.split(":", 1)[1].split("[")[0].strip()
+            elif text.startswith("ScratchSize [bytes/lane]:"):
+                if int(text.split(":")[1].split("[")[0]) != 0:
+                    raise RuntimeError(f"{src}: kernel {kernel} uses scratch memory ({text})")
+            continue
+        if line.strip() and noise not in line:
+            msgs.append(line)
     if msgs:
         sys.stderr.write("\n".join(msgs) + "\n")
     return obj
