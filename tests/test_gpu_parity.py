@@ -335,6 +335,36 @@ def test_tuning_knobs_change_launch_shape_not_results():
 
 
 
+def test_attention_batches_per_wavefront_every_value_against_the_oracle():
+    """The matrix-core attention kernel for fp16 / head_dim 128 walks 1..8 batches of 32 tokens per
+    wavefront (chosen per call, or forced by the attn_batches knob): every value, on ragged text and
+    kept lengths that end inside a batch, inside a workgroup and on a chunk boundary, against the
+    oracle's attention over the kept set (2e-3), and the planned launch against the whole rule set."""
+    import paper_2510_17777_amd as sv
+    B, Hkv, G, D, Nv, Nt, k = 4, 2, 7, 128, 5000, 700, 1300
+    inp = rand_inputs(77, B, Hkv * G, Hkv, D, Nv, Nt, np.float16)
+    vis_len = np.array([Nv, 1300, 640, 33], np.int32)      # kept: 1300, 1300, 640 (a chunk boundary for 5 batches), 33
+    txt_len = np.array([Nt, 512, 1, 0], np.int32)
+    sc = 1.0 / np.sqrt(D)
+    try:
+        ref = None
+        for nb in range(0, 9):
+            sv.sv_set_tuning("attn_batches", nb)
+            r = run_step(inp, k, vis_len=vis_len, txt_len=txt_len, dev=None if ref is None else ref["dev"])
+            if ref is None:
+                ref = r
+                oa, ol, _ = oracle.sparse_decode_attn(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"],
+                                                      r["idx"], r["count"], txt_len=txt_len, scale=sc)
+            assert np.array_equal(r["idx"], ref["idx"]) and np.array_equal(r["count"], ref["count"]), nb
+            assert np.abs(r["out"] - oa).max() <= 2e-3, (nb, np.abs(r["out"] - oa).max())
+            fin = np.isfinite(ol)
+            assert np.array_equal(np.isneginf(r["lse"]), ~fin), nb
+            assert np.abs(r["lse"] - ol)[fin].max(initial=0.0) <= 2e-3, nb
+    finally:
+        sv.sv_set_tuning("attn_batches", 0)
+    assert_step_matches(inp, k, vis_len=vis_len, txt_len=txt_len, label="planned batches")
+
+
 # ------------------------------------------------------------------ packing (retrieve once per round, decode many tokens)
 @pytest.mark.parametrize("dtype,D,G", [(np.float16, 128, 7), (np.float16, 64, 4), (np.float32, 128, 2), (np.float32, 64, 1)])
 def test_pack_selected_is_a_byte_exact_gather_and_packed_attention_matches(dtype, D, G):
