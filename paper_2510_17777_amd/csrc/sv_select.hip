@@ -13,7 +13,8 @@
 //   3. a scan of the histogram from the top finds the threshold bin and how many of
 //   its members are still needed; its members (at most 1024) are ranked exactly by
 //   (order-preserving uint32 key, index), which yields the threshold pair;
-//   4. ordered compaction: per-wavefront counts, prefix sums, ballot ranks.
+//   4. ordered compaction: counts of kept scores per lane (one workgroup: a lane owns consecutive
+//   positions) or per wavefront (parts), prefix sums, ranks inside a lane or by ballot.
 // If the range is degenerate (all scores equal) or the threshold bin is overfull, an MSD
 // radix select (11 + 11 + 10 bits) on the uint32 keys takes over.  All counting is
 // integer: the result does not depend on the order in which lanes or workgroups run.
