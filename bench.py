@@ -142,7 +142,7 @@ def parse_args():
                          "attention on the packed buffers), the dense baseline and a sweep of keep ratios; adds a "
                          "\"variants\" object to the JSON line")
     ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
-                    help="launch-shape knob for sweeps, e.g. --set attn_chunk=256")
+                    help="launch-shape knob for sweeps, e.g. --set attn_batches=4")
     return ap.parse_args()
 
 
@@ -240,7 +240,7 @@ def main():
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_visual": w.n_vis, "n_text": w.n_txt, "k": w.k, "mode": "folded_layers_one_call",
                    "score_rows_per_block": sv.sv_get_tuning("score_rows_per_block"),
-                   "attn_chunk": sv.sv_get_tuning("attn_chunk")},
+                   "attn_batches": sv.sv_get_tuning("attn_batches") or "planned per call"},
         "step_algorithmic_bytes": algo_bytes,
         "step_achieved_GBps": round(step_gbps, 1),
         "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
