@@ -20,8 +20,8 @@
 // integer: the result does not depend on the order in which lanes or workgroups run.
 //
 // Launch shapes:
-//   * rows of at most 4096 scores: one 1024-lane workgroup per (b, g), scores in
-//     registers, exact min/max as the range;
+//   * rows of at most 16384 scores: one 1024-lane workgroup per (b, g), 4, 8 or 16 scores per
+//     lane in registers, exact min/max as the range;
 //   * longer rows: a single compute unit cannot pull a long row from memory fast
 //     enough, so the row is cut into parts of 8192 scores (at most 8 parts) and three
 //     kernels run over (part, g, b):  A. per-part histogram, the range taken from a
@@ -52,7 +52,12 @@ constexpr int kPartCand = kMaxCand / kMaxParts;   // candidate slots per part
 constexpr int kPartThreads = 256;
 constexpr int kSampleLanes = 64;
 constexpr int kSingleThreads = 1024;
-constexpr int kSingleMaxN = 4096;
+constexpr int kSingleMaxN = 16384;   // one workgroup holds a row of up to 16 scores per lane
+// sv_decode_step takes the candidate filter only for rows beyond one workgroup's reach: up to there,
+// storing the scores and selecting them in one workgroup is as fast (12.5k-token rows) or faster
+// (8k-token rows: 44 against 55 us per step), the sampler's chain of memory trips being what a short
+// scoring launch waits for.
+constexpr int kFilterMinN = kSingleMaxN;
 
 enum : uint32_t { kFlagOk = 0, kFlagDegenerate = 1, kFlagOverfull = 2 };
 
@@ -279,6 +284,17 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
             const float4 v = *reinterpret_cast<const float4*>(s + j0 + i);
             vals[i] = v.x; vals[i + 1] = v.y; vals[i + 2] = v.z; vals[i + 3] = v.w;
         }
+    } else if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {   // block-uniform: 128-bit loads inside the row
+#pragma unroll
+        for (int i = 0; i < ITEMS; i += 4) {
+            if (i + 4 <= my_items) {
+                const float4 v = *reinterpret_cast<const float4*>(s + j0 + i);
+                vals[i] = v.x; vals[i + 1] = v.y; vals[i + 2] = v.z; vals[i + 3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = i; e < i + 4; ++e) vals[e] = e < my_items ? s[j0 + e] : 0.f;
+            }
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? s[j0 + i] : 0.f;
@@ -387,8 +403,11 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
     const int n = live_rows(a.vis_len, b, a.n_vis_max);
     const int kb = a.k < n ? a.k : n;
     if (emit_trivial<kSingleThreads>(a, unit, n, kb, 0, 1, tid)) return;
-    select_block<kSingleMaxN / kSingleThreads, false>(sh, a.scores + unit * a.n_vis_max, a.idx + unit * a.k, n, kb,
-                                                      tid, lane, wave);
+    const float* s = a.scores + unit * a.n_vis_max;
+    int32_t* out = a.idx + unit * a.k;
+    if (n <= 4 * kSingleThreads) select_block<4, false>(sh, s, out, n, kb, tid, lane, wave);         // block-uniform
+    else if (n <= 8 * kSingleThreads) select_block<8, false>(sh, s, out, n, kb, tid, lane, wave);
+    else select_block<kSingleMaxN / kSingleThreads, false>(sh, s, out, n, kb, tid, lane, wave);
 }
 
 // ------------------------------------------------------------------ candidate-filtered shape
@@ -875,7 +894,7 @@ struct SelectPlan { bool single; int parts, part_len, items; };   // items == 0:
 
 SelectPlan plan_select(int n_vis_max) {
     SelectPlan p{};
-    if (n_vis_max <= kSingleMaxN) { p.single = true; p.parts = 1; p.part_len = kSingleMaxN; p.items = 4; return p; }
+    if (n_vis_max <= kSingleMaxN) { p.single = true; p.parts = 1; p.part_len = kSingleMaxN; p.items = kSingleMaxN / kSingleThreads; return p; }
     if (n_vis_max <= kPartLen * kMaxParts) {
         p.parts = (n_vis_max + kPartLen - 1) / kPartLen;
         p.part_len = kPartLen;
@@ -926,7 +945,7 @@ FilterLayout layout_filter_ws(int dtype, int D, size_t units, int n_vis_max) {
 // Long rows whose expected candidate count (the sample-rank fraction of the row, plus four standard
 // deviations of that fraction) fits the on-chip ranking.
 bool filtered_select_applies(int dtype, int D, int n_vis_max, int k) {
-    if (n_vis_max <= kSingleMaxN || k <= 0 || k >= n_vis_max) return false;
+    if (n_vis_max <= kFilterMinN || k <= 0 || k >= n_vis_max) return false;
     if (filter_tile_rows(dtype, D, 0, n_vis_max, kFiltMaxTiles) == 0) return false;
     const double S = presample_rows();
     const double mean = S * (double)k / (double)n_vis_max;

@@ -140,10 +140,12 @@ def test_strided_token_major_cache_layout():
 
 # ------------------------------------------------------------------ selection, integer-exact
 @pytest.mark.parametrize("n,k", [(1, 1), (63, 5), (64, 64), (1000, 1), (4096, 512), (4097, 4000),
-                                 (8192, 512), (16385, 300), (33000, 1650), (50176, 2509), (53000, 17),
+                                 (8192, 512), (8193, 8000), (12545, 1254), (16383, 9), (16384, 8192), (16385, 300),
+                                 (33000, 1650), (50176, 2509), (53000, 17),
                                  (65536, 65535), (70000, 3500), (200001, 777)])
 def test_select_is_bit_exact_on_given_scores(n, k):
-    """Every launch shape of the selection (one workgroup; 4096-score parts; streaming parts) and
+    """Every launch shape of the selection (one workgroup with 4, 8 or 16 scores per lane, rows aligned
+    to 16 bytes or not; 8192-score parts; streaming parts) and
     every data-dependent path (value bins, exact ranking, radix fallback) against a full sort."""
     import paper_2510_17777_amd as sv
     rng = np.random.default_rng(n + k)
@@ -183,8 +185,8 @@ def _exact_sets(r, k, vis_len):
     return np.array_equal(r["count"], want_cnt) and np.array_equal(r["idx"], want_idx)
 
 
-@pytest.mark.parametrize("dtype,D,G,Nv,k", [(np.float16, 128, 7, 20000, 1000), (np.float16, 64, 2, 9001, 450),
-                                           (np.float32, 128, 1, 6000, 300), (np.float32, 64, 4, 12345, 100),
+@pytest.mark.parametrize("dtype,D,G,Nv,k", [(np.float16, 128, 7, 20000, 1000), (np.float16, 64, 2, 17001, 850),
+                                           (np.float32, 128, 1, 16500, 800), (np.float32, 64, 4, 22345, 200),
                                            (np.float16, 64, 1, 70001, 1500)])   # > 256 tiles of 256 rows: wider tiles
 def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     """Long rows inside sv_decode_step: the sampled threshold + candidate slots + on-chip ranking must
@@ -230,7 +232,7 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
 def test_filtered_selection_degenerate_rows():
     """All keys equal (every row is a candidate: more than fit on chip -> whole-row fallback), rows
     shorter than k, shorter than the sample, and empty rows, on a shape that takes the filtered path."""
-    Nv, k = 9000, 500
+    Nv, k = 17000, 900
     inp = rand_inputs(41, 5, 4, 2, 128, Nv, 8, np.float16)
     inp["k_vis"][0] = inp["k_vis"][0, :, :1]
     vis_len = np.array([Nv, 0, 1, 300, 700], np.int32)
