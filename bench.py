@@ -19,6 +19,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -97,6 +98,23 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
                           buf.out, buf.lse, buf.workspace)
         torch.cuda.synchronize()
         del qm, mscores, mws
+    if w.layers > 1 and shape.vis_len is None and B % w.layers == 0:
+        # the step as a model would issue it: one sv_decode_step per layer, one after the other
+        per = B // w.layers
+        views = []
+        for l in range(w.layers):
+            sl = slice(l * per, (l + 1) * per)
+            ls = sv.make_shape(d["q"][sl], d["k_vis"][sl], d["k_txt"][sl], k)
+            views.append((ls, sl))
+        lbuf = sv.DecodeBuffers(views[0][0], dev, with_scores=False)
+
+        def sequential():
+            for ls, sl in views:
+                sv.sv_decode_step(ls, d["q"][sl], d["k_vis"][sl], d["v_vis"][sl], d["k_txt"][sl], d["v_txt"][sl], None,
+                                  lbuf.idx, lbuf.count, lbuf.out, lbuf.lse, lbuf.workspace)
+        out["step_sequential_per_layer_calls_us"] = timed(sequential)
+        out["step_sequential_calls"] = w.layers
+        del lbuf
     if shape.vis_len is None:   # dense baseline and sweep: uniform visual length only
         Nv = shape.n_vis_max
         dshape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], Nv, txt_len=shape.txt_len)
@@ -222,6 +240,35 @@ def main():
         sv.sv_set_tuning("step_stages", 3)
     score_us = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
 
+    # What a plain read stream reaches on this device: the same visual-K bytes read once by a kernel
+    # that does nothing else (context for the roofline fraction; the peak stays the published 8 TB/s).
+    sink = torch.zeros(sv.READ_SINK_BYTES // 4, dtype=torch.int32, device=dev)
+    kv_flat = d["k_vis"].reshape(-1)
+    probe_bytes = kv_flat.numel() * kv_flat.element_size() // 16 * 16
+    pevs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for _ in range(2):
+        sv.sv_read_bytes(kv_flat, probe_bytes, sink)
+    for a, b in pevs:
+        a.record(stream)
+        sv.sv_read_bytes(kv_flat, probe_bytes, sink)
+        b.record(stream)
+    torch.cuda.synchronize()
+    probe_gbps = probe_bytes / (float(np.mean([a.elapsed_time(b) for a, b in pevs])) * 1e-3) / 1e9
+
+    # Clocks while the device is busy with steps (best effort; the box decides power state and clocks).
+    clocks = None
+    try:
+        for i in range(max(200, int(0.5 / (us_per_step * 1e-6)))):
+            step(i)
+        r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        torch.cuda.synchronize()
+        txt = r.stdout[r.stdout.index("{"):]
+        card = next(iter(json.loads(txt).values()))
+        clocks = {k.strip(" :").replace(" clock speed", "_MHz"): int("".join(c for c in v if c.isdigit()))
+                  for k, v in card.items() if "clock speed" in k}
+    except Exception:   # noqa: BLE001 - the tool may be missing or print something else
+        torch.cuda.synchronize()
+
     # Leave the buffers holding the result of a step with query 0 for the parity report.
     step(0)
     torch.cuda.synchronize()
@@ -247,7 +294,10 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": round(score_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(w.cfg), "bytes_per_launch": k_bytes,
-                     "mean_us": round(float(score_us.mean()), 2), "median_us": round(float(np.median(score_us)), 2)},
+                     "mean_us": round(float(score_us.mean()), 2), "median_us": round(float(np.median(score_us)), 2),
+                     "read_stream_probe_GBps": round(probe_gbps, 1),
+                     "frac_of_read_stream_probe": round(score_gbps / probe_gbps, 4)},
+        "clocks_under_load": clocks,
         "input_gen_s": round(t_gen, 1),
     }
 

@@ -205,6 +205,15 @@ sv_status sv_decode_step(const sv_shape *shape, const void *q,
  */
 sv_status sv_copy_bytes(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid, not part of the decode path: reads `bytes` (a multiple of 16) from the 16-byte
+ * aligned DEVICE pointer `src` once, as a plain stream of 128-bit loads, and folds what it read into
+ * `sink` (DEVICE, 16-byte aligned, SV_READ_SINK_BYTES bytes, caller-owned; its content afterwards is
+ * unspecified, it only keeps the loads alive).  Its rate is what a kernel that has to read every byte once can reach on the device.
+ */
+#define SV_READ_SINK_BYTES 4096
+sv_status sv_read_bytes(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *sv_strerror(sv_status status);
 

@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.sv_pack_selected.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.sv_copy_bytes.restype = ctypes.c_int
     lib.sv_copy_bytes.argtypes = [vp, vp, sz, vp]
+    lib.sv_read_bytes.restype = ctypes.c_int
+    lib.sv_read_bytes.argtypes = [vp, sz, vp, vp]
     lib.sv_strerror.restype = ctypes.c_char_p
     lib.sv_strerror.argtypes = [ctypes.c_int]
     lib.sv_set_tuning.restype = ctypes.c_int
@@ -232,6 +234,16 @@ def sv_pack_selected(shape: Shape, k_vis, v_vis, idx, count, k_pack, v_pack, str
 
 def sv_copy_bytes(dst: torch.Tensor, src: torch.Tensor, nbytes: int, stream=None) -> None:
     _check(load_library().sv_copy_bytes(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)), "sv_copy_bytes")
+
+
+READ_SINK_BYTES = 4096
+
+
+def sv_read_bytes(src: torch.Tensor, nbytes: int, sink: torch.Tensor, stream=None) -> None:
+    """Plain read stream over nbytes of src (measurement aid); sink: READ_SINK_BYTES bytes on the device."""
+    if sink.numel() * sink.element_size() < READ_SINK_BYTES:
+        raise ValueError("sink too small")
+    _check(load_library().sv_read_bytes(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), "sv_read_bytes")
 
 
 class DecodeBuffers:

@@ -355,6 +355,12 @@ sv_status sv_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) 
     return from_hip(sv::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
 }
 
+sv_status sv_read_bytes(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+    if (!src || !sink) return SV_ERR_NULL;
+    if (bytes % 16 || !aligned16(src) || !aligned16(sink)) return SV_ERR_ALIGN;
+    return from_hip(sv::launch_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
 const char* sv_strerror(sv_status status) {
     switch (status) {
         case SV_OK: return "ok";

@@ -137,6 +137,8 @@ size_t select_workspace_bytes(int B, int Hkv, int n_vis_max);
 
 // Plain copy of `bytes` (multiple of 16) device bytes; calibration aid for traffic counters.
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+constexpr int kReadSinkWords = 1024;   // words of the sink buffer of launch_read (a power of two)
+hipError_t launch_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 // Tokens per workgroup of the matrix-core attention kernel for head_dim 64 (fixed by its register layout).
 int attn_mfma_chunk();

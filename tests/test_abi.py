@@ -176,6 +176,24 @@ def test_strerror_and_tuning_knobs():
     assert sv.sv_get_tuning("attn_chunk") == 256
     sv.sv_set_tuning("attn_chunk", 0)
     assert sv.sv_get_tuning("attn_chunk") == before
+    assert sv.sv_get_tuning("attn_batches") == 0                    # planned per call
+    assert lib.sv_set_tuning(b"attn_batches", 9) == E_SHAPE
+    assert lib.sv_set_tuning(b"attn_batches", -1) == E_SHAPE
+    sv.sv_set_tuning("attn_batches", 5)
+    assert sv.sv_get_tuning("attn_batches") == 5
+    sv.sv_set_tuning("attn_batches", 0)
+
+
+def test_measurement_aids_check_their_arguments():
+    lib = sv.load_library()
+    lib.sv_read_bytes.restype = ctypes.c_int
+    lib.sv_read_bytes.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.sv_read_bytes(None, 1024, 4096, None) == E_NULL
+    assert lib.sv_read_bytes(4096, 1024, None, None) == E_NULL
+    assert lib.sv_read_bytes(4096, 1000, 8192, None) == E_ALIGN     # not a multiple of 16
+    assert lib.sv_read_bytes(4100, 1024, 8192, None) == E_ALIGN
+    assert lib.sv_copy_bytes(None, 4096, 1024, None) == E_NULL
+    assert lib.sv_copy_bytes(4096, 8192, 1001, None) == E_ALIGN
 
 
 def test_binding_refuses_host_tensors():
