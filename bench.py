@@ -224,9 +224,18 @@ def main():
     wall = time.perf_counter() - t0
     us_per_step = wall / args.steps * 1e6
 
+    # Spread of single steps: the same steps again, each between two events on the launch stream.
+    stream = torch.cuda.current_stream()
+    sevs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (a, b) in enumerate(sevs):
+        a.record(stream)
+        step(i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    step_ev_us = np.array([a.elapsed_time(b) * 1e3 for a, b in sevs])
+
     # The dominant kernel alone: the scoring launch exactly as the step issues it (the "step_stages"
     # knob makes sv_decode_step return after it), bracketed by events on the stream it is launched on.
-    stream = torch.cuda.current_stream()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for _ in range(args.steps)]
     sv.sv_set_tuning("step_stages", 1)
@@ -291,6 +300,9 @@ def main():
         "step_algorithmic_bytes": algo_bytes,
         "step_achieved_GBps": round(step_gbps, 1),
         "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "step_event_us": {"median": round(float(np.median(step_ev_us)), 2),
+                          "p10": round(float(np.percentile(step_ev_us, 10)), 2),
+                          "p90": round(float(np.percentile(step_ev_us, 90)), 2)},
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": round(score_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(w.cfg), "bytes_per_launch": k_bytes,
