@@ -27,6 +27,8 @@ struct FilterArgs {
     int32_t k;
     int32_t rank_override;  // > 0: use this sample rank for t_lo (tests force the fallbacks with it)
     uint32_t epoch;         // differs from call to call: marks the hint words of this call
+    uint32_t* gen;          // [1] bumped by every filtered selection: added to epoch on the device, so that replays
+                            // of a captured call (same arguments, same epoch) still tag their hint words apart
     int32_t test_mode;      // 0; tests: every third tile ignores the hint (1: keeps nothing, 2: keeps all)
 };
 

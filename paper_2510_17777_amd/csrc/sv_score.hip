@@ -56,8 +56,11 @@ __device__ __forceinline__ int sample_rank(int n, int kb) {
     return (int)ceilf(m + 5.f * sqrtf(m) + 4.f);
 }
 
+// Tag of this launch's hint words: the host's call counter plus the device's generation word.
+__device__ __forceinline__ uint32_t launch_epoch(const ScoreArgs& a) { return a.filt.epoch + a.filt.gen[0]; }
+
 __device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, float t_lo) {
-    const uint64_t word = ((uint64_t)a.filt.epoch << 32) | (uint64_t)__float_as_uint(t_lo);
+    const uint64_t word = ((uint64_t)launch_epoch(a) << 32) | (uint64_t)__float_as_uint(t_lo);
     __hip_atomic_store(a.filt.hint + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -187,7 +190,11 @@ void score_kernel(const ScoreArgs a) {
     // The row's threshold word is requested up front: all but the first tiles of the launch find it
     // ready, and the request rides along with the first loads instead of delaying the tile's end.
     uint64_t hint_word = 0;
-    if (kFilter) hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t epoch = 0;
+    if (kFilter) {
+        hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        epoch = launch_epoch(a);
+    }
 
     float qs[EPL];
 #pragma unroll
@@ -210,7 +217,7 @@ void score_kernel(const ScoreArgs a) {
         // t_lo of the row: the sampler's word, once it carries this call's epoch
         float t_lo = -INFINITY;
         for (int poll = 0; poll < kHintPolls; ++poll) {
-            if ((uint32_t)(hint_word >> 32) == a.filt.epoch) {
+            if ((uint32_t)(hint_word >> 32) == epoch) {
                 t_lo = __uint_as_float((uint32_t)hint_word);
                 if (t_lo != t_lo) t_lo = -INFINITY;   // a stale word that happens to carry the epoch
                 break;

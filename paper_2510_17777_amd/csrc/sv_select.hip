@@ -458,6 +458,8 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         word[u] = make_uint4(0u, 0u, 0u, 0u);
         if (w < f.n_tiles * kFiltRec16) word[u] = recs[w];
     }
+    // The scoring launch that read the generation word is over, the next one has not begun: bump it.
+    if (unit == 0 && tid == 0) f.gen[0] = f.gen[0] + 1u;
     const int n = live_rows(a.vis_len, b, a.n_vis_max);
     const int kb = a.k < n ? a.k : n;
     if (emit_trivial<NT>(a, unit, n, kb, 0, 1, tid)) return;
@@ -925,7 +927,7 @@ WsLayout layout_select_ws(size_t units, int parts) {
 }  // namespace
 
 namespace {
-struct FilterLayout { size_t hint, tiles, overflow, total; };
+struct FilterLayout { size_t hint, gen, tiles, overflow, total; };
 
 // Sized for the smallest tile the scoring kernel can be asked for, so that the layout does not
 // depend on the launch-shape knobs.
@@ -935,6 +937,7 @@ FilterLayout layout_filter_ws(int dtype, int D, size_t units, int n_vis_max) {
     const size_t max_tiles = (size_t)(n_vis_max + granule - 1) / granule;
     size_t off = 0;
     l.hint = off; off += align256(units * sizeof(uint64_t));
+    l.gen = off; off += align256(sizeof(uint32_t));
     l.tiles = off; off += align256(units * max_tiles * kFiltRec16 * sizeof(uint4));
     l.overflow = off; off += align256(units * ((size_t)n_vis_max + 512) * sizeof(uint2));
     l.total = off;
@@ -966,6 +969,7 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     char* p = static_cast<char*>(base);
     FilterArgs f{};
     f.hint = reinterpret_cast<uint64_t*>(p + l.hint);
+    f.gen = reinterpret_cast<uint32_t*>(p + l.gen);
     f.tiles = reinterpret_cast<uint4*>(p + l.tiles);
     f.overflow = reinterpret_cast<uint2*>(p + l.overflow);
     f.tile_rows = filter_tile_rows(dtype, D, requested_tile_rows, n_vis_max, kFiltMaxTiles);

@@ -244,6 +244,46 @@ def test_filtered_selection_degenerate_rows():
     assert_step_matches(inp, k, vis_len=vis_len, label="filtered degenerate")
 
 
+def test_step_captured_in_a_hip_graph_replays_exactly_with_fresh_queries():
+    """sv_decode_step allocates nothing and never synchronises, so a caller may capture it.  A captured
+    call replays with the arguments (and the host's call counter) it was recorded with: the tag that
+    tells this launch's threshold words from the previous launch's comes from a device-side generation
+    word as well, so a replay must not take the thresholds the previous replay left behind.  Each replay
+    runs with a fresh query written into the captured buffer, between eager steps and synchronisations,
+    and must equal the eager step on the same query bit for bit, and the oracle's selection of the
+    GPU's scores."""
+    import paper_2510_17777_amd as sv
+    B, Hkv, G, D, Nv, Nt, k = 2, 2, 7, 128, 20000, 200, 1000
+    inp = rand_inputs(99, B, Hkv * G, Hkv, D, Nv, Nt, np.float16)
+    d = {n: torch.from_numpy(inp[n]).to("cuda:0") for n in inp}
+    shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], k)
+    cap, eag = sv.DecodeBuffers(shape, "cuda:0"), sv.DecodeBuffers(shape, "cuda:0")
+
+    def call(buf):
+        sv.sv_decode_step(shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], buf.scores, buf.idx,
+                          buf.count, buf.out, buf.lse, buf.workspace)
+    call(cap)                      # first call outside the capture: one-time host set-up happens here
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(cap)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for trial in range(4):
+        scale = (1.0, 3.0, 0.2, 1.0)[trial]     # shifts the score distribution, and with it the thresholds
+        q = (rng.standard_normal((B, Hkv * G, D)) * scale).astype(np.float16)
+        d["q"].copy_(torch.from_numpy(q))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {n: getattr(cap, n).cpu().numpy() for n in ("scores", "idx", "count", "out", "lse")}
+        call(eag)
+        torch.cuda.synchronize()
+        for n in got:
+            assert np.array_equal(got[n], getattr(eag, n).cpu().numpy()), (trial, n)
+        want_idx, want_cnt = oracle.topk_select(got["scores"].astype(np.float64), k, None)
+        assert np.array_equal(got["idx"], want_idx) and np.array_equal(got["count"], want_cnt), trial
+
+
 # ------------------------------------------------------------------ edge cases
 def test_k_zero_text_only_and_no_text_visual_only():
     inp = rand_inputs(21, 2, 8, 2, 128, 300, 40, np.float16)
