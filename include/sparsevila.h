@@ -35,6 +35,11 @@
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
  *   stream).  All work is enqueued asynchronously; nothing synchronises the
  *   host.  Results are valid once the caller has synchronised the stream.
+ *   Calls that share a workspace must be ordered on one stream (or by the
+ *   caller's events).  Since nothing allocates or synchronises, a call may be
+ *   captured into a HIP graph once the same entry point has run uncaptured on
+ *   that device (one-time host set-up happens on first use); replays see the
+ *   tensors' current contents.
  * Errors.  The return value is an sv_status; SV_OK is 0, errors are negative.
  *   Arguments are checked on the host before anything is launched, so a failed
  *   call has launched nothing.  A launch failure reported by the HIP runtime
