@@ -19,7 +19,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
-import subprocess
+import glob
 import sys
 import time
 
@@ -265,18 +265,23 @@ def main():
     probe_gbps = probe_bytes / (float(np.mean([a.elapsed_time(b) for a, b in pevs])) * 1e-3) / 1e9
 
     # Clocks while the device is busy with steps (best effort; the box decides power state and clocks).
+    # Read from sysfs: starting another program from a process that holds the GPU is not an option.
     clocks = None
     try:
-        for i in range(max(200, int(0.5 / (us_per_step * 1e-6)))):
+        for i in range(max(200, int(0.2 / (us_per_step * 1e-6)))):
             step(i)
-        r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        clocks = {}
+        for name in ("sclk", "mclk"):
+            for path in sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{name}")):
+                cur = [ln for ln in open(path).read().splitlines() if ln.rstrip().endswith("*")]
+                if cur:
+                    clocks[f"{name}_MHz"] = int("".join(ch for ch in cur[0].split(":")[1] if ch.isdigit()))
+                    break
         torch.cuda.synchronize()
-        txt = r.stdout[r.stdout.index("{"):]
-        card = next(iter(json.loads(txt).values()))
-        clocks = {k.strip(" :").replace(" clock speed", "_MHz"): int("".join(c for c in v if c.isdigit()))
-                  for k, v in card.items() if "clock speed" in k}
-    except Exception:   # noqa: BLE001 - the tool may be missing or print something else
+        clocks = clocks or None
+    except Exception:   # noqa: BLE001 - files may be missing or unreadable
         torch.cuda.synchronize()
+        clocks = None
 
     # Leave the buffers holding the result of a step with query 0 for the parity report.
     step(0)
