@@ -66,7 +66,7 @@ __device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, f
 
 // Sampler workgroup of one (b, g): 512 sample scores -> t_lo.
 template <typename T, int D>
-__device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int g, float* samp, uint32_t* s_probe) {
+__device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int g, float* samp) {
     constexpr int EPL = Chunk<T>::kElems;
     constexpr int LPR = D / EPL;
     constexpr int RPW = kWave / LPR;
@@ -89,12 +89,10 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
         if (tid == 0) publish_hint(a, unit, -INFINITY);
         return;
     }
-    float qs[EPL];
-    summed_query<T>(a, b, g, c, qs);
     const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
     const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
-    for (int r = 0; r < ROUNDS; ++r) {
-        Chunk<T> kc[U];
+    Chunk<T> kc[U];
+    auto request = [&](int r) {   // the U sample rows of this lane group in round r
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = r * ROUND_ROWS + (wave * U + u) * RPW + grp;   // sample number
@@ -103,39 +101,47 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
             row = row < n ? row : n - 1;
             kc[u] = load_chunk(kbase + (int64_t)row * a.k_sn);
         }
+    };
+    // The rounds are a chain of dependent memory trips (the register budget of the streaming loop allows
+    // U loads per lane in flight): the first round is requested before the query, so that the two share a trip.
+    request(0);
+    float qs[EPL];
+    summed_query<T>(a, b, g, c, qs);
+    for (int r = 0; r < ROUNDS; ++r) {
+        float sc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < EPL; ++i) s = fmaf(kc[u].at(i), qs[i], s);
-            s = group_sum<LPR>(s) * a.scale;
+            sc[u] = s;
+        }
+        if (r + 1 < ROUNDS) request(r + 1);   // the next trip starts before the lane-group sums of this one
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float s = group_sum<LPR>(sc[u]) * a.scale;
             if (c == 0) samp[r * ROUND_ROWS + (wave * U + u) * RPW + grp] = s;
         }
     }
     __syncthreads();
-    // The rank-th largest sample, four bits of its order-preserving key per round: every
-    // wavefront holds all keys (kSample/64 per lane) and counts the keys >= four of the
-    // fifteen probes; the digit is the number of probes that still have `rank` keys.
+    // The rank-th largest sample by binary search on its order-preserving key, most significant bit
+    // first, in one wavefront with all keys in registers (kSample/64 per lane): a bit stays set if at
+    // least `rank` keys are >= the probe.  No barrier, no LDS traffic in the loop.  The search stops after
+    // kSearchBits bits; the bits below stay zero, i.e. t_lo comes out a hair lower (relative 2^-15 of
+    // its magnitude): still a valid threshold, a handful more candidates.
+    if (wave != 0) return;
     constexpr int KPL = kSample / kWave;
+    constexpr int kSearchBits = 24;
     uint32_t keys[KPL];
 #pragma unroll
     for (int i = 0; i < KPL; ++i) keys[i] = score_key(samp[lane + i * kWave]);
     uint32_t prefix = 0;
-    for (int round = 0; round < 8; ++round) {
-        const int shift = 28 - 4 * round;
-        uint32_t* probe_cnt = s_probe + (round & 1) * 16;
-        for (int d = wave + 1; d < 16; d += kScoreWaves) {
-            const uint32_t probe = prefix | ((uint32_t)d << shift);
-            int cnt = 0;
+    for (int bit = 31; bit > 31 - kSearchBits; --bit) {
+        const uint32_t probe = prefix | (1u << bit);
+        int cnt = 0;
 #pragma unroll
-            for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
-            if (lane == 0) probe_cnt[d] = (uint32_t)cnt;
-        }
-        __syncthreads();
-        uint32_t digit = 0;
-#pragma unroll
-        for (int d = 1; d < 16; ++d) digit += probe_cnt[d] >= (uint32_t)rank ? 1u : 0u;
-        prefix |= digit << shift;
+        for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
+        if (cnt >= rank) prefix = probe;   // wave-uniform
     }
     if (tid == 0) {
         const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
@@ -157,7 +163,6 @@ void score_kernel(const ScoreArgs a) {
     static_assert(U <= LPR, "store lane selection needs U <= lanes per row");
     // kFilter: the tile's scores (tile role) or the sample scores (sampler role)
     __shared__ float s_val[kFilter ? kFilterMaxTileRows : 1];
-    __shared__ uint32_t s_probe[kFilter ? 32 : 1];
     __shared__ uint2 s_pair[kFilter ? kFilterMaxTileRows : 1];
 
     int b, g, tile;
@@ -165,7 +170,7 @@ void score_kernel(const ScoreArgs a) {
         const int units = a.B * a.Hkv;
         int id = (int)blockIdx.x;
         if (id < units) {
-            sample_threshold<T, D>(a, id / a.Hkv, id % a.Hkv, s_val, s_probe);
+            sample_threshold<T, D>(a, id / a.Hkv, id % a.Hkv, s_val);
             return;
         }
         id -= units;
