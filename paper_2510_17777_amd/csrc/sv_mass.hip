@@ -358,7 +358,9 @@ __device__ __forceinline__ void colsum_stage(const KeyStage<KB>& st, int lane, c
 }
 
 template <int D>
-__global__ __launch_bounds__(kMassThreads) void mass_colsum_kernel(const MassArgs a) {
+// Three wavefronts per SIMD: at 168 registers the compiler keeps the matrix results in VGPRs (no copies from
+// accumulation registers) and still pipelines the key tiles; measured against two wavefronts per SIMD below.
+__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void mass_colsum_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
     constexpr int KT = kColBlockKeys / 16;   // key tiles per sub-block
     __shared__ KeyStage<KB> stage[2];
