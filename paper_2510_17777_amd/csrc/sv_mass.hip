@@ -120,6 +120,15 @@ __device__ __forceinline__ void tile_logits(const half8_t (&qa)[kTilesPerWave][K
         for (int t = 0; t < NTL; ++t) sv[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], sv[t], 0, 0, 0);
 }
 
+// Maximum over the 16 lanes that hold one query row's key columns.
+__device__ __forceinline__ float row_max16(float x) {
+    x = fmaxf(x, dpp_move<kDppQuadXor1>(x));
+    x = fmaxf(x, dpp_move<kDppQuadXor2>(x));
+    x = fmaxf(x, dpp_move<kDppRowHalfMirror>(x));
+    x = fmaxf(x, dpp_move<kDppRowMirror>(x));
+    return x;
+}
+
 // The loads of the query tiles must not count as outstanding inside the key loops: the wait inserted
 // for them there would also wait for the keys fetched one stage ahead.
 __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
@@ -145,12 +154,17 @@ __device__ __forceinline__ void rowstat_plain_stage(const KeyStage<KB>& st, int 
         }
         float4_t(&y)[kTilesPerWave] = sv[kt & 1];
         if (kInit && kt == 0) {
+            // the reference of a row: the largest of its first 16 logits, shared by the row's 16 lanes.  (A lane's
+            // own first logit is a poor reference: one lane-row in fifty then meets a logit 2^8 above it
+            // later in the block, and every such meeting sends the whole wavefront through the raise path.)
 #pragma unroll
             for (int t = 0; t < NTL; ++t)
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    ref[t][rr] = y[t][rr] * c2;
-                    l[t][rr] = 1.f;
+                    const float x = y[t][rr] * c2;
+                    const float r0 = row_max16(x);
+                    ref[t][rr] = r0;
+                    l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
                 }
             continue;
         }
@@ -181,7 +195,8 @@ __device__ __forceinline__ void rowstat_plain_stage(const KeyStage<KB>& st, int 
 }
 
 template <int D>
-__global__ __launch_bounds__(kMassThreads) void mass_rowstat_kernel(const MassArgs a) {
+// Two wavefronts per SIMD (256 registers): one register more and the compiler settles for one.
+__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mass_rowstat_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
     __shared__ KeyStage<KB> stage[2];
     const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -295,11 +310,7 @@ __global__ __launch_bounds__(kMassThreads) void mass_rowstat_kernel(const MassAr
         for (int rr = 0; rr < 4; ++rr) {
             const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the plain stages leave dead tiles untouched,
             const float lmine = t < ntl ? l[t][rr] : 0.f;          // the masked ones compute them: drop both
-            float mx = mine;
-            mx = fmaxf(mx, dpp_move<kDppQuadXor1>(mx));
-            mx = fmaxf(mx, dpp_move<kDppQuadXor2>(mx));
-            mx = fmaxf(mx, dpp_move<kDppRowHalfMirror>(mx));
-            mx = fmaxf(mx, dpp_move<kDppRowMirror>(mx));
+            const float mx = row_max16(mine);
             const float e = mine > -INFINITY ? __builtin_amdgcn_exp2f(mine - mx) : 0.f;
             const float lt = group_sum<16>(lmine * e);
             if (row == 0) {
