@@ -30,6 +30,8 @@
 // one multiply-add before v_exp_f32).  Pass 1 keeps a reference per (lane, row) that is raised only
 // when a logit exceeds it by more than 2^8: the usual case is one multiply-add, one exponential and
 // one add per element, and the sums stay far from overflow.
+#include <type_traits>
+
 #include "sv_device.h"
 #include "sv_kernels.h"
 
@@ -177,6 +179,8 @@ __device__ __forceinline__ void rowstat_plain_stage(const KeyStage<KB>& st, int 
                 top = fmaxf(top, y[t][rr]);
             }
         if (__ballot(top > kRaiseAbove) != 0ull) {   // rare: some reference is raised to the logit that tops it
+            asm volatile("" ::: "memory");   // emits nothing; keeps this block a real branch (as straight-line
+                                             // selects it cost every key tile 16 more exponentials per lane)
 #pragma unroll
             for (int t = 0; t < NTL; ++t)
 #pragma unroll
@@ -260,7 +264,11 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
                 }
             }
     };
-    if (key0 < k_end) {   // block-uniform
+    // The stage loop is instantiated once per count of live row tiles and chosen outside the loop: a switch
+    // inside it made the compiler shuffle the 32 state registers between the arms at every stage (as many
+    // moves and selects as useful instructions).
+    auto run = [&](auto ntl_c) __attribute__((always_inline)) {
+        constexpr int NTL = decltype(ntl_c)::value;
         fetch(key0);
         wait_for_loads();
         put(stage[0]);
@@ -271,25 +279,10 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             const bool more = s0 + kStageKeys < k_end;   // block-uniform
             if (more) fetch(s0 + kStageKeys);
             const bool plain = s0 >= nt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
-            if (plain && (ref_ready || s0 == key0)) {
-                const KeyStage<KB>& st = stage[cur];
-                if (ref_ready) {
-                    switch (ntl) {
-                        case 4: rowstat_plain_stage<KB, 4, false>(st, lane, qa, c2, ref, l); break;
-                        case 3: rowstat_plain_stage<KB, 3, false>(st, lane, qa, c2, ref, l); break;
-                        case 2: rowstat_plain_stage<KB, 2, false>(st, lane, qa, c2, ref, l); break;
-                        case 1: rowstat_plain_stage<KB, 1, false>(st, lane, qa, c2, ref, l); break;
-                        default: break;
-                    }
-                } else {   // first stage of the block: nothing seen so far
-                    switch (ntl) {
-                        case 4: rowstat_plain_stage<KB, 4, true>(st, lane, qa, c2, ref, l); break;
-                        case 3: rowstat_plain_stage<KB, 3, true>(st, lane, qa, c2, ref, l); break;
-                        case 2: rowstat_plain_stage<KB, 2, true>(st, lane, qa, c2, ref, l); break;
-                        case 1: rowstat_plain_stage<KB, 1, true>(st, lane, qa, c2, ref, l); break;
-                        default: break;
-                    }
-                }
+            if (plain && ref_ready) {
+                rowstat_plain_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
+            } else if (plain && s0 == key0) {   // first stage of the block: nothing seen so far
+                rowstat_plain_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
                 ref_ready = true;
             } else {
 #pragma unroll 1
@@ -300,6 +293,15 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             if (more) put(stage[cur ^ 1]);
             __syncthreads();
             cur ^= 1;
+        }
+    };
+    if (key0 < k_end) {   // block-uniform
+        switch (ntl) {    // wave-uniform
+            case 4: run(std::integral_constant<int, 4>{}); break;
+            case 3: run(std::integral_constant<int, 3>{}); break;
+            case 2: run(std::integral_constant<int, 2>{}); break;
+            case 1: run(std::integral_constant<int, 1>{}); break;
+            default: run(std::integral_constant<int, 0>{}); break;
         }
     }
     // merge the 16 key columns of a row (the lanes of a 16-lane row hold the same rows), store per block
