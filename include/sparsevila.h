@@ -194,7 +194,8 @@ sv_status sv_pack_selected(const sv_shape *shape, const void *k_vis, const void 
 /*
  * Steps 1 -> 2 -> 3 on one stream.  scores may be NULL (the workspace then
  * holds them); idx and count are outputs and are required when k > 0; with k == 0
- * count, if given, is set to 0.
+ * count, if given, is set to 0, no key is scored and `scores` is left untouched
+ * (text-only attention needs no retrieval).
  */
 sv_status sv_decode_step(const sv_shape *shape, const void *q,
                          const void *k_vis, const void *v_vis,

@@ -35,15 +35,18 @@ def assert_step_matches(inp, k, vis_len=None, txt_len=None, scale=0.0, label="")
     r = run_step(inp, k, vis_len=vis_len, txt_len=txt_len, scale=scale)
     o = oracle.decode_step(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"], k,
                            vis_len=vis_len, txt_len=txt_len, scale=sc)
-    # step 1: scores inside the rounding bound; padding is -inf
-    live = np.isfinite(o["scores"])
-    assert np.array_equal(np.isneginf(r["scores"]), ~live), label
-    err = np.abs(r["scores"].astype(np.float64) - o["scores"])[live]
-    assert np.all(err <= score_error_bound(inp, sc)[live]), f"{label}: score error {err.max():.3e}"
-    # step 2a: integer-exact selection for the scores the GPU itself produced
-    idx_same, cnt_same = oracle.topk_select(r["scores"].astype(np.float64), k, vis_len)
-    assert np.array_equal(r["count"], cnt_same), label
-    assert np.array_equal(r["idx"], idx_same), label
+    # step 1: scores inside the rounding bound; padding is -inf  (k == 0: nothing is scored, by contract)
+    if k > 0:
+        live = np.isfinite(o["scores"])
+        assert np.array_equal(np.isneginf(r["scores"]), ~live), label
+        err = np.abs(r["scores"].astype(np.float64) - o["scores"])[live]
+        assert np.all(err <= score_error_bound(inp, sc)[live]), f"{label}: score error {err.max():.3e}"
+        # step 2a: integer-exact selection for the scores the GPU itself produced
+        idx_same, cnt_same = oracle.topk_select(r["scores"].astype(np.float64), k, vis_len)
+        assert np.array_equal(r["count"], cnt_same), label
+        assert np.array_equal(r["idx"], idx_same), label
+    else:
+        assert not r["count"].any(), label
     # step 2b: against the oracle's own float64 scores, with the tie-band rule
     rep = check_index_sets(o["scores"], k, vis_len, r["idx"], r["count"])
     assert rep.ok, f"{label}: {rep.failures[:3]}"
@@ -282,6 +285,39 @@ def test_step_captured_in_a_hip_graph_replays_exactly_with_fresh_queries():
             assert np.array_equal(got[n], getattr(eag, n).cpu().numpy()), (trial, n)
         want_idx, want_cnt = oracle.topk_select(got["scores"].astype(np.float64), k, None)
         assert np.array_equal(got["idx"], want_idx) and np.array_equal(got["count"], want_cnt), trial
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_seeded_random_shapes_match_the_oracle(case):
+    """Shapes nobody chose by hand: batch, heads, group size, head_dim, dtype, lengths (ragged or not), k and
+    the softmax scale drawn from a seeded generator; the whole rule set of assert_step_matches each time.
+    Row lengths reach past 16384 in some cases, so that every selection path and both attention kernels
+    for fp16 caches come up."""
+    rng = np.random.default_rng(4200 + case)
+    D = int(rng.choice([64, 128]))
+    dtype = np.float16 if rng.random() < 0.7 else np.float32
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16]))
+    Hkv = int(rng.integers(1, 4))
+    B = int(rng.integers(1, 5))
+    Nv = int(rng.choice([rng.integers(1, 200), rng.integers(200, 5000), rng.integers(5000, 17000),
+                         rng.integers(17000, 40000)]))
+    Nt = int(rng.choice([0, 1, rng.integers(2, 100), rng.integers(100, 900)]))
+    k = int(rng.choice([0, 1, max(1, Nv // 20), max(1, Nv // 4), Nv, Nv + 5]))
+    if Nt == 0 and k == 0:
+        k = 1
+    ragged = rng.random() < 0.5
+    vis_len = rng.integers(0, Nv + 1, size=B).astype(np.int32) if ragged else None
+    txt_len = rng.integers(0 if k > 0 else 1, Nt + 1, size=B).astype(np.int32) if (ragged and Nt > 0) else None
+    if vis_len is not None and txt_len is None and Nt == 0:
+        vis_len = np.maximum(vis_len, 1)            # an empty token list is its own test
+    if vis_len is not None and txt_len is not None:
+        vis_len = np.where((txt_len == 0) & (vis_len == 0), 1, vis_len).astype(np.int32)
+    scale = 0.0 if rng.random() < 0.6 else float(rng.uniform(0.02, 0.3))
+    inp = rand_inputs(5000 + case, B, Hkv * G, Hkv, D, Nv, max(Nt, 1) if Nt == 0 else Nt, dtype)
+    if Nt == 0:
+        inp["k_txt"], inp["v_txt"] = inp["k_txt"][:, :, :0], inp["v_txt"][:, :, :0]
+    label = f"case {case}: B={B} Hkv={Hkv} G={G} D={D} {np.dtype(dtype).name} Nv={Nv} Nt={Nt} k={k} ragged={ragged}"
+    assert_step_matches(inp, k, vis_len=vis_len, txt_len=txt_len, scale=scale, label=label)
 
 
 # ------------------------------------------------------------------ edge cases
