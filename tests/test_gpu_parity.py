@@ -526,6 +526,42 @@ def test_attention_mass_scores_match_the_oracle(D, G, Tq, Nv, Nt):
     assert check_index_sets(want, k, vis_len, idx, cnt).ok
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_attention_mass_seeded_random_shapes(case):
+    """sv_score_visual_mass on shapes drawn from a seeded generator (head_dim, group size, question length up
+    to the 256-row limit, key counts across the 64-key stages and 1024-key blocks of the kernels, ragged
+    lengths, a question longer than the live text): masses within 2e-4 relative, lse within 1e-4."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(7700 + case)
+    D = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 4, 7, 8, 16]))
+    Tq = int(rng.integers(1, 256 // G + 1))
+    Hkv, B = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    Nv = int(rng.choice([rng.integers(1, 70), rng.integers(70, 1100), rng.integers(1100, 4200)]))
+    Nt = int(rng.choice([1, rng.integers(2, 70), rng.integers(70, 1300)]))
+    f = lambda *sh: rng.standard_normal(sh, dtype=np.float32).astype(np.float16)
+    qm, kv, kt = f(B, Tq, Hkv * G, D), f(B, Hkv, Nv, D), f(B, Hkv, Nt, D)
+    ragged = rng.random() < 0.6
+    vis_len = rng.integers(0, Nv + 1, size=B).astype(np.int32) if ragged else None
+    txt_len = rng.integers(0, Nt + 1, size=B).astype(np.int32) if ragged else None
+    want, want_lse = oracle.score_visual_mass(qm, kv, kt, vis_len=vis_len, txt_len=txt_len)
+    dq, dkv, dkt = (torch.from_numpy(x).to("cuda:0") for x in (qm, kv, kt))
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, 1, vis_len=vis_len, txt_len=txt_len)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, Tq, Hkv * G), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, lse)
+    torch.cuda.synchronize()
+    got, got_lse = scores.cpu().numpy(), lse.cpu().numpy()
+    label = f"case {case}: B={B} Hkv={Hkv} G={G} Tq={Tq} D={D} Nv={Nv} Nt={Nt} ragged={ragged}"
+    live = np.isfinite(want)
+    assert np.array_equal(np.isneginf(got), ~live), label
+    err = np.abs(np.where(live, got, 0.0).astype(np.float64) - np.where(live, want, 0.0))
+    assert np.all(err <= 2e-4 * np.where(live, want, 0.0) + 1e-9), f"{label}: mass error {err.max():.3e}"
+    fin = np.isfinite(want_lse)
+    assert np.array_equal(np.isfinite(got_lse), fin), label
+    assert np.abs(np.where(fin, got_lse, 0.0) - np.where(fin, want_lse, 0.0)).max(initial=0.0) <= 1e-4, label
+
+
 def test_query_agnostic_salience_of_an_encoder_layer_by_the_same_mass_kernel():
     """Section 3.1 (prefill): for encoders without a summary token the salience of visual token j is the
     attention it receives averaged over all tokens, computed without forming the N x N matrix.  That is the
