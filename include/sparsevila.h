@@ -117,9 +117,11 @@ sv_status sv_score_visual(const sv_shape *shape, const void *q, const void *k_vi
  * idx[b,g,0..count) = the k_b = min(k, vis_len[b]) indices j < vis_len[b] with
  * the largest scores[b,g,j]; equal scores are resolved toward the lower index
  * (+0 and -0 are equal); indices ascend; idx[b,g,count..k) = -1;
- * count[b,g] = k_b.  Only the visual fields and k of the shape are used.
+ * count[b,g] = k_b.  Only the visual fields, k, and -- for the layout of the
+ * workspace -- dtype and head_dim of the shape are used.
  * Integer-exact: the result is the unique set defined above for the given
- * float scores.  k == 0 is valid (nothing is written to idx).
+ * float scores.  k == 0 is valid (nothing is written to idx).  Rows of up to
+ * 16384 scores need no workspace (workspace may be NULL for such shapes).
  */
 sv_status sv_topk_select(const sv_shape *shape, const float *scores,
                          int32_t *idx, int32_t *count,

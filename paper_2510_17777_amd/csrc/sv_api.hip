@@ -233,8 +233,28 @@ sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, i
         st = check_workspace(w, workspace, workspace_bytes);
         if (st != SV_OK) return st;
     }
-    return from_hip(sv::launch_select(make_select_args(s, w, workspace, scores, idx, count),
-                                      static_cast<hipStream_t>(stream)));
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const sv::SelectArgs sel = make_select_args(s, w, workspace, scores, idx, count);
+    const bool filter = w.filt_bytes > 0 && w.sel_bytes > 0 &&
+                        (g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter) != 0;
+    if (filter) {   // long rows: one pass over the scores hands the on-chip selection its candidates
+        sv::ScoreArgs sa{};
+        sa.scores = const_cast<float*>(scores);   // read only: write_scores = 1 keeps the selection's fallback off it
+        sa.vis_len = s->vis_len;
+        sa.B = s->batch; sa.Hkv = s->n_kv_heads; sa.G = s->n_q_heads / s->n_kv_heads;
+        sa.D = s->head_dim; sa.n_vis_max = s->n_vis_max; sa.dtype = s->dtype;
+        sa.write_scores = 1;
+        sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, s->dtype, s->head_dim,
+                                             s->batch, s->n_kv_heads, s->n_vis_max, s->k,
+                                             g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block
+                                                                               : kDefaultScoreRows);
+        sa.filt.rank_override = g_tuning.filter_rank;
+        sa.filt.test_mode = g_tuning.filter_test_mode;
+        sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
+        if (sv::launch_scores_filter(sa, hs) != hipSuccess) return SV_ERR_LAUNCH;
+        return from_hip(sv::launch_select_filtered(sel, sa, hs));
+    }
+    return from_hip(sv::launch_select(sel, hs));
 }
 
 sv_status sv_sparse_decode_attn(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,

@@ -116,6 +116,9 @@ size_t mass_workspace_bytes(int B, int Hkv, int n_txt_max, int n_vis_max);
 int mass_max_rows();   // most query rows (tokens x heads of a group) the kernels hold
 
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
+// Scores given (a.scores, read only): sampler + tile workgroups hand the selection the candidates of every row
+// (a.filt from carve_filter_workspace); then launch_select_filtered with a.write_scores = 1.
+hipError_t launch_scores_filter(const ScoreArgs& a, hipStream_t stream);
 hipError_t launch_pack(const PackArgs& a, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, hipStream_t stream);
 hipError_t launch_attend(const AttnArgs& a, hipStream_t stream);   // partials + combine

@@ -64,6 +64,37 @@ __device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, f
     __hip_atomic_store(a.filt.hint + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The rank-th largest of the kSample scores in samp (LDS), by one wavefront: binary search on the
+// order-preserving key, most significant bit first, all keys in registers (kSample/64 per lane): a bit
+// stays set if at least `rank` keys are >= the probe.  No barrier, no LDS traffic in the loop.  The search
+// stops after kSearchBits bits; the bits below stay zero, i.e. the result comes out a hair lower (relative
+// 2^-15 of its magnitude): still a valid threshold, a handful more candidates.
+__device__ __forceinline__ float rank_statistic(const float* samp, int rank, int lane) {
+    constexpr int KPL = kSample / kWave;
+    constexpr int kSearchBits = 24;
+    uint32_t keys[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) keys[i] = score_key(samp[lane + i * kWave]);
+    uint32_t prefix = 0;
+    for (int bit = 31; bit > 31 - kSearchBits; --bit) {
+        const uint32_t probe = prefix | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
+        if (cnt >= rank) prefix = probe;   // wave-uniform
+    }
+    const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
+    return __uint_as_float(u);
+}
+
+// Row number of sample i of a (b, g) with n live rows: stratified, with a jitter that differs per (b, g).
+__device__ __forceinline__ int sample_row_of(int i, int n, int64_t unit) {
+    const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
+    int row = (int)(((int64_t)i * n) / kSample);
+    if (stratum > 1) row += (int)(mix32((uint32_t)unit * 0x9E3779B9u + (uint32_t)i) % (uint32_t)stratum);
+    return row < n ? row : n - 1;
+}
+
 // Sampler workgroup of one (b, g): 512 sample scores -> t_lo.
 template <typename T, int D>
 __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int g, float* samp) {
@@ -90,16 +121,12 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
         return;
     }
     const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
-    const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
     Chunk<T> kc[U];
     auto request = [&](int r) {   // the U sample rows of this lane group in round r
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = r * ROUND_ROWS + (wave * U + u) * RPW + grp;   // sample number
-            int row = (int)(((int64_t)i * n) / kSample);
-            if (stratum > 1) row += (int)(mix32((uint32_t)unit * 0x9E3779B9u + (uint32_t)i) % (uint32_t)stratum);
-            row = row < n ? row : n - 1;
-            kc[u] = load_chunk(kbase + (int64_t)row * a.k_sn);
+            kc[u] = load_chunk(kbase + (int64_t)sample_row_of(i, n, unit) * a.k_sn);
         }
     };
     // The rounds are a chain of dependent memory trips (the register budget of the streaming loop allows
@@ -124,28 +151,64 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
         }
     }
     __syncthreads();
-    // The rank-th largest sample by binary search on its order-preserving key, most significant bit
-    // first, in one wavefront with all keys in registers (kSample/64 per lane): a bit stays set if at
-    // least `rank` keys are >= the probe.  No barrier, no LDS traffic in the loop.  The search stops after
-    // kSearchBits bits; the bits below stay zero, i.e. t_lo comes out a hair lower (relative 2^-15 of
-    // its magnitude): still a valid threshold, a handful more candidates.
     if (wave != 0) return;
-    constexpr int KPL = kSample / kWave;
-    constexpr int kSearchBits = 24;
-    uint32_t keys[KPL];
-#pragma unroll
-    for (int i = 0; i < KPL; ++i) keys[i] = score_key(samp[lane + i * kWave]);
-    uint32_t prefix = 0;
-    for (int bit = 31; bit > 31 - kSearchBits; --bit) {
-        const uint32_t probe = prefix | (1u << bit);
-        int cnt = 0;
-#pragma unroll
-        for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(keys[i] >= probe));
-        if (cnt >= rank) prefix = probe;   // wave-uniform
+    const float t_lo = rank_statistic(samp, rank, lane);
+    if (tid == 0) publish_hint(a, unit, t_lo);
+}
+
+// End of a tile, one wavefront: waits (bounded) for the row's threshold and stores the tile's record.
+// s_val holds the tile's scores (-inf past the live rows), s_pair is scratch for the pairs.
+__device__ __forceinline__ void emit_tile_record(const ScoreArgs& a, int64_t unit, int tile, int row_begin, int row_end,
+                                                 const float* s_val, uint2* s_pair, uint64_t hint_word, uint32_t epoch,
+                                                 int lane) {
+    // t_lo of the row: the sampler's word, once it carries this call's epoch
+    float t_lo = -INFINITY;
+    for (int poll = 0; poll < kHintPolls; ++poll) {
+        if ((uint32_t)(hint_word >> 32) == epoch) {
+            t_lo = __uint_as_float((uint32_t)hint_word);
+            if (t_lo != t_lo) t_lo = -INFINITY;   // a stale word that happens to carry the epoch
+            break;
+        }
+        __builtin_amdgcn_s_sleep(32);
+        hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (tid == 0) {
-        const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
-        publish_hint(a, unit, __uint_as_float(u));
+    if (a.filt.test_mode != 0 && tile % 3 == 1) t_lo = a.filt.test_mode == 1 ? INFINITY : -INFINITY;
+    // Record of this tile, 8-byte items: {count, t_lo used}, {largest pair score, 0}, then the first kFilterPrimary
+    // pairs in row order; records of consecutive tiles are adjacent.  A tile with more pairs also
+    // writes all of them to its overflow rows.  Every store covers whole 128-byte lines (the
+    // tail of the last line is zero-filled): a partially written line costs a fetch of the rest.
+    const int64_t tile_id = unit * a.filt.n_tiles + tile;
+    uint2* rec = reinterpret_cast<uint2*>(a.filt.tiles) + tile_id * (kFilterPrimary + 2);
+    uint2* ovf = a.filt.overflow + tile_id * a.rows_per_block;
+    const int tile_len = row_end - row_begin;
+    const uint64_t lanes_below = (1ull << lane) - 1ull;
+    uint32_t count = 0;
+    float top = -INFINITY;
+    for (int r = lane; r - lane < tile_len; r += kWave) {   // wave-uniform trip count
+        const float v = r < tile_len ? s_val[r] : -INFINITY;
+        const bool is_cand = r < tile_len && v >= t_lo && v > -INFINITY;
+        if (is_cand) top = fmaxf(top, v);
+        const uint64_t cand_lanes = __ballot(is_cand);
+        if (is_cand)
+            s_pair[count + (uint32_t)__popcll(cand_lanes & lanes_below)] =
+                make_uint2(__float_as_uint(v), (uint32_t)(row_begin + r));
+        count += (uint32_t)__popcll(cand_lanes);
+    }
+    top = wave_max(top);
+    __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+    {
+        const uint32_t items = min(count + 2u, (uint32_t)kFilterPrimary + 2u);
+        if ((uint32_t)lane < ((items + 15u) & ~15u)) {
+            uint2 v = make_uint2(0u, 0u);
+            if (lane == 0) v = make_uint2(count, __float_as_uint(t_lo));
+            else if (lane == 1) v = make_uint2(__float_as_uint(top), 0u);
+            else if (lane >= 2 && (uint32_t)lane < items) v = s_pair[lane - 2];
+            rec[lane] = v;
+        }
+    }
+    if (count > (uint32_t)kFilterPrimary) {
+        const uint32_t padded = min((count + 15u) & ~15u, (uint32_t)a.rows_per_block);
+        for (uint32_t f = lane; f < padded; f += kWave) ovf[f] = f < count ? s_pair[f] : make_uint2(0u, 0u);
     }
 }
 
@@ -219,56 +282,57 @@ void score_kernel(const ScoreArgs a) {
     if (kFilter) {
         __syncthreads();
         if (wave != 0) return;
-        // t_lo of the row: the sampler's word, once it carries this call's epoch
-        float t_lo = -INFINITY;
-        for (int poll = 0; poll < kHintPolls; ++poll) {
-            if ((uint32_t)(hint_word >> 32) == epoch) {
-                t_lo = __uint_as_float((uint32_t)hint_word);
-                if (t_lo != t_lo) t_lo = -INFINITY;   // a stale word that happens to carry the epoch
-                break;
-            }
-            __builtin_amdgcn_s_sleep(32);
-            hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (a.filt.test_mode != 0 && tile % 3 == 1) t_lo = a.filt.test_mode == 1 ? INFINITY : -INFINITY;
-        // Record of this tile, 8-byte items: {count, t_lo used}, {largest pair score, 0}, then the first kFilterPrimary
-        // pairs in row order; records of consecutive tiles are adjacent.  A tile with more pairs also
-        // writes all of them to its overflow rows.  Every store covers whole 128-byte lines (the
-        // tail of the last line is zero-filled): a partially written line costs a fetch of the rest.
-        const int64_t tile_id = unit * a.filt.n_tiles + tile;
-        uint2* rec = reinterpret_cast<uint2*>(a.filt.tiles) + tile_id * (kFilterPrimary + 2);
-        uint2* ovf = a.filt.overflow + tile_id * a.rows_per_block;
-        const int tile_len = row_end - row_begin;
-        const uint64_t lanes_below = (1ull << lane) - 1ull;
-        uint32_t count = 0;
-        float top = -INFINITY;
-        for (int r = lane; r - lane < tile_len; r += kWave) {   // wave-uniform trip count
-            const float v = r < tile_len ? s_val[r] : -INFINITY;
-            const bool is_cand = r < tile_len && v >= t_lo && v > -INFINITY;
-            if (is_cand) top = fmaxf(top, v);
-            const uint64_t cand_lanes = __ballot(is_cand);
-            if (is_cand)
-                s_pair[count + (uint32_t)__popcll(cand_lanes & lanes_below)] =
-                    make_uint2(__float_as_uint(v), (uint32_t)(row_begin + r));
-            count += (uint32_t)__popcll(cand_lanes);
-        }
-        top = wave_max(top);
-        __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
-        {
-            const uint32_t items = min(count + 2u, (uint32_t)kFilterPrimary + 2u);
-            if ((uint32_t)lane < ((items + 15u) & ~15u)) {
-                uint2 v = make_uint2(0u, 0u);
-                if (lane == 0) v = make_uint2(count, __float_as_uint(t_lo));
-                else if (lane == 1) v = make_uint2(__float_as_uint(top), 0u);
-                else if (lane >= 2 && (uint32_t)lane < items) v = s_pair[lane - 2];
-                rec[lane] = v;
-            }
-        }
-        if (count > (uint32_t)kFilterPrimary) {
-            const uint32_t padded = min((count + 15u) & ~15u, (uint32_t)a.rows_per_block);
-            for (uint32_t f = lane; f < padded; f += kWave) ovf[f] = f < count ? s_pair[f] : make_uint2(0u, 0u);
-        }
+        emit_tile_record(a, unit, tile, row_begin, row_end, s_val, s_pair, hint_word, epoch, lane);
     }
+}
+
+// The same hand-over for scores that already exist (sv_topk_select on long rows): the sampler workgroups
+// read 512 of the row's scores, the tile workgroups read their scores instead of computing them.  One
+// pass over the scores replaces the two of the three-kernel selection.
+__global__ __launch_bounds__(kScoreThreads) void scores_filter_kernel(const ScoreArgs a, const int groups) {
+    __shared__ float s_val[kScoreWaves][kFilterMaxTileRows];
+    __shared__ uint2 s_pair[kScoreWaves][kFilterMaxTileRows];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int units = a.B * a.Hkv;
+    int id = (int)blockIdx.x;
+    if (id < units) {   // sampler of unit id
+        const int64_t unit = id;
+        const int n = live_rows_of(a, id / a.Hkv);
+        const int kb = a.filt.k < n ? a.filt.k : n;
+        if (kb == 0 || kb == n) {   // the selection handles these rows without candidates
+            if (tid == 0) publish_hint(a, unit, INFINITY);
+            return;
+        }
+        const int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb);
+        if (rank > kSample - kSample / 8) {
+            if (tid == 0) publish_hint(a, unit, -INFINITY);
+            return;
+        }
+        const float* __restrict__ srow = a.scores + unit * a.n_vis_max;
+        float* samp = &s_val[0][0];
+        for (int i = tid; i < kSample; i += kScoreThreads) samp[i] = srow[sample_row_of(i, n, unit)];
+        __syncthreads();
+        if (wave != 0) return;
+        const float t_lo = rank_statistic(samp, rank, lane);
+        if (tid == 0) publish_hint(a, unit, t_lo);
+        return;
+    }
+    // a workgroup takes kScoreWaves consecutive tiles of one row, one per wavefront (a tile is 1-2 KB of
+    // scores: with a workgroup per tile the launch was bound by the life of its 22 k tiny workgroups)
+    id -= units;
+    const int unit = id / groups;
+    const int tile = (id - unit * groups) * kScoreWaves + wave;
+    if (tile >= a.filt.n_tiles) return;   // wave-uniform; no barrier below
+    const int n = live_rows_of(a, unit / a.Hkv);
+    const int row_begin = tile * a.rows_per_block;
+    const int row_end = min(row_begin + a.rows_per_block, a.n_vis_max);
+    const uint64_t hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t epoch = launch_epoch(a);
+    const float* __restrict__ srow = a.scores + (int64_t)unit * a.n_vis_max;
+    for (int r = lane; r < row_end - row_begin; r += kWave)
+        s_val[wave][r] = row_begin + r < n ? srow[row_begin + r] : -INFINITY;
+    __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+    emit_tile_record(a, unit, tile, row_begin, row_end, s_val[wave], s_pair[wave], hint_word, epoch, lane);
 }
 
 template <typename T, int D>
@@ -297,6 +361,18 @@ hipError_t launch_typed(const ScoreArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t launch_scores_filter(const ScoreArgs& a, hipStream_t stream) {
+    if (!a.filt.tiles || a.filt.tile_rows <= 0) return hipErrorInvalidValue;
+    ScoreArgs k = a;
+    k.rows_per_block = a.filt.tile_rows;
+    const int groups = (a.filt.n_tiles + kScoreWaves - 1) / kScoreWaves;   // workgroups per row
+    const uint64_t blocks = (uint64_t)a.B * a.Hkv * (1u + (uint64_t)groups);
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(scores_filter_kernel, dim3((unsigned)blocks), dim3(kScoreThreads), 0, stream, k, groups);
+    return hipGetLastError();
+}
 
 int score_row_granule(int dtype, int D) {
     const int epl = dtype == 0 ? 8 : 4;
