@@ -138,10 +138,11 @@ struct RadixShared {
 // MSD radix select over one whole row by one workgroup of NT lanes, re-reading the
 // scores in every pass; wavefront w owns the contiguous range [w*seg, (w+1)*seg).
 // `map` (or nullptr) renames position j to map[j] on output; it must ascend with j.
+// `stride` (in elements) separates consecutive scores in s and consecutive names in map (2: interleaved pairs).
 template <int NT>
 __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* __restrict__ s,
                                                  int32_t* __restrict__ out, int n, int kb, int tid, int lane, int wave,
-                                                 const int32_t* map = nullptr) {
+                                                 const int32_t* map = nullptr, int stride = 1) {
     constexpr int NW = NT / kWave;
     const int seg = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
     const int seg_items = seg / kWave;
@@ -149,7 +150,7 @@ __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* _
     const int seg_end = min(n, wave * seg + seg);
     auto key_at = [&](int i) -> uint32_t {   // 0 = "no key" (valid keys are never 0)
         const int j = j0 + i * kWave;
-        return j < seg_end ? score_key(s[j]) : 0u;
+        return j < seg_end ? score_key(s[(int64_t)j * stride]) : 0u;
     };
     uint32_t prefix = 0, mask = 0;
     uint32_t need = (uint32_t)kb;
@@ -199,7 +200,7 @@ __device__ __forceinline__ void radix_select_row(RadixShared& sh, const float* _
         const uint32_t slot = pos + (uint32_t)__popcll(keep_ballot & lane_lt);
         if (keep && slot < (uint32_t)kb) {   // slot < kb holds for finite scores
             const int j = j0 + i * kWave;
-            out[slot] = map ? map[j] : j;
+            out[slot] = map ? map[(int64_t)j * stride] : j;
         }
         pos += (uint32_t)__popcll(keep_ballot);
         eq_seen += (uint32_t)__popcll(eq_ballot);
@@ -265,7 +266,8 @@ struct SingleShared {
 // Requires 0 < kb < n.  Lane t owns the ITEMS consecutive positions from t*ITEMS on, so that thread
 // order is position order: the output slot of a lane's first kept score is one prefix sum over the
 // lanes' kept counts away, and a score's bin is computed once and kept in a register.
-// kVec: s and map are 16-byte aligned LDS arrays with ITEMS*1024 readable entries (vector reads).
+// kVec: the scores and their names sit interleaved in LDS -- s points at 16-byte aligned (score, name) pairs,
+// ITEMS*1024 of them readable, map is ignored -- and are read with 128-bit loads, two pairs at a time.
 // With have_range the caller vouches that lo_hint <= every score and supplies an upper value for the
 // binning (scores above it share the top bin); the workgroup then skips its own min/max pass.
 template <int ITEMS, bool kVec>
@@ -274,15 +276,17 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
                                              const int32_t* map = nullptr, bool have_range = false,
                                              float lo_hint = 0.f, float hi_hint = 0.f) {
     constexpr int NT = kSingleThreads, NW = NT / kWave;
-    static_assert(!kVec || ITEMS % 4 == 0, "vector reads take four entries");
+    static_assert(!kVec || ITEMS % 2 == 0, "vector reads take two pairs");
     const int j0 = tid * ITEMS;
     const int my_items = min(max(n - j0, 0), ITEMS);
     float vals[ITEMS];
+    int32_t pair_name[kVec ? ITEMS : 1];
     if (kVec) {
 #pragma unroll
-        for (int i = 0; i < ITEMS; i += 4) {
-            const float4 v = *reinterpret_cast<const float4*>(s + j0 + i);
-            vals[i] = v.x; vals[i + 1] = v.y; vals[i + 2] = v.z; vals[i + 3] = v.w;
+        for (int i = 0; i < ITEMS; i += 2) {
+            const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint2*>(s) + j0 + i);
+            vals[i] = __uint_as_float(v.x); pair_name[i] = (int32_t)v.y;
+            vals[i + 1] = __uint_as_float(v.z); pair_name[i + 1] = (int32_t)v.w;
         }
     } else if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {   // block-uniform: 128-bit loads inside the row
 #pragma unroll
@@ -371,12 +375,9 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
             uint32_t pos = block_inclusive_scan<NT>(n_keep, sh.rx.wave_tot2, lane, wave) - n_keep;
             if (keep_bits) {
                 int32_t name[ITEMS];
-                if (map && kVec) {
+                if (kVec) {
 #pragma unroll
-                    for (int i = 0; i < ITEMS; i += 4) {
-                        const int4 v = *reinterpret_cast<const int4*>(map + j0 + i);
-                        name[i] = v.x; name[i + 1] = v.y; name[i + 2] = v.z; name[i + 3] = v.w;
-                    }
+                    for (int i = 0; i < ITEMS; ++i) name[i] = pair_name[i];
                 } else {
 #pragma unroll
                     for (int i = 0; i < ITEMS; ++i) name[i] = (map && i < my_items) ? map[j0 + i] : j0 + i;
@@ -390,7 +391,8 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
     }
     if (!done) {   // block-uniform
         __syncthreads();
-        radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave, map);
+        if (kVec) radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave, reinterpret_cast<const int32_t*>(s) + 1, 2);
+        else radix_select_row<NT>(sh.rx, s, out, n, kb, tid, lane, wave, map);
     }
 }
 
@@ -426,12 +428,12 @@ constexpr int kFiltLoads = kFiltMaxTiles * kFiltRec16 / kSingleThreads;
 
 struct FilteredShared {
     SingleShared sel;
-    alignas(16) float c_score[kFiltCap];
-    alignas(16) int32_t c_row[kFiltCap];
-    uint32_t tile_cnt[kFiltMaxTiles];
+    alignas(16) uint2 c_pair[kFiltCap];      // (score bits, row) of the candidates, in row order
+    alignas(16) uint32_t tile_cnt[kFiltMaxTiles];
     float tile_tlo[kFiltMaxTiles];          // the threshold each tile used
     float tile_top[kFiltMaxTiles];          // the largest candidate score of each tile
-    uint32_t tile_off[kFiltMaxTiles + 1];   // exclusive prefix sums of the tile counts
+    alignas(16) uint32_t tile_off[kFiltMaxTiles + 4];   // exclusive prefix sums of the tile counts, then their total
+    uint32_t max_cnt;                        // the largest tile count
     uint32_t wave_tot[16];
     float tlo_min[4], tlo_max[4], top_max[4];
     uint32_t n_at_or_above;
@@ -477,17 +479,23 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     }
     if (tid == 0) sh.n_at_or_above = 0;
     __syncthreads();
-    const uint32_t my_count = tid < kFiltMaxTiles ? sh.tile_cnt[tid] : 0u;
     if (tid < kFiltMaxTiles) {   // wavefronts 0..3: the spread of the thresholds the tiles used
         const float t = sh.tile_tlo[tid];
         const float lo = wave_min_f(tid < live_tiles ? t : INFINITY);
         const float hi = wave_max(tid < live_tiles ? t : -INFINITY);
         const float top = wave_max(tid < live_tiles ? sh.tile_top[tid] : -INFINITY);
         if (lane == 0) { sh.tlo_min[wave] = lo; sh.tlo_max[wave] = hi; sh.top_max[wave] = top; }
+    } else if (wave == kFiltMaxTiles / kWave) {   // one more wavefront: prefix sums of the tile counts, four tiles per lane
+        static_assert(kFiltMaxTiles == 4 * kWave, "four tiles per lane");
+        const uint4 c4 = reinterpret_cast<const uint4*>(sh.tile_cnt)[lane];
+        const uint32_t s4 = c4.x + c4.y + c4.z + c4.w;
+        const uint32_t incl = wave_inclusive_scan(s4, lane);
+        const uint32_t base = incl - s4;
+        reinterpret_cast<uint4*>(sh.tile_off)[lane] =
+            make_uint4(base, base + c4.x, base + c4.x + c4.y, base + c4.x + c4.y + c4.z);
+        const float big = wave_max((float)max(max(c4.x, c4.y), max(c4.z, c4.w)));   // counts <= 512: exact in fp32
+        if (lane == kWave - 1) { sh.tile_off[kFiltMaxTiles] = incl; sh.max_cnt = (uint32_t)big; }
     }
-    const uint32_t incl = block_inclusive_scan<NT>(my_count, sh.wave_tot, lane, wave);
-    if (tid < kFiltMaxTiles) sh.tile_off[tid] = incl - my_count;
-    if (tid == NT - 1) sh.tile_off[kFiltMaxTiles] = incl;
     __syncthreads();
     const uint32_t m = sh.tile_off[kFiltMaxTiles];   // candidates of the row
 
@@ -512,51 +520,41 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         if (tile < live_tiles && q > 0) {
             const uint32_t off = sh.tile_off[tile], cnt = sh.tile_cnt[tile];
             const uint32_t e = 2 * (q - 1);
-            if (e < cnt) {
-                sh.c_score[off + e] = __uint_as_float(word[u].x);
-                sh.c_row[off + e] = (int32_t)word[u].y;
-            }
-            if (e + 1 < cnt) {
-                sh.c_score[off + e + 1] = __uint_as_float(word[u].z);
-                sh.c_row[off + e + 1] = (int32_t)word[u].w;
-            }
+            if (e < cnt) sh.c_pair[off + e] = make_uint2(word[u].x, word[u].y);
+            if (e + 1 < cnt) sh.c_pair[off + e + 1] = make_uint2(word[u].z, word[u].w);
         }
     }
     // The fuller tiles: their remaining pairs from the overflow rows (which hold all pairs of such a tile).
     // Lane q of a tile's 31 takes pairs 62 + (q - 1) + 31 i.  The loads of i < 2 (tiles of up to 124
     // candidates) are all issued before any is used: one more trip through memory, not one per tile.
-    constexpr uint32_t kStride = kFiltRec16 - 1;
-    uint2 ov[kFiltLoads][2];
+    if (sh.max_cnt > (uint32_t)kFiltPrimary) {   // block-uniform
+        constexpr uint32_t kStride = kFiltRec16 - 1;
+        uint2 ov[kFiltLoads][2];
 #pragma unroll
-    for (int u = 0; u < kFiltLoads; ++u) {
-        const int w = tid + u * NT;
-        const int tile = w / kFiltRec16, q = w % kFiltRec16;
-        const uint32_t cnt = (tile < live_tiles && q > 0) ? sh.tile_cnt[tile] : 0u;
-#pragma unroll
-        for (uint32_t i = 0; i < 2; ++i) {
-            const uint32_t x = kFiltPrimary + (q - 1) + i * kStride;
-            ov[u][i] = make_uint2(0u, 0u);
-            if (x < cnt) ov[u][i] = ovf[(int64_t)tile * f.tile_rows + x];
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < kFiltLoads; ++u) {
-        const int w = tid + u * NT;
-        const int tile = w / kFiltRec16, q = w % kFiltRec16;
-        if (tile < live_tiles && q > 0) {
-            const uint32_t off = sh.tile_off[tile], cnt = sh.tile_cnt[tile];
+        for (int u = 0; u < kFiltLoads; ++u) {
+            const int w = tid + u * NT;
+            const int tile = w / kFiltRec16, q = w % kFiltRec16;
+            const uint32_t cnt = (tile < live_tiles && q > 0) ? sh.tile_cnt[tile] : 0u;
 #pragma unroll
             for (uint32_t i = 0; i < 2; ++i) {
                 const uint32_t x = kFiltPrimary + (q - 1) + i * kStride;
-                if (x < cnt) {
-                    sh.c_score[off + x] = __uint_as_float(ov[u][i].x);
-                    sh.c_row[off + x] = (int32_t)ov[u][i].y;
-                }
+                ov[u][i] = make_uint2(0u, 0u);
+                if (x < cnt) ov[u][i] = ovf[(int64_t)tile * f.tile_rows + x];
             }
-            for (uint32_t x = kFiltPrimary + (q - 1) + 2 * kStride; x < cnt; x += kStride) {   // rare: > 124 candidates
-                const uint2 v = ovf[(int64_t)tile * f.tile_rows + x];
-                sh.c_score[off + x] = __uint_as_float(v.x);
-                sh.c_row[off + x] = (int32_t)v.y;
+        }
+#pragma unroll
+        for (int u = 0; u < kFiltLoads; ++u) {
+            const int w = tid + u * NT;
+            const int tile = w / kFiltRec16, q = w % kFiltRec16;
+            if (tile < live_tiles && q > 0) {
+                const uint32_t off = sh.tile_off[tile], cnt = sh.tile_cnt[tile];
+#pragma unroll
+                for (uint32_t i = 0; i < 2; ++i) {
+                    const uint32_t x = kFiltPrimary + (q - 1) + i * kStride;
+                    if (x < cnt) sh.c_pair[off + x] = ov[u][i];
+                }
+                for (uint32_t x = kFiltPrimary + (q - 1) + 2 * kStride; x < cnt; x += kStride)   // rare: > 124 candidates
+                    sh.c_pair[off + x] = ovf[(int64_t)tile * f.tile_rows + x];
             }
         }
     }
@@ -567,7 +565,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
     const float t_max = fmaxf(fmaxf(sh.tlo_max[0], sh.tlo_max[1]), fmaxf(sh.tlo_max[2], sh.tlo_max[3]));
     if (t_min != t_max) {   // block-uniform
         uint32_t c = 0;
-        for (uint32_t i = tid; i < m; i += NT) c += sh.c_score[i] >= t_max ? 1u : 0u;
+        for (uint32_t i = tid; i < m; i += NT) c += __uint_as_float(sh.c_pair[i].x) >= t_max ? 1u : 0u;
         c = wave_inclusive_scan(c, lane);
         if (lane == kWave - 1 && c > 0) atomicAdd(&sh.n_at_or_above, c);
         __syncthreads();
@@ -577,17 +575,17 @@ __global__ __launch_bounds__(kSingleThreads) void select_filtered_kernel(const S
         }
     }
     if (m == (uint32_t)kb) {   // every candidate is kept
-        for (uint32_t i = tid; i < m; i += NT) out[i] = sh.c_row[i];
+        for (uint32_t i = tid; i < m; i += NT) out[i] = (int32_t)sh.c_pair[i].y;
         return;
     }
     // every candidate is >= its tile's threshold >= t_min, and none exceeds the largest tile maximum
     const float top = fmaxf(fmaxf(sh.top_max[0], sh.top_max[1]), fmaxf(sh.top_max[2], sh.top_max[3]));
     const bool have_range = t_min > -INFINITY && top < INFINITY && top > t_min;
+    const float* pairs = reinterpret_cast<const float*>(sh.c_pair);
     if (m <= (uint32_t)(8 * NT))   // block-uniform: the usual case keeps eight candidates per lane
-        select_block<8, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min, top);
+        select_block<8, true>(sh.sel, pairs, out, (int)m, kb, tid, lane, wave, nullptr, have_range, t_min, top);
     else
-        select_block<kFiltCap / NT, true>(sh.sel, sh.c_score, out, (int)m, kb, tid, lane, wave, sh.c_row, have_range, t_min,
-                                          top);
+        select_block<kFiltCap / NT, true>(sh.sel, pairs, out, (int)m, kb, tid, lane, wave, nullptr, have_range, t_min, top);
 }
 
 // ------------------------------------------------------------------ multi-part shape
