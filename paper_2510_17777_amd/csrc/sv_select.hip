@@ -130,7 +130,7 @@ __device__ __forceinline__ ThresholdBin find_threshold_bin(const uint32_t* hist,
 }
 
 struct RadixShared {
-    uint32_t hist[kBins];
+    alignas(16) uint32_t hist[kBins];
     uint32_t wave_tot[16], wave_tot2[16];
     ThresholdBin tb;
 };
@@ -372,7 +372,12 @@ __device__ __forceinline__ void select_block(SingleShared& sh, const float* __re
                 keep_bits |= keep ? (1u << i) : 0u;
             }
             const uint32_t n_keep = (uint32_t)__popc(keep_bits);
-            uint32_t pos = block_inclusive_scan<NT>(n_keep, sh.rx.wave_tot2, lane, wave) - n_keep;
+            const uint32_t wincl = wave_inclusive_scan(n_keep, lane);
+            if (lane == kWave - 1) sh.rx.wave_tot2[wave] = wincl;
+            __syncthreads();
+            uint32_t pos = wincl - n_keep;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) pos += (w < wave) ? sh.rx.wave_tot2[w] : 0u;
             if (keep_bits) {
                 int32_t name[ITEMS];
                 if (kVec) {
