@@ -40,6 +40,7 @@ constexpr int kFilterMaxTileRows = 512;   // rows of one scoring workgroup when 
 constexpr int kFilterPrimary = kFilterRecordPairs;
 constexpr int kSample = 512;              // sampled rows per (b, g)
 constexpr int kHintPolls = 64;            // bounded wait for t_lo
+constexpr int kFilterTilesPerWave = 4;    // scores_filter_kernel: tiles one wavefront turns into records
 
 __device__ __forceinline__ uint32_t mix32(uint32_t x) {   // integer finaliser, for the sample jitter
     x ^= x >> 16; x *= 0x7feb352du;
@@ -159,7 +160,7 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
 // End of a tile, one wavefront: waits (bounded) for the row's threshold and stores the tile's record.
 // s_val holds the tile's scores (-inf past the live rows), s_pair is scratch for the pairs.
 __device__ __forceinline__ void emit_tile_record(const ScoreArgs& a, int64_t unit, int tile, int row_begin, int row_end,
-                                                 const float* s_val, uint2* s_pair, uint64_t hint_word, uint32_t epoch,
+                                                 const float* s_val, uint2* s_pair, uint64_t& hint_word, uint32_t epoch,
                                                  int lane) {
     // t_lo of the row: the sampler's word, once it carries this call's epoch
     float t_lo = -INFINITY;
@@ -317,22 +318,41 @@ __global__ __launch_bounds__(kScoreThreads) void scores_filter_kernel(const Scor
         if (tid == 0) publish_hint(a, unit, t_lo);
         return;
     }
-    // a workgroup takes kScoreWaves consecutive tiles of one row, one per wavefront (a tile is 1-2 KB of
-    // scores: with a workgroup per tile the launch was bound by the life of its 22 k tiny workgroups)
+    // A wavefront takes kFilterTilesPerWave consecutive tiles of one row (a tile is 1-2 KB of scores: with a
+    // workgroup per tile the launch was bound by the life of its 22 k tiny workgroups).  The scores of all
+    // its tiles are requested at once; the records follow one after the other.
     id -= units;
     const int unit = id / groups;
-    const int tile = (id - unit * groups) * kScoreWaves + wave;
-    if (tile >= a.filt.n_tiles) return;   // wave-uniform; no barrier below
+    const int tile0 = ((id - unit * groups) * kScoreWaves + wave) * kFilterTilesPerWave;
+    if (tile0 >= a.filt.n_tiles) return;   // wave-uniform; no barrier below
     const int n = live_rows_of(a, unit / a.Hkv);
-    const int row_begin = tile * a.rows_per_block;
-    const int row_end = min(row_begin + a.rows_per_block, a.n_vis_max);
-    const uint64_t hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const uint32_t epoch = launch_epoch(a);
+    uint64_t hint_word = __hip_atomic_load(a.filt.hint + unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // re-read by the
+    const uint32_t epoch = launch_epoch(a);                                                                      // first record if stale
     const float* __restrict__ srow = a.scores + (int64_t)unit * a.n_vis_max;
-    for (int r = lane; r < row_end - row_begin; r += kWave)
-        s_val[wave][r] = row_begin + r < n ? srow[row_begin + r] : -INFINITY;
-    __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
-    emit_tile_record(a, unit, tile, row_begin, row_end, s_val[wave], s_pair[wave], hint_word, epoch, lane);
+    constexpr int PER_LANE = kFilterMaxTileRows / kWave;   // scores of one tile per lane
+    float v[kFilterTilesPerWave][PER_LANE];
+#pragma unroll
+    for (int t = 0; t < kFilterTilesPerWave; ++t) {
+        const int row_begin = (tile0 + t) * a.rows_per_block;
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) {
+            const int r = i * kWave + lane;
+            const int row = row_begin + r;
+            v[t][i] = (r < a.rows_per_block && row < n) ? srow[row] : -INFINITY;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kFilterTilesPerWave; ++t) {
+        const int tile = tile0 + t;
+        if (tile >= a.filt.n_tiles) break;   // wave-uniform
+        const int row_begin = tile * a.rows_per_block;
+        const int row_end = min(row_begin + a.rows_per_block, a.n_vis_max);
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) s_val[wave][i * kWave + lane] = v[t][i];
+        __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+        emit_tile_record(a, unit, tile, row_begin, row_end, s_val[wave], s_pair[wave], hint_word, epoch, lane);
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 template <typename T, int D>
@@ -366,7 +386,8 @@ hipError_t launch_scores_filter(const ScoreArgs& a, hipStream_t stream) {
     if (!a.filt.tiles || a.filt.tile_rows <= 0) return hipErrorInvalidValue;
     ScoreArgs k = a;
     k.rows_per_block = a.filt.tile_rows;
-    const int groups = (a.filt.n_tiles + kScoreWaves - 1) / kScoreWaves;   // workgroups per row
+    const int per_group = kScoreWaves * kFilterTilesPerWave;
+    const int groups = (a.filt.n_tiles + per_group - 1) / per_group;   // workgroups per row
     const uint64_t blocks = (uint64_t)a.B * a.Hkv * (1u + (uint64_t)groups);
     if (blocks == 0) return hipSuccess;
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
