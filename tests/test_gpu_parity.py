@@ -232,6 +232,15 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     assert_step_matches(inp, k, vis_len=vis_len, label="filtered")
 
 
+def test_step_on_rows_beyond_the_reach_of_the_candidate_filter():
+    """Rows longer than 256 tiles of 512 scores (131 072) cannot take the candidate filter: the step then
+    stores the scores and runs the three-kernel selection (streaming parts).  Whole rule set."""
+    Nv, k = 140001, 3000
+    inp = rand_inputs(63, 1, 2, 1, 64, Nv, 50, np.float16)
+    vis_len = np.array([Nv - 77], np.int32)
+    assert_step_matches(inp, k, vis_len=vis_len, label="beyond the filter")
+
+
 def test_filtered_selection_degenerate_rows():
     """All keys equal (every row is a candidate: more than fit on chip -> whole-row fallback), rows
     shorter than k, shorter than the sample, and empty rows, on a shape that takes the filtered path."""
