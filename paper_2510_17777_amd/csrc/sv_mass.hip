@@ -203,6 +203,7 @@ template <int D>
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mass_rowstat_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
     __shared__ KeyStage<KB> stage[2];
+    __shared__ __align__(16) int s_last_txt[kMaxRowTiles * 16];
     const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int row = lane & 15, quad = lane >> 4;
@@ -215,6 +216,10 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     const float c2 = a.scale * kLog2e;
     const int64_t unit = (int64_t)b * a.Hkv + g;
     float* part = a.part + ((unit * a.n_stat_blocks + blk) * (int64_t)(kMaxRowTiles * 16)) * 2;
+    // last text row that query row r sees: its token i = r / G sits at text row nt - Tq + i (one division per
+    // row here instead of one per logit in the masked tiles); read after the first barrier below
+    static_assert(kMassThreads == kMaxRowTiles * 16, "one thread per query row");
+    s_last_txt[threadIdx.x] = nt - a.Tq + ((int)threadIdx.x < R ? (int)threadIdx.x / a.G : 0);
 
     half8_t qa[kTilesPerWave][KB];
     load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
@@ -250,11 +255,12 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         float4_t sv[kTilesPerWave];
         tile_logits<KB, kTilesPerWave>(qa, kf, sv);   // rows past R are zero rows: computed, never stored
 #pragma unroll
-        for (int t = 0; t < kTilesPerWave; ++t)
+        for (int t = 0; t < kTilesPerWave; ++t) {
+            const int4 last4 = *reinterpret_cast<const int4*>(&s_last_txt[row_tile_of(wave, rot, t) * 16 + 4 * quad]);
+            const int last_of[4] = {last4.x, last4.y, last4.z, last4.w};
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int r = row_tile_of(wave, rot, t) * 16 + 4 * quad + rr;
-                const int last_txt = nt - a.Tq + (r < R ? r / a.G : 0);   // query token i sits at text row nt - Tq + i
+                const int last_txt = last_of[rr];
                 const bool seen = key < n_keys && (key >= nt || key <= last_txt);
                 const float x = seen ? sv[t][rr] * c2 : -INFINITY;
                 const float mn = fmaxf(ref[t][rr], x);
@@ -263,6 +269,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
                     ref[t][rr] = mn;
                 }
             }
+        }
     };
     // The stage loop is instantiated once per count of live row tiles and chosen outside the loop: a switch
     // inside it made the compiler shuffle the 32 state registers between the arms at every stage (as many
