@@ -439,7 +439,6 @@ struct FilteredShared {
     float tile_top[kFiltMaxTiles];          // the largest candidate score of each tile
     alignas(16) uint32_t tile_off[kFiltMaxTiles + 4];   // exclusive prefix sums of the tile counts, then their total
     uint32_t max_cnt;                        // the largest tile count
-    uint32_t wave_tot[16];
     float tlo_min[4], tlo_max[4], top_max[4];
     uint32_t n_at_or_above;
 };
