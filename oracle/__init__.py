@@ -229,3 +229,35 @@ def score_visual_mass(q_multi, k_vis, k_txt, vis_len=None, txt_len=None, scale: 
                 lse[b, i, h] = m + np.log(z)
                 mass[b, g, :nv] += np.exp(logit_v - m) / z
     return mass, lse
+
+
+def salience_self(q_all, k_all, vis_len=None, scale: Optional[float] = None):
+    """Query-agnostic salience of the tokens of a vision-encoder layer that has no summary token (paper
+    section 3.1, "Token Salience Estimation": importance is the intra-visual attention averaged over
+    all tokens), written out as its definition in float64 with the attention matrix formed explicitly:
+    per head, every token's query row takes one softmax over all live tokens' keys; salience[b, j] is the
+    probability that key j receives, averaged over the query tokens and the heads.
+    q_all [B, N, H, D], k_all [B, H, N, D]; tokens at or past vis_len[b] neither ask nor are seen.
+    Returns (salience [B, N] float64 with -inf past vis_len, lse [B, N, H] float64 with +inf past vis_len)."""
+    q = _c(q_all).astype(np.float64)
+    k = _c(k_all).astype(np.float64)
+    B, N, H, D = q.shape
+    assert k.shape == (B, H, N, D)
+    sc = default_scale(D) if scale is None else scale
+    vl = np.full(B, N) if vis_len is None else np.asarray(vis_len)
+    sal = np.full((B, N), -np.inf)
+    lse = np.full((B, N, H), np.inf)
+    for b in range(B):
+        n = int(vl[b])
+        if n == 0:
+            continue
+        total = np.zeros(n)
+        for h in range(H):
+            logits = sc * (q[b, :n, h] @ k[b, h, :n].T)          # [query token, key token]
+            m = logits.max(axis=1, keepdims=True)
+            e = np.exp(logits - m)
+            z = e.sum(axis=1, keepdims=True)
+            lse[b, :n, h] = (m + np.log(z))[:, 0]
+            total += (e / z).sum(axis=0)                          # attention received by each key
+        sal[b, :n] = total / (H * n)
+    return sal, lse

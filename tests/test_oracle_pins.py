@@ -15,6 +15,9 @@ transposed operand fails at least one of them:
   order      : permutation of the visual / text cache rows
   ragged     : padding rows are never read; k = 0, Nt = 0, k >= Nv
   widening   : all 65536 binary16 patterns against numpy's float16 -> float64
+  mass       : library softmax of the masked matrix; probability conservation; Tq = G = 1 is the attention weight
+  salience   : library attention with V = I; two-token logistic closed form; one shared query -> its softmax;
+               uniform / conservation / key-shift / permutation invariants; dominant key
 """
 import os
 
@@ -464,3 +467,98 @@ def test_mass_of_one_token_one_head_ranks_like_the_logit_and_matches_attention_w
         wt = np.exp(sc * kt[0, h].astype(np.float64) @ q[0, h].astype(np.float64) - lse[0, 0, h])
         out = wt @ vt[0, h].astype(np.float64) + mass[0, h] @ vv[0, h].astype(np.float64)
         assert np.allclose(out, dense["out"][0, h], rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ query-agnostic salience of an encoder layer
+def _enc_case(seed, B=2, N=23, H=3, D=16):
+    rng = np.random.default_rng(seed)
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    return f(B, N, H, D), f(B, H, N, D)
+
+
+def test_salience_is_the_column_mean_of_library_attention_on_an_identity_value_matrix():
+    """Library routine as a special case: SDPA (float64) with V = I returns the attention matrix itself;
+    its column means over query tokens and heads are the salience."""
+    q, k = _enc_case(11)
+    B, N, H, D = q.shape
+    sal, lse = oracle.salience_self(q, k)
+    qt = torch.from_numpy(q.astype(np.float64)).permute(0, 2, 1, 3)      # [B, H, N, D]
+    kt = torch.from_numpy(k.astype(np.float64))
+    eye = torch.eye(N, dtype=torch.float64).expand(B, H, N, N)
+    p = torch.nn.functional.scaled_dot_product_attention(qt, kt, eye).numpy()   # [B, H, query, key]
+    assert np.allclose(sal, p.mean(axis=(1, 2)), rtol=1e-12, atol=1e-15)
+    from scipy.special import logsumexp
+    logits = np.einsum("bihd,bhjd->bihj", q.astype(np.float64), k.astype(np.float64)) / np.sqrt(D)
+    assert np.allclose(lse, logsumexp(logits, axis=3), rtol=1e-12)
+
+
+def test_salience_of_two_tokens_is_the_logistic_closed_form():
+    """N = 2: a row's probability of key 0 is the logistic function of the logit difference; written with
+    math.exp and plain loops.  Normalising over the wrong axis, or a transposed product, fails here."""
+    import math
+    q, k = _enc_case(12, B=1, N=2, H=2, D=8)
+    sal, _ = oracle.salience_self(q, k)
+    sc = 1.0 / math.sqrt(8)
+    recv = [0.0, 0.0]
+    for h in range(2):
+        for i in range(2):
+            l0 = sc * sum(float(q[0, i, h, d]) * float(k[0, h, 0, d]) for d in range(8))
+            l1 = sc * sum(float(q[0, i, h, d]) * float(k[0, h, 1, d]) for d in range(8))
+            p0 = 1.0 / (1.0 + math.exp(l1 - l0))
+            recv[0] += p0
+            recv[1] += 1.0 - p0
+    assert np.allclose(sal[0], np.array(recv) / 4.0, rtol=1e-12)
+
+
+def test_salience_with_one_shared_query_is_the_softmax_of_that_query():
+    """Every token asks the same question, one head: all rows of the attention matrix are equal, so the
+    salience is that row -- scipy's softmax of scale * K u.  Also fixes the explicit scale."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(13)
+    N, D = 31, 16
+    u = rng.standard_normal(D).astype(np.float32)
+    k = rng.standard_normal((1, 1, N, D)).astype(np.float32)
+    q = np.broadcast_to(u, (1, N, 1, D)).copy()
+    sal, _ = oracle.salience_self(q, k, scale=0.37)
+    assert np.allclose(sal[0], softmax(0.37 * k[0, 0].astype(np.float64) @ u.astype(np.float64)), rtol=1e-12)
+
+
+def test_salience_invariants():
+    """Identical keys -> uniform 1/n; the salience of the live tokens sums to 1 for any lengths; adding a vector
+    to every key changes nothing; permuting the tokens permutes the salience; permuting only who asks
+    changes nothing; rows past vis_len are neither read nor counted."""
+    q, k = _enc_case(14)
+    B, N, H, D = q.shape
+    k_same = np.broadcast_to(k[:, :, :1], k.shape).copy()
+    sal, _ = oracle.salience_self(q, k_same)
+    assert np.allclose(sal, 1.0 / N, rtol=1e-12)
+    vis_len = np.array([N, 9], np.int32)
+    sal, lse = oracle.salience_self(q, k, vis_len=vis_len)
+    assert np.allclose([sal[0].sum(), sal[1, :9].sum()], 1.0, rtol=1e-12)
+    assert np.all(np.isneginf(sal[1, 9:])) and np.all(np.isposinf(lse[1, 9:]))
+    q2, k2 = q.copy(), k.copy()
+    q2[1, 9:] = 1e4
+    k2[1, :, 9:] = 1e4
+    sal2, lse2 = oracle.salience_self(q2, k2, vis_len=vis_len)
+    assert np.array_equal(sal2, sal) and np.array_equal(lse2, lse)
+    full, _ = oracle.salience_self(q, k)
+    shift = np.random.default_rng(15).standard_normal(D).astype(np.float32)
+    moved, _ = oracle.salience_self(q.astype(np.float64), k.astype(np.float64) + shift)
+    assert np.allclose(moved, full, rtol=1e-9)
+    perm = np.random.default_rng(16).permutation(N)
+    both, _ = oracle.salience_self(q[:, perm], k[:, :, perm])
+    assert np.allclose(both, full[:, perm], rtol=1e-12)
+    askers, _ = oracle.salience_self(q[:, perm], k)
+    assert np.allclose(askers, full, rtol=1e-12)
+
+
+def test_salience_of_a_dominant_key_approaches_one():
+    """One key far along every query's direction takes all the attention."""
+    rng = np.random.default_rng(17)
+    N, D = 12, 8
+    u = np.ones(D, np.float32)
+    q = (np.abs(rng.standard_normal((1, N, 1, D))) + 0.5).astype(np.float32)   # positive along u
+    k = rng.standard_normal((1, 1, N, D)).astype(np.float32)
+    k[0, 0, 5] = 60.0 * u
+    sal, _ = oracle.salience_self(q, k)
+    assert sal[0, 5] > 1 - 1e-9 and np.all(sal[0, np.arange(N) != 5] < 1e-9)
