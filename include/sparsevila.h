@@ -179,6 +179,35 @@ sv_status sv_score_visual_mass(const sv_shape *shape, const void *q_multi, int32
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Query-agnostic salience of the tokens of one vision-encoder layer (section 3.1, "Token
+ * Salience Estimation": for encoders without a summary token, importance is the intra-visual
+ * attention averaged over all tokens; "Efficient Implementation": normalisation and
+ * accumulation are streamed, the N x N attention matrix is never formed).  The prefill-side
+ * pruning keeps the tokens of highest salience: the output feeds sv_topk_select (on a shape
+ * with one kv head) unchanged.
+ *   salience[b, j] = 1 / (H n_b) * sum_h sum_{i < n_b} softmax_(i,h)[j],     n_b = vis_len[b],
+ * where row (i, h) is the query of token i, head h, and its softmax runs over the keys of the
+ * n_b live tokens of the same head with logits scale * <q, key>; no mask.  The salience of the
+ * live tokens of a batch entry sums to 1; -inf for n_b <= j < n_vis_max.
+ * Fields of the shape that are used: batch (images, frames or windows: attention stays inside a
+ * batch entry), n_q_heads = n_kv_heads = H (SV_ERR_SHAPE otherwise), head_dim 64, 96 or 128
+ * (an encoder with 72 or 80 dims per head zero-pads q and k to 96 and passes its own scale),
+ * n_vis_max = N (token capacity), vis_len, scale, dtype (fp16 only, SV_ERR_DTYPE otherwise),
+ * q_stride_b / q_stride_h and the kv_vis strides; the text fields and k are ignored.
+ *   q_all  [B, N, H, D] addressed with q_stride_b, q_stride_t (ELEMENTS, a multiple of 8), q_stride_h
+ *   k_all  [B, H, N, D] addressed with kv_vis_stride_b, kv_vis_stride_h, kv_vis_stride_n
+ *          (both accept the token-major layout of a fused qkv projection through the strides)
+ *   salience [B, N] fp32 (output);  lse [B, N, H] fp32 or NULL (optional output: log of every
+ *          row's normaliser, +inf past vis_len)
+ * The workspace must hold sv_salience_workspace_bytes(shape) bytes (0 for an invalid shape).
+ * Deterministic: the same inputs give the same bits.
+ */
+size_t sv_salience_workspace_bytes(const sv_shape *shape);
+sv_status sv_salience_self(const sv_shape *shape, const void *q_all, int64_t q_stride_t,
+                           const void *k_all, float *salience, float *lse,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Packing (section 3.2: the selected visual KV entries are packed into a contiguous
  * region, so that the attention of the tokens decoded afterwards reads no irregular
  * pattern).  k_pack/v_pack are dense DEVICE buffers [B, Hkv, k, D] of the shape's dtype:

@@ -73,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.sv_mass_workspace_bytes.argtypes = [P, i32]
     lib.sv_score_visual_mass.restype = ctypes.c_int
     lib.sv_score_visual_mass.argtypes = [P, vp, i32, ctypes.c_int64, vp, vp, vp, vp, vp, sz, vp]
+    lib.sv_salience_workspace_bytes.restype = sz
+    lib.sv_salience_workspace_bytes.argtypes = [P]
+    lib.sv_salience_self.restype = ctypes.c_int
+    lib.sv_salience_self.argtypes = [P, vp, ctypes.c_int64, vp, vp, vp, vp, sz, vp]
     lib.sv_pack_selected.restype = ctypes.c_int
     lib.sv_pack_selected.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.sv_copy_bytes.restype = ctypes.c_int
@@ -224,6 +228,37 @@ def sv_score_visual_mass(shape: Shape, q_multi, k_vis, k_txt, scores, lse=None, 
     _check(load_library().sv_score_visual_mass(
         ctypes.byref(shape.c), _ptr(q_multi), Tq, q_multi.stride(1), _ptr(k_vis), _ptr(k_txt), _ptr(scores),
         _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream)), "sv_score_visual_mass")
+    return workspace
+
+
+def make_encoder_shape(q_all: torch.Tensor, k_all: torch.Tensor, vis_len=None, scale: float = 0.0) -> Shape:
+    """sv_shape of one encoder layer for sv_salience_self: q_all [B, N, H, D], k_all [B, H, N, D] (any strides
+    with D contiguous; views of a fused qkv tensor are fine)."""
+    B, N, H, D = q_all.shape
+    if tuple(k_all.shape) != (B, H, N, D):
+        raise ValueError("k_all must be [B, H, N, D] for q_all [B, N, H, D]")
+    if q_all.stride(3) != 1 or k_all.stride(3) != 1:
+        raise ValueError("head_dim must be contiguous")
+    s = SvShape()
+    s.batch, s.n_q_heads, s.n_kv_heads, s.head_dim = B, H, H, D
+    s.n_vis_max, s.n_txt_max, s.k, s.dtype, s.scale, s.reserved = N, 0, 0, _dtype_code(q_all), float(scale), 0
+    s.q_stride_b, s.q_stride_h = q_all.stride(0), q_all.stride(2)
+    s.kv_vis_stride_b, s.kv_vis_stride_h, s.kv_vis_stride_n = k_all.stride(0), k_all.stride(1), k_all.stride(2)
+    s.kv_txt_stride_b, s.kv_txt_stride_h, s.kv_txt_stride_n = 0, 0, D
+    vl = _len_tensor(vis_len, B, q_all.device)
+    s.vis_len = _ptr(vl)
+    s.txt_len = None
+    return Shape(s, vl, None)
+
+
+def sv_salience_self(shape: Shape, q_all, k_all, salience, lse=None, workspace=None, stream=None):
+    """shape from make_encoder_shape; salience [B, N] fp32; returns the workspace it used."""
+    if workspace is None:
+        nbytes = int(load_library().sv_salience_workspace_bytes(ctypes.byref(shape.c)))
+        workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q_all.device)
+    _check(load_library().sv_salience_self(
+        ctypes.byref(shape.c), _ptr(q_all), q_all.stride(1), _ptr(k_all), _ptr(salience), _ptr(lse),
+        _ptr(workspace), workspace.numel(), _stream(stream)), "sv_salience_self")
     return workspace
 
 

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparsevila.so")
-SOURCES = ["sv_api.hip", "sv_score.hip", "sv_select.hip", "sv_attend.hip", "sv_attend_mfma.hip", "sv_attend_flash.hip", "sv_pack.hip", "sv_mass.hip", "sv_util.hip"]
+SOURCES = ["sv_api.hip", "sv_score.hip", "sv_select.hip", "sv_attend.hip", "sv_attend_mfma.hip", "sv_attend_flash.hip", "sv_pack.hip", "sv_mass.hip", "sv_salience.hip", "sv_util.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -352,6 +352,67 @@ sv_status sv_score_visual_mass(const sv_shape* s, const void* q_multi, int32_t n
     return from_hip(sv::launch_mass(a, static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+// The fields sv_salience_self uses; head_dim 96 is allowed here only.
+sv_status check_salience_shape(const sv_shape* s) {
+    if (!s) return SV_ERR_NULL;
+    if (s->dtype != SV_F16 && s->dtype != SV_F32) return SV_ERR_DTYPE;
+    if (s->reserved != 0) return SV_ERR_SHAPE;
+    if (s->batch < 1 || s->batch > kMaxGridYZ) return SV_ERR_SHAPE;
+    if (s->n_kv_heads < 1 || s->n_q_heads != s->n_kv_heads) return SV_ERR_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 96 && s->head_dim != 128) return SV_ERR_SHAPE;
+    if (s->n_vis_max < 0) return SV_ERR_SHAPE;
+    if (!(s->scale >= 0.f) || std::isinf(s->scale)) return SV_ERR_SHAPE;
+    if (s->dtype != SV_F16) return SV_ERR_DTYPE;
+    const int64_t D = s->head_dim;
+    if (s->q_stride_h < D || s->q_stride_b < 0) return SV_ERR_SHAPE;
+    if ((s->q_stride_h * 2) % 16 || (s->q_stride_b * 2) % 16) return SV_ERR_ALIGN;
+    if (s->n_vis_max > 0) {
+        if (s->kv_vis_stride_n < D || s->kv_vis_stride_h < 0 || s->kv_vis_stride_b < 0) return SV_ERR_SHAPE;
+        if ((s->kv_vis_stride_n * 2) % 16 || (s->kv_vis_stride_h * 2) % 16 || (s->kv_vis_stride_b * 2) % 16)
+            return SV_ERR_ALIGN;
+        const sv::SaliencePlan p = sv::salience_plan(s->batch, s->n_kv_heads, s->n_vis_max);
+        if ((int64_t)s->n_kv_heads * p.n_row_chunks > kMaxGridYZ || (int64_t)s->n_kv_heads * p.n_seg > kMaxGridYZ)
+            return SV_ERR_SHAPE;
+    }
+    return SV_OK;
+}
+}  // namespace
+
+size_t sv_salience_workspace_bytes(const sv_shape* s) {
+    if (check_salience_shape(s) != SV_OK) return 0;
+    const sv::SaliencePlan p = sv::salience_plan(s->batch, s->n_kv_heads, s->n_vis_max);
+    const size_t lse = align_up((size_t)s->batch * s->n_vis_max * s->n_kv_heads * sizeof(float));
+    return lse + align_up(p.part_bytes) + align_up(p.colpart_bytes) + kAlign;
+}
+
+sv_status sv_salience_self(const sv_shape* s, const void* q_all, int64_t q_stride_t, const void* k_all, float* salience,
+                           float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+    sv_status st = check_salience_shape(s);
+    if (st != SV_OK) return st;
+    if (q_stride_t < s->head_dim) return SV_ERR_SHAPE;
+    if ((q_stride_t * 2) % 16) return SV_ERR_ALIGN;
+    if (s->n_vis_max == 0) return SV_OK;
+    if (!q_all || !k_all || !salience) return SV_ERR_NULL;
+    if (!aligned16(q_all) || !aligned16(k_all)) return SV_ERR_ALIGN;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign ||
+        workspace_bytes < sv_salience_workspace_bytes(s))
+        return SV_ERR_WORKSPACE;
+    const sv::SaliencePlan p = sv::salience_plan(s->batch, s->n_kv_heads, s->n_vis_max);
+    const size_t lse_bytes = align_up((size_t)s->batch * s->n_vis_max * s->n_kv_heads * sizeof(float));
+    char* ws = static_cast<char*>(workspace);
+    sv::SalienceArgs a{};
+    a.q = q_all; a.k = k_all; a.vis_len = s->vis_len; a.salience = salience;
+    a.lse = lse ? lse : reinterpret_cast<float*>(ws);
+    a.part = reinterpret_cast<float*>(ws + lse_bytes);
+    a.colpart = reinterpret_cast<float*>(ws + lse_bytes + align_up(p.part_bytes));
+    a.B = s->batch; a.H = s->n_kv_heads; a.D = s->head_dim; a.N = s->n_vis_max;
+    a.scale = effective_scale(s);
+    a.q_sb = s->q_stride_b; a.q_st = q_stride_t; a.q_sh = s->q_stride_h;
+    a.k_sb = s->kv_vis_stride_b; a.k_sh = s->kv_vis_stride_h; a.k_sn = s->kv_vis_stride_n;
+    return from_hip(sv::launch_salience(a, static_cast<hipStream_t>(stream)));
+}
+
 sv_status sv_pack_selected(const sv_shape* s, const void* k_vis, const void* v_vis, const int32_t* idx,
                            const int32_t* count, void* k_pack, void* v_pack, void* stream) {
     sv_status st = check_shape(s, kNeedVis);

@@ -115,6 +115,30 @@ hipError_t launch_mass(const MassArgs& a, hipStream_t stream);
 size_t mass_workspace_bytes(int B, int Hkv, int n_txt_max, int n_vis_max);
 int mass_max_rows();   // most query rows (tokens x heads of a group) the kernels hold
 
+// Query-agnostic salience of an encoder layer (sv_salience_self).
+struct SalienceArgs {
+    const void* q;            // [B, N, H, D] through q_sb, q_st, q_sh (fp16)
+    const void* k;            // [B, H, N, D] through k_sb, k_sh, k_sn (fp16)
+    const int32_t* vis_len;
+    float* salience;          // [B, N]
+    float* lse;               // [B, N, H]
+    float* part;              // SaliencePlan::part_bytes: per key block (max, sum) of every query row
+    float* colpart;           // SaliencePlan::colpart_bytes: per query segment and head, the mass of every key
+    int32_t B, H, D, N;
+    float scale;
+    int64_t q_sb, q_st, q_sh;
+    int64_t k_sb, k_sh, k_sn;
+    int32_t n_row_chunks, stat_block_keys, n_stat_blocks, seg_len, n_seg;   // set by the launcher from the plan
+};
+struct SaliencePlan {
+    int n_row_chunks;        // groups of 256 tokens
+    int stat_block_keys, n_stat_blocks;   // pass 1: keys per workgroup, key blocks per row
+    int seg_len, n_seg;      // pass 2: query tokens per workgroup, segments per row
+    size_t part_bytes, colpart_bytes;
+};
+SaliencePlan salience_plan(int B, int H, int N);   // all zero for an empty problem
+hipError_t launch_salience(const SalienceArgs& a, hipStream_t stream);
+
 hipError_t launch_score(const ScoreArgs& a, hipStream_t stream);
 // Scores given (a.scores, read only): sampler + tile workgroups hand the selection the candidates of every row
 // (a.filt from carve_filter_workspace); then launch_select_filtered with a.write_scores = 1.

@@ -36,7 +36,7 @@ def good_shape(**kw) -> SvShape:
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("sv_score_visual", "sv_topk_select", "sv_sparse_decode_attn", "sv_decode_step",
-                 "sv_pack_selected", "sv_score_visual_mass", "sv_mass_workspace_bytes", "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
+                 "sv_pack_selected", "sv_score_visual_mass", "sv_mass_workspace_bytes", "sv_salience_self", "sv_salience_workspace_bytes", "sv_workspace_bytes", "sv_strerror", "sv_shape_set_contiguous"):
         assert must in names
 
 
@@ -203,3 +203,35 @@ def test_binding_refuses_host_tensors():
     shape = sv.make_shape(q, k, None, 2)
     with pytest.raises(ValueError):
         sv.sv_score_visual(shape, q, k, torch.zeros((1, 1, 8)))
+
+
+def test_salience_entry_point_checks_its_arguments():
+    lib = sv.load_library()
+    s = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=5000)
+    sp = ctypes.byref(s)
+    need = lib.sv_salience_workspace_bytes(sp)
+    assert need > 0 and need % 256 == 0
+    ok_args = (FAKE, 16 * 96, FAKE, FAKE, None)          # q_all, q_stride_t, k_all, salience, lse (optional)
+    assert lib.sv_salience_self(sp, *ok_args, FAKE, need - 1, None) == E_WS
+    assert lib.sv_salience_self(sp, *ok_args, None, need, None) == E_WS
+    assert lib.sv_salience_self(sp, None, 16 * 96, FAKE, FAKE, None, FAKE, need, None) == E_NULL
+    assert lib.sv_salience_self(sp, FAKE, 16 * 96, None, FAKE, None, FAKE, need, None) == E_NULL
+    assert lib.sv_salience_self(sp, FAKE, 16 * 96, FAKE, None, None, FAKE, need, None) == E_NULL
+    assert lib.sv_salience_self(sp, FAKE + 8, 16 * 96, FAKE, FAKE, None, FAKE, need, None) == E_ALIGN
+    assert lib.sv_salience_self(sp, FAKE, 16 * 96 + 4, FAKE, FAKE, None, FAKE, need, None) == E_ALIGN
+    assert lib.sv_salience_self(sp, FAKE, 64, FAKE, FAKE, None, FAKE, need, None) == E_SHAPE      # token stride < D
+    for bad, want in ((dict(n_q_heads=32), E_SHAPE),      # grouped heads: an encoder layer has none
+                      (dict(head_dim=72), E_SHAPE),       # pad to 96
+                      (dict(dtype=1), E_DTYPE),
+                      (dict(batch=0), E_SHAPE)):
+        t = good_shape(**{**dict(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=5000), **bad})
+        assert lib.sv_salience_workspace_bytes(ctypes.byref(t)) == 0
+        assert lib.sv_salience_self(ctypes.byref(t), *ok_args, FAKE, 1 << 40, None) == want, bad
+    # the other entry points still refuse head_dim 96
+    assert lib.sv_workspace_bytes(sp) == 0
+    # an empty layer does nothing and needs nothing
+    e = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=64, n_vis_max=0)
+    assert lib.sv_salience_self(ctypes.byref(e), None, 16 * 64, None, None, None, None, 0, None) == OK
+    # the workspace grows with the layer
+    big = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=20000)
+    assert lib.sv_salience_workspace_bytes(ctypes.byref(big)) > need

@@ -596,3 +596,125 @@ def test_query_agnostic_salience_of_an_encoder_layer_by_the_same_mass_kernel():
     want = softmax(logits, axis=-1).mean(axis=2)
     assert np.abs(got - want).max() <= 2e-4 * want.max()
     assert abs(got.sum(axis=-1) - 1.0).max() <= 1e-4   # every query row spends probability 1
+
+
+# ------------------------------------------------------------------ query-agnostic salience of an encoder layer
+def _salience_on_gpu(q, k, vis_len=None, scale=0.0, dq=None, dk=None):
+    import paper_2510_17777_amd as sv
+    B, N, H, _ = q.shape
+    if dq is None:
+        dq, dk = torch.from_numpy(q).to("cuda:0"), torch.from_numpy(k).to("cuda:0")
+    shape = sv.make_encoder_shape(dq, dk, vis_len=vis_len, scale=scale)
+    sal = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, N, H), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_salience_self(shape, dq, dk, sal, lse)
+    torch.cuda.synchronize()
+    return sal, lse
+
+
+def _assert_salience_matches(q, k, vis_len, scale, got, got_lse, label=""):
+    """Per element within 2e-4 relative: both sides use the same fp16 inputs exactly; the kernel's logits
+    are fp32 (relative error ~1e-6 of a logit of a few units), its exponentials within a few ulp, so every
+    probability is off by ~1e-5 relative at most and a token's salience is a mean of such probabilities."""
+    want, want_lse = oracle.salience_self(q, k, vis_len=vis_len, scale=scale if scale else None)
+    live = np.isfinite(want)
+    assert np.array_equal(np.isneginf(got), ~live), label
+    err = np.abs(np.where(live, got, 0.0).astype(np.float64) - np.where(live, want, 0.0))
+    assert np.all(err <= 2e-4 * np.where(live, want, 0.0) + 1e-12), f"{label}: salience error {err.max():.3e}"
+    fin = np.isfinite(want_lse)
+    assert np.array_equal(np.isposinf(got_lse), ~fin), label
+    assert np.abs(np.where(fin, got_lse, 0.0) - np.where(fin, want_lse, 0.0)).max(initial=0.0) <= 1e-4, label
+    return want
+
+
+@pytest.mark.parametrize("B,N,H,D,lens", [
+    (2, 729, 4, 64, [729, 500]),         # one 27 x 27 patch grid per image, the second image smaller
+    (1, 1500, 2, 128, None),             # six groups of 256 tokens, two key blocks, ragged last stage
+    (3, 300, 3, 96, [300, 17, 0]),       # padded head dim; a tiny and an empty image
+    (1, 4500, 2, 128, None),             # query segments in pass 2, five key blocks in pass 1
+    (2, 256, 1, 64, [256, 255]),         # exactly one group; one token short of it
+    (1, 1, 2, 64, None),                 # a single token attends to itself: salience 1
+])
+def test_salience_self_matches_the_oracle(B, N, H, D, lens):
+    """sv_salience_self against the oracle's explicit attention matrices, salience and lse."""
+    rng = np.random.default_rng(8800 + N)
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    q, k = f(B, N, H, D), f(B, H, N, D)
+    vis_len = None if lens is None else np.array(lens, np.int32)
+    if vis_len is not None:                      # rows past the live tokens hold a sentinel: never read
+        for b in range(B):
+            q[b, vis_len[b]:] = 1e4
+            k[b, :, vis_len[b]:] = 1e4
+    sal, lse = _salience_on_gpu(q, k, vis_len)
+    got = sal.cpu().numpy()
+    _assert_salience_matches(q, k, vis_len, 0.0, got, lse.cpu().numpy())
+    for b in range(B):
+        n = N if vis_len is None else int(vis_len[b])
+        if n:
+            assert abs(float(got[b, :n].astype(np.float64).sum()) - 1.0) <= 1e-4   # every row spends probability 1
+
+
+def test_salience_self_on_views_of_a_fused_qkv_tensor_with_an_explicit_scale():
+    """q and k as strided views of one [B, N, 3, H, D] projection output (token-major keys), an encoder
+    whose 80 dims per head are zero-padded to 96 and which passes its own scale 1/sqrt(80)."""
+    rng = np.random.default_rng(8901)
+    B, N, H, D, d_model = 2, 700, 4, 96, 80
+    qkv = np.zeros((B, N, 3, H, D), np.float16)
+    qkv[..., :d_model] = rng.standard_normal((B, N, 3, H, d_model), dtype=np.float32).astype(np.float16)
+    dqkv = torch.from_numpy(qkv).to("cuda:0")
+    dq, dk = dqkv[:, :, 0], dqkv[:, :, 1].permute(0, 2, 1, 3)
+    assert not dk.is_contiguous()
+    scale = float(1.0 / np.sqrt(d_model))
+    vis_len = np.array([700, 333], np.int32)
+    q, k = qkv[:, :, 0], np.ascontiguousarray(qkv[:, :, 1].transpose(0, 2, 1, 3))
+    sal, lse = _salience_on_gpu(q, k, vis_len, scale, dq, dk)
+    want = _assert_salience_matches(q, k, vis_len, scale, sal.cpu().numpy(), lse.cpu().numpy())
+    # the padding changes nothing: the unpadded 80-dim problem has the same definition
+    plain, _ = oracle.salience_self(np.ascontiguousarray(q[..., :d_model]), np.ascontiguousarray(k[..., :d_model]),
+                                    vis_len=vis_len, scale=scale)
+    assert np.array_equal(plain, want)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_salience_self_seeded_random_shapes(case):
+    """Shapes drawn from a seeded generator: head dims 64 / 96 / 128, token counts across the 64-token stages,
+    the 256-token groups and the 1024-key blocks of the kernels, ragged batches with empty entries."""
+    rng = np.random.default_rng(9900 + case)
+    D = int(rng.choice([64, 96, 128]))
+    H, B = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    N = int(rng.choice([rng.integers(1, 70), rng.integers(70, 600), rng.integers(600, 2300)]))
+    f = lambda *s: (rng.standard_normal(s, dtype=np.float32) * rng.choice([0.5, 1.0, 1.5])).astype(np.float16)
+    q, k = f(B, N, H, D), f(B, H, N, D)
+    vis_len = rng.integers(0, N + 1, size=B).astype(np.int32) if rng.random() < 0.6 else None
+    sal, lse = _salience_on_gpu(q, k, vis_len)
+    _assert_salience_matches(q, k, vis_len, 0.0, sal.cpu().numpy(), lse.cpu().numpy(),
+                             f"case {case}: B={B} H={H} N={N} D={D} lens={None if vis_len is None else vis_len.tolist()}")
+
+
+def test_salience_self_feeds_the_selection_and_is_deterministic():
+    """The prefill-side pruning: keep the tokens of highest salience with the unchanged sv_topk_select on a
+    one-kv-head shape -- bit-exact against a sort of the GPU's own salience, inside the tie band of the
+    oracle's; a second run gives the same bits; planted tokens that every query looks at are kept."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9001)
+    B, N, H, D, keep = 2, 1200, 4, 64, 300
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    q, k = f(B, N, H, D), f(B, H, N, D)
+    planted = rng.choice(N, size=40, replace=False)
+    k[:, :, planted] += (0.5 * q.astype(np.float32).mean(axis=1)[:, :, None, :]).astype(np.float16) * 8   # along the mean query
+    vis_len = np.array([N, 1000], np.int32)
+    dq, dk = torch.from_numpy(q).to("cuda:0"), torch.from_numpy(k).to("cuda:0")
+    sal, _ = _salience_on_gpu(q, k, vis_len, 0.0, dq, dk)
+    sal2, _ = _salience_on_gpu(q, k, vis_len, 0.0, dq, dk)
+    assert torch.equal(sal, sal2)
+    got = sal.cpu().numpy()
+    want, _ = oracle.salience_self(q, k, vis_len=vis_len)
+    scores = sal.view(B, 1, N)
+    shape = sv.make_shape(dq[:, 0, :1], dk[:, :1], None, keep, vis_len=vis_len)
+    buf = sv.DecodeBuffers(shape, "cuda:0")
+    sv.sv_topk_select(shape, scores, buf.idx, buf.count, buf.workspace)
+    torch.cuda.synchronize()
+    idx, cnt = buf.idx.cpu().numpy(), buf.count.cpu().numpy()
+    want_idx, want_cnt = oracle.topk_select(got.astype(np.float64)[:, None], keep, vis_len)
+    assert np.array_equal(cnt, want_cnt) and np.array_equal(idx, want_idx)
+    assert check_index_sets(want[:, None], keep, vis_len, idx, cnt).ok
