@@ -31,8 +31,7 @@ namespace sv {
 namespace {
 
 constexpr int kRowsPerGroup = kMaxRowTiles * 16;   // 256 rows held in registers by one workgroup
-constexpr int kMaxStatBlocks = 16;                 // key blocks per row in pass 1
-constexpr int kTargetColsumGroups = 3072;          // pass 2: query segments are cut until this many workgroups exist
+constexpr int kTargetGroups = 3072;                // the streamed side is cut into segments until this many workgroups exist
 
 // A 16-row tile of the operand kept in registers: lane (row, quad) supplies dims 8*quad + 32*kb .. +8 of
 // row `r`; plain (cached) loads, every row is read again by other workgroups.
@@ -59,6 +58,63 @@ __device__ __forceinline__ void load_held_tiles(const _Float16* base, int64_t st
 }
 
 // ---- pass 1 ----
+// A stage of 64 live keys on the fast path.  The reference of a row is the largest of its first 16 logits of
+// the key block (kInit, shared by the row's 16 lanes) and is never raised: a later logit far above it makes a
+// large term, which fp32 sums as accurately as a small one; only a logit more than ~2^7 above it (in base 2)
+// would overflow, and the kernel checks the sums for that after the block and redoes the block on the exact path.
+// So an element costs a multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no
+// branch; the matrix instructions of the next key tile go between the vector instructions of this one.
+template <int KB, int NTL, bool kInit>
+__device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
+                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
+    half8_t kf[2][KB];
+    float4_t sv[2][kTilesPerWave];
+    read_key_tile<KB>(st, 0, lane, kf[0]);
+    tile_logits<KB, NTL>(qa, kf[0], sv[0]);
+    constexpr int n_m = KB * NTL, n_e = 4 * NTL;
+    static_assert(KB <= 4, "at most one matrix instruction per element");
+#pragma unroll
+    for (int kt = 0; kt < kMassWaves; ++kt) {
+        const int cur = kt & 1, nxt = cur ^ 1;
+        const bool has_next = kt + 1 < kMassWaves;
+        if (has_next) {
+            read_key_tile<KB>(st, kt + 1, lane, kf[nxt]);
+#pragma unroll
+            for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
+        }
+        if (kInit && kt == 0) {   // once per key block: the references; the next tile's matrix instructions run meanwhile
+#pragma unroll
+            for (int m = 0; m < n_m; ++m)
+                sv[nxt][m % NTL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[m % NTL][m / NTL], kf[nxt][m / NTL], sv[nxt][m % NTL], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < NTL; ++t)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const float x = sv[cur][t][rr] * c2;
+                    const float r0 = row_max16(x);
+                    ref[t][rr] = r0;
+                    l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
+                }
+            continue;
+        }
+        float y[n_e > 0 ? n_e : 1], pr[n_e > 0 ? n_e : 1];
+#pragma unroll
+        for (int step = 0; step < n_e + 2; ++step) {
+            if (has_next && step < n_e) {
+#pragma unroll
+                for (int m = step * n_m / n_e; m < (step + 1) * n_m / n_e; ++m) {
+                    const int kb = m / NTL, t = m % NTL;
+                    sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
+                }
+            }
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
+            if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
+            if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void salience_rowstat_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
@@ -80,13 +136,6 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     half8_t qa[kTilesPerWave][KB];
     load_held_tiles<KB>(qrows, a.q_st, row0, n, wave, rot, lane, qa);
     float ref[kTilesPerWave][4], l[kTilesPerWave][4];
-#pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t)
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            ref[t][rr] = -INFINITY;
-            l[t][rr] = 0.f;
-        }
     const int k_end = min(key0 + a.stat_block_keys, n);
     half8_t kfetch[KB];
     auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns masked at use
@@ -115,10 +164,21 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
                 }
             }
     };
-    // instantiated once per count of live row tiles and chosen outside the loop (a switch inside it makes the
-    // compiler shuffle the state registers between the arms at every stage)
-    auto run = [&](auto ntl_c) __attribute__((always_inline)) {
+    // One sweep over the key block.  exact = false: full stages on the fast path; exact = true: every tile with the
+    // exact running maximum (taken only after a sweep whose sums overflowed).  Instantiated once per count of live
+    // row tiles and chosen outside the loop (a switch inside it makes the compiler shuffle the state registers
+    // between the arms at every stage).  No branch around the fetch and the store of the next stage: past the end
+    // they are harmless (clamped rows, a buffer nobody reads), and conditional blocks in the body keep the scheduler
+    // from placing the matrix and vector instructions of a stage together.
+    auto run = [&](auto ntl_c, bool exact) __attribute__((always_inline)) {
         constexpr int NTL = decltype(ntl_c)::value;
+#pragma unroll
+        for (int t = 0; t < kTilesPerWave; ++t)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                ref[t][rr] = -INFINITY;
+                l[t][rr] = 0.f;
+            }
         fetch(key0);
         wait_for_loads();
         put(stage[0]);
@@ -126,32 +186,40 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         int cur = 0;
         bool ref_ready = false;   // block-uniform: every reference is finite
         for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
-            const bool more = s0 + kStageKeys < k_end;   // block-uniform
-            if (more) fetch(s0 + kStageKeys);
-            const bool plain = s0 + kStageKeys <= k_end;   // all 64 keys live
+            fetch(s0 + kStageKeys);
+            const bool plain = !exact && s0 + kStageKeys <= k_end;   // all 64 keys live
             if (plain && ref_ready) {
-                rowstat_plain_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
             } else if (plain && s0 == key0) {
-                rowstat_plain_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
                 ref_ready = true;
             } else {
 #pragma unroll 1
                 for (int kt = 0; kt < kMassWaves; ++kt)
                     if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);
-                if (plain) ref_ready = true;
             }
-            if (more) put(stage[cur ^ 1]);
+            put(stage[cur ^ 1]);
             __syncthreads();
             cur ^= 1;
         }
     };
-    switch (ntl) {   // wave-uniform
-        case 4: run(std::integral_constant<int, 4>{}); break;
-        case 3: run(std::integral_constant<int, 3>{}); break;
-        case 2: run(std::integral_constant<int, 2>{}); break;
-        case 1: run(std::integral_constant<int, 1>{}); break;
-        default: run(std::integral_constant<int, 0>{}); break;
-    }
+    auto sweep = [&](bool exact) __attribute__((always_inline)) {
+        switch (ntl) {   // wave-uniform
+            case 4: run(std::integral_constant<int, 4>{}, exact); break;
+            case 3: run(std::integral_constant<int, 3>{}, exact); break;
+            case 2: run(std::integral_constant<int, 2>{}, exact); break;
+            case 1: run(std::integral_constant<int, 1>{}, exact); break;
+            default: run(std::integral_constant<int, 0>{}, exact); break;
+        }
+    };
+    sweep(false);
+    // did a sum leave the range in which it is trusted?  (inf, NaN or above 2^100: a logit far above its row's reference)
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < kTilesPerWave; ++t)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < 0x1p100f);
+    if (__syncthreads_or(bad)) sweep(true);   // block-uniform
     // merge the 16 key columns of a row, store per key block (natural-log units from here on)
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
@@ -208,22 +276,47 @@ __device__ __forceinline__ void colsum_swapped_stage(const KeyStage<KB>& st, con
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, qf[0]);
     tile_logits<KB, NTL>(ka, qf[0], sv[0]);
+    constexpr int n_m = KB * NTL, n_e = 4 * NTL;   // matrix instructions of a query tile, elements per lane of a query tile
+    static_assert(KB <= 4, "at most one matrix instruction per element");
 #pragma unroll
     for (int qt = 0; qt < kMassWaves; ++qt) {
-        if (qt + 1 < kMassWaves) {
-            read_key_tile<KB>(st, qt + 1, lane, qf[(qt + 1) & 1]);
-            tile_logits<KB, NTL>(ka, qf[(qt + 1) & 1], sv[(qt + 1) & 1]);
+        const int cur = qt & 1, nxt = cur ^ 1;
+        const bool has_next = qt + 1 < kMassWaves;
+        if (has_next) {
+            read_key_tile<KB>(st, qt + 1, lane, qf[nxt]);
+#pragma unroll
+            for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
         }
         const float l2 = lse2[qt * 16 + row];
+        // Instruction order: one matrix instruction of the next query tile, then the multiply-add of element e, the
+        // exponential of element e - 1 and the add of element e - 2 of this tile -- a matrix instruction keeps its
+        // pipe busy for as long as those vector instructions take to issue, and none of them waits for its
+        // neighbour.  The fences keep the scheduler from gathering the matrix instructions in one place.
+        float y[n_e > 0 ? n_e : 1], pr[n_e > 0 ? n_e : 1];
 #pragma unroll
-        for (int t = 0; t < NTL; ++t)
+        for (int step = 0; step < n_e + 2; ++step) {
+            if (has_next && step < n_e) {
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) acc[t][rr] += __builtin_amdgcn_exp2f(fmaf(sv[qt & 1][t][rr], c2, -l2));
+                for (int m = step * n_m / n_e; m < (step + 1) * n_m / n_e; ++m) {
+                    const int kb = m / NTL, t = m % NTL;
+                    sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kb], qf[nxt][kb], sv[nxt][t], 0, 0, 0);
+                }
+            }
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -l2);
+            if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
+            if (step >= 2) acc[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
+// Wavefronts per SIMD the register budget of a head dim allows without spilling (more of them: more chances that one
+// issues vector instructions while another's matrix instruction runs).
+#ifndef SV_COLSUM_W
+#define SV_COLSUM_W(D) ((D) <= 64 ? 4 : 3)
+#endif
 template <int D>
-__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void salience_colsum_kernel(const SalienceArgs a) {
+__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV_COLSUM_W(D), SV_COLSUM_W(D)))) void salience_colsum_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
     __shared__ KeyStage<KB> stage[2];
     __shared__ float s_lse2[2][kStageKeys];
@@ -261,7 +354,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     auto put = [&](int buf) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) stage[buf].w[wave][kb][lane] = qfetch[kb];
-        if (quad == 0) s_lse2[buf][wave * 16 + row] = lfetch;
+        s_lse2[buf][wave * 16 + row] = lfetch;   // the four quads store the same value: no divergent branch in the loop body
     };
     auto run = [&](auto ntl_c) __attribute__((always_inline)) {
         constexpr int NTL = decltype(ntl_c)::value;
@@ -271,10 +364,12 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         __syncthreads();
         int cur = 0;
         for (int s0 = q0; s0 < q_end; s0 += kStageKeys) {
-            const bool more = s0 + kStageKeys < q_end;   // block-uniform
-            if (more) fetch(s0 + kStageKeys);
+            // No branch inside the body: the fetch and the store of the stage after the last one are harmless (clamped
+            // rows, a buffer nobody reads), and a conditional store in the middle made the compiler sink every
+            // vector instruction of the stage below it, away from the matrix instructions they are to overlap with.
+            fetch(s0 + kStageKeys);
             colsum_swapped_stage<KB, NTL>(stage[cur], s_lse2[cur], lane, ka, c2, acc);
-            if (more) put(cur ^ 1);
+            put(cur ^ 1);
             __syncthreads();
             cur ^= 1;
         }
@@ -324,18 +419,20 @@ SaliencePlan salience_plan(int B, int H, int N) {
     SaliencePlan p{};
     if (B < 1 || H < 1 || N < 1) return p;
     p.n_row_chunks = (N + kRowsPerGroup - 1) / kRowsPerGroup;
-    const int granule = 1024;   // keys per workgroup in pass 1, raised for long rows so that a row has at most 16 blocks
-    p.stat_block_keys = granule * ((N + granule * kMaxStatBlocks - 1) / (granule * kMaxStatBlocks));
-    p.n_stat_blocks = (N + p.stat_block_keys - 1) / p.stat_block_keys;
-    const int64_t base = (int64_t)B * H * p.n_row_chunks;   // pass 2 workgroups with one query segment
-    int64_t want = (kTargetColsumGroups + base - 1) / base;
-    const int64_t most = N / 512 > 1 ? N / 512 : 1;          // a segment has at least 512 query tokens
+    // Both passes hold a group of 256 tokens in registers and stream the others; the streamed side is cut into
+    // segments only as far as it takes to fill the chip (a workgroup pays for loading its held rows and for a
+    // merge at the end, so long segments are cheaper), and a segment has at least 512 tokens.
+    const int64_t base = (int64_t)B * H * p.n_row_chunks;   // workgroups with one segment
+    int64_t want = (kTargetGroups + base - 1) / base;
+    const int64_t most = N / 512 > 1 ? N / 512 : 1;
     if (want > most) want = most;
     if (want < 1) want = 1;
     int seg_len = (int)((N + want - 1) / want);
     seg_len = (seg_len + kStageKeys - 1) / kStageKeys * kStageKeys;
     p.seg_len = seg_len;
     p.n_seg = (N + seg_len - 1) / seg_len;
+    p.stat_block_keys = p.seg_len;
+    p.n_stat_blocks = p.n_seg;
     p.part_bytes = (size_t)B * H * p.n_row_chunks * p.n_stat_blocks * kRowsPerGroup * 2 * sizeof(float);
     p.colpart_bytes = (size_t)B * H * p.n_seg * N * sizeof(float);
     return p;

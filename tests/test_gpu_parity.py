@@ -718,3 +718,22 @@ def test_salience_self_feeds_the_selection_and_is_deterministic():
     want_idx, want_cnt = oracle.topk_select(got.astype(np.float64)[:, None], keep, vis_len)
     assert np.array_equal(cnt, want_cnt) and np.array_equal(idx, want_idx)
     assert check_index_sets(want[:, None], keep, vis_len, idx, cnt).ok
+
+
+def test_salience_self_redoes_a_key_block_whose_sums_overflow():
+    """Pass 1 takes a row's reference from its first 16 keys of a key block and never raises it; keys whose logits
+    lie hundreds of units above those (here one planted key per head, deep inside the second key block of each row,
+    plus a block that starts with very negative logits) overflow the sums, and the kernel must notice and redo
+    the block exactly.  The oracle's answer: nearly all the attention goes to the planted keys."""
+    rng = np.random.default_rng(9100)
+    B, N, H, D = 1, 1500, 2, 64
+    q = np.full((B, N, H, D), 4.0, np.float16)
+    q += rng.standard_normal((B, N, H, D), dtype=np.float32).astype(np.float16)
+    k = (0.1 * rng.standard_normal((B, H, N, D), dtype=np.float32)).astype(np.float16)
+    k[0, 0, 1300] = 20.0            # logit ~ 0.125 * 64 * 4 * 20 = 640: 2^900 above the row's first keys
+    k[0, 1, 1100] = 3.0             # logit ~ 96: above the reference by more than 2^100
+    k[0, 1, :64] = -3.0             # and a first stage of very negative logits in the first block
+    sal, lse = _salience_on_gpu(q, k)
+    got = sal.cpu().numpy()
+    want = _assert_salience_matches(q, k, None, 0.0, got, lse.cpu().numpy())
+    assert want[0, 1300] > 0.49 and want[0, 1100] > 0.49
