@@ -17,7 +17,7 @@
 //          blocks into lse[b,i,h] = log sum_keys exp(logit);
 //   pass 2 (mass_colsum_kernel)    p = exp(logit - lse) for every (row, visual key), summed over
 //          the rows: each lane sums the rows it holds, lanes and wavefronts are merged once per
-//          block of 256 keys.
+//          stage of 64 keys.
 // The R = Tq * G query rows of a (b, g) are cut into tiles of 16; a wavefront of a workgroup
 // holds up to four of them in registers for the whole kernel (R <= 256), and all four wavefronts
 // work on the same keys.  The keys come through LDS in stages of 64: wavefront w fetches key tile w
@@ -25,11 +25,12 @@
 // LDS buffer afterwards (one barrier per stage), so a key line crosses the memory system once per
 // workgroup and a whole stage of compute hides its latency.  (Each wavefront fetching every key
 // tile itself, one tile ahead, was bound by that latency: 2 us per 16 keys.)
-// The work is a contraction plus one exponential per (row, key) and pass: bound by the
-// exponential and matrix pipes, not by HBM.  Everything runs in base 2 (scale * log2(e) folded into
-// one multiply-add before v_exp_f32).  Pass 1 keeps a reference per (lane, row) that is raised only
-// when a logit exceeds it by more than 2^8: the usual case is one multiply-add, one exponential and
-// one add per element, and the sums stay far from overflow.
+// The work is a contraction plus one exponential per (row, key) and pass: bound by the vector and
+// matrix pipes, not by HBM.  Everything runs in base 2 (scale * log2(e) folded into one multiply-add
+// before v_exp_f32), and an element costs a multiply-add, an exponential and an add in both passes.
+// Pass 1 takes a row's reference from its first visual keys of the block and never raises it; sums
+// that leave the trusted range send the block through an exact sweep.  The matrix instructions of
+// the next key tile are placed between the vector instructions of the current one.
 #include <type_traits>
 
 #include "sv_kernels.h"
@@ -38,9 +39,7 @@
 namespace sv {
 namespace {
 
-constexpr int kStatBlockKeys = 1024;              // keys per workgroup in pass 1
-constexpr int kColBlockKeys = 256;                // keys per sub-block in pass 2 (their masses sit in registers)
-constexpr int kColSubBlocks = 4;                  // sub-blocks per workgroup: the query tiles are loaded once for 1024 keys
+constexpr int kMinBlockKeys = 1024;               // a workgroup streams at least this many keys (if the row has them)
 
 // The A operands of this wavefront: a row tile holds rows 16*tile + (lane & 15); lane (row, quad) supplies
 // dims 8*quad + 32*kb .. +8.  Row r is query token r / G, head g*G + r % G; rows >= R are zero.
@@ -68,7 +67,8 @@ __device__ __forceinline__ void load_query_tiles(const MassArgs& a, int b, int g
 // Key list of a (b, g): text rows [0, nt), then visual rows [0, nv).  Query token i sits at text row
 // nt - Tq + i and sees the text rows up to itself.
 template <int D>
-// Two wavefronts per SIMD (256 registers): one register more and the compiler settles for one.
+// Two wavefronts per SIMD: the query tiles, the two statistics of 16 rows and two key tiles in flight need more
+// than the 168 registers that three would leave.
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mass_rowstat_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
     __shared__ KeyStage<KB> stage[2];
@@ -78,13 +78,15 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int row = lane & 15, quad = lane >> 4;
     const int rot = blk & (kMassWaves - 1);
     const int nt = live_len(a.txt_len, b, a.n_txt_max), nv = live_len(a.vis_len, b, a.n_vis_max);
-    const int n_keys = nt + nv;
-    const int key0 = blk * kStatBlockKeys;
+    // The first n_txt_blocks key blocks cover the text rows, the others the visual rows: a workgroup streams one kind
+    // of key only, with one base address and one stride.
+    const bool is_txt = blk < a.n_txt_blocks;                                    // block-uniform
+    const int key0 = (is_txt ? blk : blk - a.n_txt_blocks) * a.stat_block_keys;   // within the text or the visual rows
+    const int n_keys = is_txt ? nt : nv;
     const int R = a.Tq * a.G;
     const int ntl = live_tiles_of(wave, rot, R);   // wave-uniform
     const float c2 = a.scale * kLog2e;
-    const int64_t unit = (int64_t)b * a.Hkv + g;
-    float* part = a.part + ((unit * a.n_stat_blocks + blk) * (int64_t)(kMaxRowTiles * 16)) * 2;
+    if (key0 >= n_keys) return;   // block-uniform; the merge reads the live blocks only
     // last text row that query row r sees: its token i = r / G sits at text row nt - Tq + i (one division per
     // row here instead of one per logit in the masked tiles); read after the first barrier below
     static_assert(kMassThreads == kMaxRowTiles * 16, "one thread per query row");
@@ -93,45 +95,39 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     half8_t qa[kTilesPerWave][KB];
     load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
     // per lane, for the 4 rows (4*quad + rr) of each of its tiles, over the key columns it sees, in base 2:
-    // a reference value ref (the largest logit met, or up to 8 below it) and l = sum 2^(logit - ref)
+    // a reference value ref and l = sum 2^(logit - ref)
     float ref[kTilesPerWave][4], l[kTilesPerWave][4];
-#pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t)
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            ref[t][rr] = -INFINITY;
-            l[t][rr] = 0.f;
-        }
-    const _Float16* ktxt = static_cast<const _Float16*>(a.k_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh;
-    const _Float16* kvis = static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const _Float16* keys = is_txt ? static_cast<const _Float16*>(a.k_txt) + (int64_t)b * a.txt_sb + (int64_t)g * a.txt_sh
+                                  : static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+    const int64_t key_sn = is_txt ? a.txt_sn : a.vis_sn;
 
-    const int k_end = min(key0 + kStatBlockKeys, n_keys);
+    const int k_end = min(key0 + a.stat_block_keys, n_keys);
     half8_t kfetch[KB];
-    auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns
-        const int kc = min(s0 + wave * 16 + row, n_keys - 1);   // are masked at use
-        if (kc < nt) load_key_tile<KB>(ktxt, a.txt_sn, kc, quad, kfetch);
-        else load_key_tile<KB>(kvis, a.vis_sn, kc - nt, quad, kfetch);
+    auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns masked at use
+        load_key_tile<KB>(keys, key_sn, min(s0 + wave * 16 + row, n_keys - 1), quad, kfetch);
     };
     auto put = [&](KeyStage<KB>& st) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
     };
-    // text tiles, ragged tiles, and visual tiles met before every reference is set: masked, exact running maximum
+    // text tiles, ragged tiles, visual tiles met before every reference is set, and every tile of an exact sweep:
+    // masked, exact running maximum
     auto masked_tile = [&](int k0, const KeyStage<KB>& st, int kt) {
         half8_t kf[KB];
         read_key_tile<KB>(st, kt, lane, kf);
         const int key = k0 + row;   // this lane's key column
-        float4_t sv[kTilesPerWave];
-        tile_logits<KB, kTilesPerWave>(qa, kf, sv);   // rows past R are zero rows: computed, never stored
 #pragma unroll
-        for (int t = 0; t < kTilesPerWave; ++t) {
+        for (int t = 0; t < kTilesPerWave; ++t) {   // one row tile at a time: this path is rare and is kept light on registers
+            float4_t sv = {0.f, 0.f, 0.f, 0.f};     // rows past R are zero rows: computed, never stored
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) sv = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], sv, 0, 0, 0);
             const int4 last4 = *reinterpret_cast<const int4*>(&s_last_txt[row_tile_of(wave, rot, t) * 16 + 4 * quad]);
             const int last_of[4] = {last4.x, last4.y, last4.z, last4.w};
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int last_txt = last_of[rr];
-                const bool seen = key < n_keys && (key >= nt || key <= last_txt);
-                const float x = seen ? sv[t][rr] * c2 : -INFINITY;
+                const bool seen = key < n_keys && (!is_txt || key <= last_txt);
+                const float x = seen ? sv[rr] * c2 : -INFINITY;
                 const float mn = fmaxf(ref[t][rr], x);
                 if (mn > -INFINITY) {   // something seen so far
                     l[t][rr] = l[t][rr] * __builtin_amdgcn_exp2f(ref[t][rr] - mn) + __builtin_amdgcn_exp2f(x - mn);
@@ -140,11 +136,21 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             }
         }
     };
-    // The stage loop is instantiated once per count of live row tiles and chosen outside the loop: a switch
-    // inside it made the compiler shuffle the 32 state registers between the arms at every stage (as many
-    // moves and selects as useful instructions).
-    auto run = [&](auto ntl_c) __attribute__((always_inline)) {
+    // One sweep over the key block.  exact = false: full visual stages on the fast path once every reference is
+    // set; exact = true: every tile with the exact running maximum (taken only after a sweep whose sums left the
+    // trusted range).  Instantiated once per count of live row tiles and chosen outside the loop (a switch inside it
+    // makes the compiler shuffle the state registers between the arms at every stage).  No branch around the fetch
+    // and the store of the next stage: past the end they are harmless (clamped rows, a buffer nobody reads), and
+    // conditional blocks in the body keep the scheduler from placing the matrix and vector instructions together.
+    auto run = [&](auto ntl_c, bool exact) __attribute__((always_inline)) {
         constexpr int NTL = decltype(ntl_c)::value;
+#pragma unroll
+        for (int t = 0; t < kTilesPerWave; ++t)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                ref[t][rr] = -INFINITY;
+                l[t][rr] = 0.f;
+            }
         fetch(key0);
         wait_for_loads();
         put(stage[0]);
@@ -152,13 +158,12 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         int cur = 0;
         bool ref_ready = false;   // block-uniform: every reference is finite
         for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
-            const bool more = s0 + kStageKeys < k_end;   // block-uniform
-            if (more) fetch(s0 + kStageKeys);
-            const bool plain = s0 >= nt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
+            fetch(s0 + kStageKeys);
+            const bool plain = !exact && !is_txt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
             if (plain && ref_ready) {
-                rowstat_plain_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
             } else if (plain && s0 == key0) {   // first stage of the block: nothing seen so far
-                rowstat_plain_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
                 ref_ready = true;
             } else {
 #pragma unroll 1
@@ -166,27 +171,37 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
                     if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);
                 if (plain) ref_ready = true;   // every row saw these 64 keys
             }
-            if (more) put(stage[cur ^ 1]);
+            put(stage[cur ^ 1]);
             __syncthreads();
             cur ^= 1;
         }
     };
-    if (key0 < k_end) {   // block-uniform
-        switch (ntl) {    // wave-uniform
-            case 4: run(std::integral_constant<int, 4>{}); break;
-            case 3: run(std::integral_constant<int, 3>{}); break;
-            case 2: run(std::integral_constant<int, 2>{}); break;
-            case 1: run(std::integral_constant<int, 1>{}); break;
-            default: run(std::integral_constant<int, 0>{}); break;
+    auto sweep = [&](bool exact) __attribute__((always_inline)) {
+        switch (ntl) {   // wave-uniform
+            case 4: run(std::integral_constant<int, 4>{}, exact); break;
+            case 3: run(std::integral_constant<int, 3>{}, exact); break;
+            case 2: run(std::integral_constant<int, 2>{}, exact); break;
+            case 1: run(std::integral_constant<int, 1>{}, exact); break;
+            default: run(std::integral_constant<int, 0>{}, exact); break;
         }
-    }
+    };
+    sweep(false);
+    // did a sum leave the range in which it is trusted (inf, NaN, or huge: a logit far above its row's reference)?
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < kTilesPerWave; ++t)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < kSumLimit);
+    if (__syncthreads_or(bad)) sweep(true);   // block-uniform
     // merge the 16 key columns of a row (the lanes of a 16-lane row hold the same rows), store per block
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    float* part = a.part + ((unit * a.n_stat_blocks + blk) * (int64_t)(kMaxRowTiles * 16)) * 2;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
         const int tile = row_tile_of(wave, rot, t);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the plain stages leave dead tiles untouched,
+            const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the fast stages leave dead tiles untouched,
             const float lmine = t < ntl ? l[t][rr] : 0.f;          // the masked ones compute them: drop both
             const float mx = row_max16(mine);
             const float e = mine > -INFINITY ? __builtin_amdgcn_exp2f(mine - mx) : 0.f;
@@ -200,7 +215,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     }
 }
 
-// lse[b, i, h] = log sum over the key blocks; one thread per query row.
+// lse[b, i, h] = log sum over the live key blocks (text blocks first, then visual ones); one thread per query row.
 __global__ __launch_bounds__(256) void mass_lse_kernel(const MassArgs a) {
     const int g = blockIdx.y, b = blockIdx.z;
     const int r = blockIdx.x * 256 + threadIdx.x;
@@ -208,12 +223,16 @@ __global__ __launch_bounds__(256) void mass_lse_kernel(const MassArgs a) {
     if (r >= R) return;
     const int64_t unit = (int64_t)b * a.Hkv + g;
     const int nt = live_len(a.txt_len, b, a.n_txt_max), nv = live_len(a.vis_len, b, a.n_vis_max);
-    const int live_blocks = (nt + nv + kStatBlockKeys - 1) / kStatBlockKeys;
     const float* part = a.part + (unit * a.n_stat_blocks * (int64_t)(kMaxRowTiles * 16)) * 2;
+    auto live = [&](int s) {   // did pass 1 run this block?
+        return s < a.n_txt_blocks ? s * a.stat_block_keys < nt : (s - a.n_txt_blocks) * a.stat_block_keys < nv;
+    };
     float mx = -INFINITY;
-    for (int s = 0; s < live_blocks; ++s) mx = fmaxf(mx, part[((int64_t)s * kMaxRowTiles * 16 + r) * 2]);
+    for (int s = 0; s < a.n_stat_blocks; ++s)
+        if (live(s)) mx = fmaxf(mx, part[((int64_t)s * kMaxRowTiles * 16 + r) * 2]);
     float sum = 0.f;
-    for (int s = 0; s < live_blocks; ++s) {
+    for (int s = 0; s < a.n_stat_blocks; ++s) {
+        if (!live(s)) continue;
         const float ms = part[((int64_t)s * kMaxRowTiles * 16 + r) * 2];
         if (ms > -INFINITY) sum += part[((int64_t)s * kMaxRowTiles * 16 + r) * 2 + 1] * expf(ms - mx);
     }
@@ -231,134 +250,165 @@ __device__ __forceinline__ void colsum_stage(const KeyStage<KB>& st, int lane, c
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, kf[0]);
     tile_logits<KB, NTL>(qa, kf[0], sv[0]);
+    constexpr int n_m = KB * NTL, n_e = 4 * NTL;   // matrix instructions of a key tile, elements per lane of a key tile
+    constexpr int NT1 = NTL > 0 ? NTL : 1, n_e1 = n_e > 0 ? n_e : 1;   // divisors that exist when a wavefront holds no live tile
+    static_assert(KB <= 4, "at most one matrix instruction per element");
 #pragma unroll
     for (int kt = 0; kt < kMassWaves; ++kt) {
-        if (kt + 1 < kMassWaves) {
-            read_key_tile<KB>(st, kt + 1, lane, kf[(kt + 1) & 1]);
-            tile_logits<KB, NTL>(qa, kf[(kt + 1) & 1], sv[(kt + 1) & 1]);
+        const int cur = kt & 1, nxt = cur ^ 1;
+        const bool has_next = kt + 1 < kMassWaves;
+        if (has_next) {
+            read_key_tile<KB>(st, kt + 1, lane, kf[nxt]);
+#pragma unroll
+            for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
         }
-        float acc = 0.f;
+        // Instruction order: one matrix instruction of the next key tile, then the multiply-add of element e, the
+        // exponential of element e - 1 and the add of element e - 2 of this tile (two partial sums, so that no add
+        // waits for the one before it), fenced so that the scheduler keeps it.
+        float y[n_e1], pr[n_e1], part[2] = {0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < NTL; ++t)
+        for (int step = 0; step < n_e + 2; ++step) {
+            if (has_next && step < n_e) {
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) acc += __builtin_amdgcn_exp2f(fmaf(sv[kt & 1][t][rr], c2, -lse2[t][rr]));
-        col[kt] = acc;
+                for (int m = step * n_m / n_e1; m < (step + 1) * n_m / n_e1; ++m) {
+                    const int kb = m / NT1, t = m % NT1;
+                    sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
+                }
+            }
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -lse2[step / 4][step % 4]);
+            if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
+            if (step >= 2) part[(step - 2) & 1] += pr[step - 2];
+            SV_STAGE_FENCE();
+        }
+        col[kt] = part[0] + part[1];
     }
 }
 
 template <int D>
-// Three wavefronts per SIMD: at 168 registers the compiler keeps the matrix results in VGPRs (no copies from
-// accumulation registers) and still pipelines the key tiles; measured against two wavefronts per SIMD below.
+// Three wavefronts per SIMD (168 registers): the more of them, the more often one issues vector instructions while
+// another's matrix instruction runs.
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void mass_colsum_kernel(const MassArgs a) {
     constexpr int KB = D / 32;
-    constexpr int KT = kColBlockKeys / 16;   // key tiles per sub-block
     __shared__ KeyStage<KB> stage[2];
-    __shared__ float s_col[kMassWaves][kColBlockKeys];
+    __shared__ float s_col[2][kMassWaves][kStageKeys];
     const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int row = lane & 15, quad = lane >> 4;
     const int rot = blk & (kMassWaves - 1);
     const int nv = live_len(a.vis_len, b, a.n_vis_max);
-    const int key0 = blk * kColBlockKeys * kColSubBlocks;
+    const int key0 = blk * a.stat_block_keys;
+    const int blk_end = min(key0 + a.stat_block_keys, a.n_vis_max);   // keys this workgroup writes
+    const int k_end = min(blk_end, nv);                                // live keys among them
     const int R = a.Tq * a.G;
     const int ntl = live_tiles_of(wave, rot, R);   // wave-uniform
     const float c2 = a.scale * kLog2e;
     const int64_t unit = (int64_t)b * a.Hkv + g;
     float* out = a.scores + unit * a.n_vis_max;
 
-    half8_t qa[kTilesPerWave][KB];
-    load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
-    float lse2[kTilesPerWave][4];   // base 2, of rows 4*quad + rr of each tile; +inf for the padding rows: p = 0
+    if (key0 < k_end) {   // block-uniform
+        half8_t qa[kTilesPerWave][KB];
+        load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
+        float lse2[kTilesPerWave][4];   // base 2, of rows 4*quad + rr of each tile; +inf for the padding rows: p = 0
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t)
+        for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int r = row_tile_of(wave, rot, t) * 16 + 4 * quad + rr;
-            const int rc = min(r, R - 1);
-            const int i = rc / a.G, hh = rc - i * a.G;
-            const float v = a.lse[((int64_t)b * a.Tq + i) * a.Hq + g * a.G + hh];   // unconditional, clamped row
-            lse2[t][rr] = r < R ? v * kLog2e : INFINITY;
-        }
-    const _Float16* kvis = static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
-    const int k_end = min(key0 + kColBlockKeys * kColSubBlocks, nv);   // live keys of this workgroup end here
-
-    half8_t kfetch[KB];
-    auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns dropped below
-        load_key_tile<KB>(kvis, a.vis_sn, min(s0 + wave * 16 + row, nv - 1), quad, kfetch);
-    };
-    auto put = [&](KeyStage<KB>& st) {
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = row_tile_of(wave, rot, t) * 16 + 4 * quad + rr;
+                const int rc = min(r, R - 1);
+                const int i = rc / a.G, hh = rc - i * a.G;
+                const float v = a.lse[((int64_t)b * a.Tq + i) * a.Hq + g * a.G + hh];   // unconditional, clamped row
+                lse2[t][rr] = r < R ? v * kLog2e : INFINITY;
+            }
+        const _Float16* kvis = static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
+        half8_t kfetch[KB];
+        auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns dropped below
+            load_key_tile<KB>(kvis, a.vis_sn, min(s0 + wave * 16 + row, nv - 1), quad, kfetch);
+        };
+        auto put = [&](KeyStage<KB>& st) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
-    };
-    int cur = 0;
-    if (key0 < k_end) fetch(key0);   // block-uniform
-    wait_for_loads();
-    if (key0 < k_end) put(stage[0]);
-    __syncthreads();
-    for (int sub = 0; sub < kColSubBlocks; ++sub) {
-        const int sub0 = key0 + sub * kColBlockKeys;
-        if (sub0 >= a.n_vis_max) break;   // block-uniform
-        float col[KT];   // per lane: mass of key column (16*kt + row) from the rows this lane holds
+            for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
+        };
+        // Chosen outside the loop per count of live row tiles; the fetch and the store of the stage after the last
+        // one are harmless (clamped rows, a buffer nobody reads) and so sit in no conditional block.
+        auto run = [&](auto ntl_c) __attribute__((always_inline)) {
+            constexpr int NTL = decltype(ntl_c)::value;
+            fetch(key0);
+            wait_for_loads();
+            put(stage[0]);
+            __syncthreads();
+            int cur = 0;
+            for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
+                fetch(s0 + kStageKeys);
+                float col[kMassWaves];   // per lane: mass of key column (16*kt + row) of this stage from the rows this lane holds
+                colsum_stage<KB, NTL>(stage[cur], lane, qa, c2, lse2, col);
+                // the four quads of a wavefront hold different rows of the same key columns: add them (every lane ends
+                // up with the total, and the four quads store the same value: no divergent branch)
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) col[kt] = 0.f;
-        if (sub0 < k_end) {   // block-uniform
-#pragma unroll
-            for (int st = 0; st < kColBlockKeys / kStageKeys; ++st) {
-                const int s0 = sub0 + st * kStageKeys;
-                if (s0 >= k_end) break;   // block-uniform
-                const bool more = s0 + kStageKeys < k_end;
-                if (more) fetch(s0 + kStageKeys);
-                switch (ntl) {
-                    case 4: colsum_stage<KB, 4>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
-                    case 3: colsum_stage<KB, 3>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
-                    case 2: colsum_stage<KB, 2>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
-                    case 1: colsum_stage<KB, 1>(stage[cur], lane, qa, c2, lse2, &col[st * kMassWaves]); break;
-                    default: break;
+                for (int kt = 0; kt < kMassWaves; ++kt) {
+                    float x = col[kt];
+                    x += __shfl_xor(x, 16, kWave);
+                    x += __shfl_xor(x, 32, kWave);
+                    s_col[cur][wave][kt * 16 + row] = x;
                 }
-                if (more) put(stage[cur ^ 1]);
+                put(stage[cur ^ 1]);
                 __syncthreads();
+                // then the wavefronts: wavefront w finishes keys 16w .. 16w + 15 of the stage; s_col[cur] is written
+                // again two stages on, behind the next barrier
+                if (lane < 16) {
+                    const int j = wave * 16 + lane, key = s0 + j;
+                    if (key < blk_end) {
+                        const float x = (s_col[cur][0][j] + s_col[cur][1][j]) + (s_col[cur][2][j] + s_col[cur][3][j]);
+                        out[key] = key < nv ? x : -INFINITY;
+                    }
+                }
                 cur ^= 1;
             }
+        };
+        switch (ntl) {   // wave-uniform
+            case 4: run(std::integral_constant<int, 4>{}); break;
+            case 3: run(std::integral_constant<int, 3>{}); break;
+            case 2: run(std::integral_constant<int, 2>{}); break;
+            case 1: run(std::integral_constant<int, 1>{}); break;
+            default: run(std::integral_constant<int, 0>{}); break;
         }
-        // the four quads of a wavefront hold different rows of the same key columns: add them, then the wavefronts
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
-            float x = col[kt];
-            x += __shfl_xor(x, 16, kWave);
-            x += __shfl_xor(x, 32, kWave);
-            if (quad == 0) s_col[wave][kt * 16 + row] = x;
-        }
-        __syncthreads();
-        for (int j = threadIdx.x; j < kColBlockKeys; j += kMassThreads) {
-            const int key = sub0 + j;
-            if (key < a.n_vis_max) {
-                const float x = (s_col[0][j] + s_col[1][j]) + (s_col[2][j] + s_col[3][j]);
-                out[key] = key < nv ? x : -INFINITY;
-            }
-        }
-        __syncthreads();
     }
+    // keys of the block past the stages above hold no live token
+    const int done = key0 < k_end ? key0 + (k_end - key0 + kStageKeys - 1) / kStageKeys * kStageKeys : key0;
+    for (int key = done + (int)threadIdx.x; key < blk_end; key += kMassThreads) out[key] = -INFINITY;
 }
 
 }  // namespace
 
-int mass_stat_blocks(int n_txt_max, int n_vis_max) { return (n_txt_max + n_vis_max + kStatBlockKeys - 1) / kStatBlockKeys; }
+namespace {
+struct MassPlan { int stat_block_keys, n_txt_blocks, n_stat_blocks, n_col_blocks; };
+MassPlan mass_plan(int B, int Hkv, int n_txt_max, int n_vis_max) {
+    MassPlan p{};
+    const int64_t units = (int64_t)B * Hkv;
+    // one block length for both passes, planned on the visual rows (the text rows are few)
+    p.stat_block_keys = planned_block_len(units, n_vis_max, kMinBlockKeys);
+    p.n_txt_blocks = (n_txt_max + p.stat_block_keys - 1) / p.stat_block_keys;
+    p.n_col_blocks = (n_vis_max + p.stat_block_keys - 1) / p.stat_block_keys;
+    p.n_stat_blocks = p.n_txt_blocks + p.n_col_blocks;
+    return p;
+}
+}  // namespace
+
 int mass_max_rows() { return kMaxRowTiles * 16; }
 
 size_t mass_workspace_bytes(int B, int Hkv, int n_txt_max, int n_vis_max) {
-    return (size_t)B * Hkv * mass_stat_blocks(n_txt_max, n_vis_max) * kMaxRowTiles * 16 * 2 * sizeof(float);
+    return (size_t)B * Hkv * mass_plan(B, Hkv, n_txt_max, n_vis_max).n_stat_blocks * kMaxRowTiles * 16 * 2 * sizeof(float);
 }
 
 hipError_t launch_mass(const MassArgs& a, hipStream_t stream) {
     if (a.B == 0 || a.Hkv == 0 || a.n_vis_max == 0) return hipSuccess;
     if (a.Tq * a.G > kMaxRowTiles * 16 || a.Tq < 1) return hipErrorInvalidValue;
+    const MassPlan p = mass_plan(a.B, a.Hkv, a.n_txt_max, a.n_vis_max);
     MassArgs k = a;
-    k.n_stat_blocks = mass_stat_blocks(a.n_txt_max, a.n_vis_max);
+    k.stat_block_keys = p.stat_block_keys; k.n_txt_blocks = p.n_txt_blocks; k.n_stat_blocks = p.n_stat_blocks;
     const dim3 block(kMassThreads);
-    const dim3 grid1((unsigned)k.n_stat_blocks, (unsigned)a.Hkv, (unsigned)a.B);
+    const dim3 grid1((unsigned)p.n_stat_blocks, (unsigned)a.Hkv, (unsigned)a.B);
     const dim3 grid2((unsigned)((a.Tq * a.G + 255) / 256), (unsigned)a.Hkv, (unsigned)a.B);
-    const dim3 grid3((unsigned)((a.n_vis_max + kColBlockKeys * kColSubBlocks - 1) / (kColBlockKeys * kColSubBlocks)),
-                     (unsigned)a.Hkv, (unsigned)a.B);
+    const dim3 grid3((unsigned)p.n_col_blocks, (unsigned)a.Hkv, (unsigned)a.B);
     if (a.D == 128) {
         hipLaunchKernelGGL((mass_rowstat_kernel<128>), grid1, block, 0, stream, k);
         hipLaunchKernelGGL(mass_lse_kernel, grid2, dim3(256), 0, stream, k);

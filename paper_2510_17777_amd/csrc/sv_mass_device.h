@@ -5,6 +5,10 @@
 #pragma once
 #include "sv_device.h"
 
+#ifndef SV_STAGE_FENCE
+#define SV_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
 namespace sv {
 
 constexpr int kMassWaves = 4;
@@ -14,7 +18,8 @@ constexpr int kTilesPerWave = kMaxRowTiles / kMassWaves;
 constexpr int kStageKeys = 16 * kMassWaves;       // keys per LDS stage: one key tile per wavefront
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kRaiseAbove = 8.f;                // pass 1: a reference is raised when a logit tops it by 2^8
+constexpr float kSumLimit = 0x1p100f;             // pass 1: a sum at or above this (or NaN) sends its key block to the exact path
+constexpr int kTargetGroups = 3072;               // the streamed side is cut into blocks until this many workgroups exist
 
 __device__ __forceinline__ int live_len(const int32_t* p, int i, int cap) {
     if (!p) return cap;
@@ -79,64 +84,76 @@ __device__ __forceinline__ float row_max16(float x) {
 // for them there would also wait for the keys fetched one stage ahead.
 __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
-// Pass 1, a stage of 64 live keys that every row sees: per lane, for rows 4*quad + rr of each row tile over
-// the key columns the lane meets, a reference value ref and l = sum 2^(logit - ref), in base 2.  kInit: nothing was seen before, the first
-// key tile sets the references.  The logits of key tile k + 1 are issued before those of tile k are used.
+// Pass 1.  A stage of 64 live keys on the fast path.  The reference of a row is the largest of its first 16 logits of
+// the key block (kInit, shared by the row's 16 lanes) and is never raised: a later logit far above it makes a
+// large term, which fp32 sums as accurately as a small one; only a logit more than ~2^7 above it (in base 2)
+// would overflow, and the kernel checks the sums for that after the block and redoes the block on the exact path.
+// So an element costs a multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no
+// branch; the matrix instructions of the next key tile go between the vector instructions of this one.
 template <int KB, int NTL, bool kInit>
-__device__ __forceinline__ void rowstat_plain_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
-                                                    float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
+__device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
+                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
     half8_t kf[2][KB];
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, kf[0]);
     tile_logits<KB, NTL>(qa, kf[0], sv[0]);
+    constexpr int n_m = KB * NTL, n_e = 4 * NTL;
+    constexpr int NT1 = NTL > 0 ? NTL : 1, n_e1 = n_e > 0 ? n_e : 1;   // divisors that exist when a wavefront holds no live tile
+    static_assert(KB <= 4, "at most one matrix instruction per element");
 #pragma unroll
     for (int kt = 0; kt < kMassWaves; ++kt) {
-        if (kt + 1 < kMassWaves) {
-            read_key_tile<KB>(st, kt + 1, lane, kf[(kt + 1) & 1]);
-            tile_logits<KB, NTL>(qa, kf[(kt + 1) & 1], sv[(kt + 1) & 1]);
+        const int cur = kt & 1, nxt = cur ^ 1;
+        const bool has_next = kt + 1 < kMassWaves;
+        if (has_next) {
+            read_key_tile<KB>(st, kt + 1, lane, kf[nxt]);
+#pragma unroll
+            for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
         }
-        float4_t(&y)[kTilesPerWave] = sv[kt & 1];
-        if (kInit && kt == 0) {
-            // the reference of a row: the largest of its first 16 logits, shared by the row's 16 lanes.  (A lane's
-            // own first logit is a poor reference: one lane-row in fifty then meets a logit 2^8 above it
-            // later in the block, and every such meeting sends the whole wavefront through the raise path.)
+        if (kInit && kt == 0) {   // once per key block: the references; the next tile's matrix instructions run meanwhile
+#pragma unroll
+            for (int m = 0; m < n_m; ++m)
+                sv[nxt][m % NT1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[m % NT1][m / NT1], kf[nxt][m / NT1], sv[nxt][m % NT1], 0, 0, 0);
 #pragma unroll
             for (int t = 0; t < NTL; ++t)
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const float x = y[t][rr] * c2;
+                    const float x = sv[cur][t][rr] * c2;
                     const float r0 = row_max16(x);
                     ref[t][rr] = r0;
                     l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
                 }
             continue;
         }
-        float top = -INFINITY;
+        float y[n_e1], pr[n_e1];
 #pragma unroll
-        for (int t = 0; t < NTL; ++t)
+        for (int step = 0; step < n_e + 2; ++step) {
+            if (has_next && step < n_e) {
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                y[t][rr] = fmaf(y[t][rr], c2, -ref[t][rr]);   // logit - ref, base 2
-                top = fmaxf(top, y[t][rr]);
+                for (int m = step * n_m / n_e1; m < (step + 1) * n_m / n_e1; ++m) {
+                    const int kb = m / NT1, t = m % NT1;
+                    sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
+                }
             }
-        if (__ballot(top > kRaiseAbove) != 0ull) {   // rare: some reference is raised to the logit that tops it
-            asm volatile("" ::: "memory");   // emits nothing; keeps this block a real branch (as straight-line
-                                             // selects it cost every key tile 16 more exponentials per lane)
-#pragma unroll
-            for (int t = 0; t < NTL; ++t)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr)
-                    if (y[t][rr] > kRaiseAbove) {
-                        l[t][rr] *= __builtin_amdgcn_exp2f(-y[t][rr]);
-                        ref[t][rr] += y[t][rr];
-                        y[t][rr] = 0.f;
-                    }
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
+            if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
+            if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
+            SV_STAGE_FENCE();
         }
-#pragma unroll
-        for (int t = 0; t < NTL; ++t)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) l[t][rr] += __builtin_amdgcn_exp2f(y[t][rr]);
     }
+}
+
+// Length of the blocks the streamed side (n rows) is cut into when `units` workgroup rows stream it: cut only as far
+// as it takes to fill the chip -- a workgroup pays for loading the rows it holds and for a merge at the end, so long
+// blocks are cheaper -- never below min_len rows, a multiple of the 64-row stage.
+inline int planned_block_len(int64_t units, int n, int min_len) {
+    if (n < 1) return kStageKeys;
+    if (units < 1) units = 1;
+    int64_t want = (kTargetGroups + units - 1) / units;
+    const int64_t most = n / min_len > 1 ? n / min_len : 1;
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    const int len = (int)((n + want - 1) / want);
+    return (len + kStageKeys - 1) / kStageKeys * kStageKeys;
 }
 
 }  // namespace sv

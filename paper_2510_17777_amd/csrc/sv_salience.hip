@@ -31,7 +31,6 @@ namespace sv {
 namespace {
 
 constexpr int kRowsPerGroup = kMaxRowTiles * 16;   // 256 rows held in registers by one workgroup
-constexpr int kTargetGroups = 3072;                // the streamed side is cut into segments until this many workgroups exist
 
 // A 16-row tile of the operand kept in registers: lane (row, quad) supplies dims 8*quad + 32*kb .. +8 of
 // row `r`; plain (cached) loads, every row is read again by other workgroups.
@@ -58,63 +57,6 @@ __device__ __forceinline__ void load_held_tiles(const _Float16* base, int64_t st
 }
 
 // ---- pass 1 ----
-// A stage of 64 live keys on the fast path.  The reference of a row is the largest of its first 16 logits of
-// the key block (kInit, shared by the row's 16 lanes) and is never raised: a later logit far above it makes a
-// large term, which fp32 sums as accurately as a small one; only a logit more than ~2^7 above it (in base 2)
-// would overflow, and the kernel checks the sums for that after the block and redoes the block on the exact path.
-// So an element costs a multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no
-// branch; the matrix instructions of the next key tile go between the vector instructions of this one.
-template <int KB, int NTL, bool kInit>
-__device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
-                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
-    half8_t kf[2][KB];
-    float4_t sv[2][kTilesPerWave];
-    read_key_tile<KB>(st, 0, lane, kf[0]);
-    tile_logits<KB, NTL>(qa, kf[0], sv[0]);
-    constexpr int n_m = KB * NTL, n_e = 4 * NTL;
-    static_assert(KB <= 4, "at most one matrix instruction per element");
-#pragma unroll
-    for (int kt = 0; kt < kMassWaves; ++kt) {
-        const int cur = kt & 1, nxt = cur ^ 1;
-        const bool has_next = kt + 1 < kMassWaves;
-        if (has_next) {
-            read_key_tile<KB>(st, kt + 1, lane, kf[nxt]);
-#pragma unroll
-            for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
-        }
-        if (kInit && kt == 0) {   // once per key block: the references; the next tile's matrix instructions run meanwhile
-#pragma unroll
-            for (int m = 0; m < n_m; ++m)
-                sv[nxt][m % NTL] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[m % NTL][m / NTL], kf[nxt][m / NTL], sv[nxt][m % NTL], 0, 0, 0);
-#pragma unroll
-            for (int t = 0; t < NTL; ++t)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const float x = sv[cur][t][rr] * c2;
-                    const float r0 = row_max16(x);
-                    ref[t][rr] = r0;
-                    l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
-                }
-            continue;
-        }
-        float y[n_e > 0 ? n_e : 1], pr[n_e > 0 ? n_e : 1];
-#pragma unroll
-        for (int step = 0; step < n_e + 2; ++step) {
-            if (has_next && step < n_e) {
-#pragma unroll
-                for (int m = step * n_m / n_e; m < (step + 1) * n_m / n_e; ++m) {
-                    const int kb = m / NTL, t = m % NTL;
-                    sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
-                }
-            }
-            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
-            if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
-            if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-}
-
 template <int D>
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void salience_rowstat_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
@@ -218,7 +160,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < 0x1p100f);
+        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < kSumLimit);
     if (__syncthreads_or(bad)) sweep(true);   // block-uniform
     // merge the 16 key columns of a row, store per key block (natural-log units from here on)
 #pragma unroll
@@ -277,6 +219,7 @@ __device__ __forceinline__ void colsum_swapped_stage(const KeyStage<KB>& st, con
     read_key_tile<KB>(st, 0, lane, qf[0]);
     tile_logits<KB, NTL>(ka, qf[0], sv[0]);
     constexpr int n_m = KB * NTL, n_e = 4 * NTL;   // matrix instructions of a query tile, elements per lane of a query tile
+    constexpr int NT1 = NTL > 0 ? NTL : 1, n_e1 = n_e > 0 ? n_e : 1;   // divisors that exist when a wavefront holds no live tile
     static_assert(KB <= 4, "at most one matrix instruction per element");
 #pragma unroll
     for (int qt = 0; qt < kMassWaves; ++qt) {
@@ -292,20 +235,20 @@ __device__ __forceinline__ void colsum_swapped_stage(const KeyStage<KB>& st, con
         // exponential of element e - 1 and the add of element e - 2 of this tile -- a matrix instruction keeps its
         // pipe busy for as long as those vector instructions take to issue, and none of them waits for its
         // neighbour.  The fences keep the scheduler from gathering the matrix instructions in one place.
-        float y[n_e > 0 ? n_e : 1], pr[n_e > 0 ? n_e : 1];
+        float y[n_e1], pr[n_e1];
 #pragma unroll
         for (int step = 0; step < n_e + 2; ++step) {
             if (has_next && step < n_e) {
 #pragma unroll
-                for (int m = step * n_m / n_e; m < (step + 1) * n_m / n_e; ++m) {
-                    const int kb = m / NTL, t = m % NTL;
+                for (int m = step * n_m / n_e1; m < (step + 1) * n_m / n_e1; ++m) {
+                    const int kb = m / NT1, t = m % NT1;
                     sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][kb], qf[nxt][kb], sv[nxt][t], 0, 0, 0);
                 }
             }
             if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -l2);
             if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
             if (step >= 2) acc[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
-            __builtin_amdgcn_sched_barrier(0);
+            SV_STAGE_FENCE();
         }
     }
 }
@@ -419,18 +362,9 @@ SaliencePlan salience_plan(int B, int H, int N) {
     SaliencePlan p{};
     if (B < 1 || H < 1 || N < 1) return p;
     p.n_row_chunks = (N + kRowsPerGroup - 1) / kRowsPerGroup;
-    // Both passes hold a group of 256 tokens in registers and stream the others; the streamed side is cut into
-    // segments only as far as it takes to fill the chip (a workgroup pays for loading its held rows and for a
-    // merge at the end, so long segments are cheaper), and a segment has at least 512 tokens.
-    const int64_t base = (int64_t)B * H * p.n_row_chunks;   // workgroups with one segment
-    int64_t want = (kTargetGroups + base - 1) / base;
-    const int64_t most = N / 512 > 1 ? N / 512 : 1;
-    if (want > most) want = most;
-    if (want < 1) want = 1;
-    int seg_len = (int)((N + want - 1) / want);
-    seg_len = (seg_len + kStageKeys - 1) / kStageKeys * kStageKeys;
-    p.seg_len = seg_len;
-    p.n_seg = (N + seg_len - 1) / seg_len;
+    // Both passes hold a group of 256 tokens in registers and stream the others in segments of one planned length.
+    p.seg_len = planned_block_len((int64_t)B * H * p.n_row_chunks, N, 512);
+    p.n_seg = (N + p.seg_len - 1) / p.seg_len;
     p.stat_block_keys = p.seg_len;
     p.n_stat_blocks = p.n_seg;
     p.part_bytes = (size_t)B * H * p.n_row_chunks * p.n_stat_blocks * kRowsPerGroup * 2 * sizeof(float);
