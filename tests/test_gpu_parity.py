@@ -737,3 +737,31 @@ def test_salience_self_redoes_a_key_block_whose_sums_overflow():
     got = sal.cpu().numpy()
     want = _assert_salience_matches(q, k, None, 0.0, got, lse.cpu().numpy())
     assert want[0, 1300] > 0.49 and want[0, 1100] > 0.49
+
+
+def test_attention_mass_redoes_a_key_block_whose_sums_overflow():
+    """Pass 1 of sv_score_visual_mass takes a row's reference from the first visual keys of a key block and never
+    raises it: a visual key whose logit lies hundreds of units above them overflows the row sums, and the kernel
+    must notice and redo the block exactly (one planted key deep inside a block, one block that starts with
+    very negative logits).  The oracle's answer: the planted keys take nearly all the mass."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9200)
+    B, Tq, Hkv, G, D, Nv, Nt = 1, 5, 2, 4, 64, 2600, 40
+    qm = np.full((B, Tq, Hkv * G, D), 4.0, np.float16)
+    qm += rng.standard_normal(qm.shape, dtype=np.float32).astype(np.float16)
+    kv = (0.1 * rng.standard_normal((B, Hkv, Nv, D), dtype=np.float32)).astype(np.float16)
+    kt = (0.1 * rng.standard_normal((B, Hkv, Nt, D), dtype=np.float32)).astype(np.float16)
+    kv[0, 0, 2300] = 20.0           # logit ~ 0.125 * 64 * 4 * 20 = 640
+    kv[0, 1, 1500] = 3.0            # logit ~ 96: above the reference by more than 2^100
+    kv[0, 1, :64] = -3.0            # a first stage of very negative logits
+    want, want_lse = oracle.score_visual_mass(qm, kv, kt)
+    dq, dkv, dkt = (torch.from_numpy(x).to("cuda:0") for x in (qm, kv, kt))
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, 1)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, Tq, Hkv * G), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, lse)
+    torch.cuda.synchronize()
+    got, got_lse = scores.cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    assert np.all(np.abs(got - want) <= 2e-4 * want + 1e-9), f"mass error {np.abs(got - want).max():.3e}"
+    assert np.abs(got_lse - want_lse).max() <= 1e-4 * np.maximum(1.0, np.abs(want_lse)).max()
+    assert want[0, 0, 2300] > 0.99 * Tq * G and want[0, 1, 1500] > 0.99 * Tq * G
