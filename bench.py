@@ -141,6 +141,51 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
     return out
 
 
+# Vector-issue bound of the two attention-mass computations: per (query, key, head) element and pass a wavefront issues a
+# matrix instruction, a multiply-add, an exponential (two slots) and an add -- five 4-cycle issue slots for 64 lanes --
+# on each of the 4 SIMDs of the 256 compute units at 2.4 GHz.
+VALU_ISSUE_PEAK_ELEMENT_PASSES = 256 * 4 * 64 / (5 * 4) * 2.4e9
+
+
+def time_encoder_salience(sv, torch, reps):
+    """Query-agnostic salience of a vision-encoder layer (paper section 3.1; figure on the salience kernels, panel a):
+    synthetic q, k ~ N(0, 1) in the shapes of the two encoder families the paper names, head dims zero-padded to 96."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(20251017)
+    out = []
+    for name, B, N, H, d_head in (("siglip_256_frames_x_729_tokens", 256, 729, 16, 72),
+                                  ("qwenvl_one_sequence_of_16384_tokens", 1, 16384, 16, 80)):
+        D = 96
+        q = torch.zeros((B, N, H, D), dtype=torch.float16, device=dev)
+        k = torch.zeros((B, H, N, D), dtype=torch.float16, device=dev)
+        q[..., :d_head] = torch.randn((B, N, H, d_head), device=dev, dtype=torch.float32, generator=g).to(torch.float16)
+        k[..., :d_head] = torch.randn((B, H, N, d_head), device=dev, dtype=torch.float32, generator=g).to(torch.float16)
+        shape = sv.make_encoder_shape(q, k, scale=float(d_head) ** -0.5)
+        sal = torch.empty((B, N), dtype=torch.float32, device=dev)
+        ws = sv.sv_salience_self(shape, q, k, sal)
+        for _ in range(2):
+            sv.sv_salience_self(shape, q, k, sal, None, ws)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        stream = torch.cuda.current_stream()
+        for a, b in evs:
+            a.record(stream)
+            sv.sv_salience_self(shape, q, k, sal, None, ws)
+            b.record(stream)
+        torch.cuda.synchronize()
+        us = float(np.median([a.elapsed_time(b) * 1e3 for a, b in evs]))
+        elements = float(B) * H * N * N
+        rate = 2.0 * elements / (us * 1e-6)          # element-passes per second (two passes)
+        out.append({"workload": name, "tokens": N, "batch": B, "heads": H, "head_dim": d_head, "padded_head_dim": D,
+                    "us": round(us, 1), "QK_TFLOPs": round(2 * 2 * elements * D / (us * 1e-6) / 1e12, 1),
+                    "Gexp_per_s": round(rate / 1e9, 1),
+                    "frac_of_vector_issue_peak": round(rate / VALU_ISSUE_PEAK_ELEMENT_PASSES, 3),
+                    "salience_sums_to_one_max_dev": float((sal.double().sum(dim=1) - 1.0).abs().max()),
+                    "workspace_MB": round(ws.numel() / 1e6, 1)})
+        del q, k, sal, ws
+    return out
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,8 +202,8 @@ def parse_args():
                     help="hand sv_decode_step a scores buffer (it then also stores all 22 MB of scores per step)")
     ap.add_argument("--variants", action="store_true",
                     help="also time, on the same inputs, the paper's retrieve-once use (pack the kept rows, then "
-                         "attention on the packed buffers), the dense baseline and a sweep of keep ratios; adds a "
-                         "\"variants\" object to the JSON line")
+                         "attention on the packed buffers), the dense baseline and a sweep of keep ratios, and the "
+                         "query-agnostic salience of two encoder-shaped layers; adds a \"variants\" object to the JSON line")
     ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
                     help="launch-shape knob for sweeps, e.g. --set attn_batches=4")
     return ap.parse_args()
@@ -320,6 +365,7 @@ def main():
 
     if args.variants:
         result["variants"] = time_variants(sv, torch, w, d, shape, buf, args.steps)
+        result["variants"]["encoder_salience"] = time_encoder_salience(sv, torch, min(args.steps, 10))
 
     if args.oracle_layers > 0:
         import oracle

@@ -161,11 +161,11 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             fetch(s0 + kStageKeys);
             const bool plain = !exact && !is_txt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
             if (plain && ref_ready) {
-                rowstat_fast_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, false, false>(stage[cur], lane, qa, c2, ref, l);
             } else if (plain && s0 == key0) {   // first stage of the block: nothing seen so far
-                rowstat_fast_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
+                rowstat_fast_stage<KB, NTL, true, false>(stage[cur], lane, qa, c2, ref, l);
                 ref_ready = true;
-            } else {
+            } else {   // text, the ragged last stage of the visual rows, an exact sweep
 #pragma unroll 1
                 for (int kt = 0; kt < kMassWaves; ++kt)
                     if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);

@@ -90,9 +90,13 @@ __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x
 // would overflow, and the kernel checks the sums for that after the block and redoes the block on the exact path.
 // So an element costs a multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no
 // branch; the matrix instructions of the next key tile go between the vector instructions of this one.
-template <int KB, int NTL, bool kInit>
+// kRagged: only the first n_live (1..63) keys of the stage are live (the last stage of a row); a lane whose key
+// column is dead takes -inf for its logits, one select more per element.
+template <int KB, int NTL, bool kInit, bool kRagged>
 __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
-                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4]) {
+                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4],
+                                                   int n_live = kStageKeys) {
+    const int row = lane & 15;
     half8_t kf[2][KB];
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, kf[0]);
@@ -117,7 +121,7 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
             for (int t = 0; t < NTL; ++t)
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const float x = sv[cur][t][rr] * c2;
+                    const float x = !kRagged || row < n_live ? sv[cur][t][rr] * c2 : -INFINITY;   // key 0 of the stage is live
                     const float r0 = row_max16(x);
                     ref[t][rr] = r0;
                     l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
@@ -134,7 +138,10 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
                     sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
                 }
             }
-            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
+            if (step < n_e) {
+                y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
+                if (kRagged) y[step] = kt * 16 + row < n_live ? y[step] : -INFINITY;
+            }
             if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
             if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
             SV_STAGE_FENCE();

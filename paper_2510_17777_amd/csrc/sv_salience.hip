@@ -129,11 +129,14 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         bool ref_ready = false;   // block-uniform: every reference is finite
         for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
             fetch(s0 + kStageKeys);
-            const bool plain = !exact && s0 + kStageKeys <= k_end;   // all 64 keys live
-            if (plain && ref_ready) {
-                rowstat_fast_stage<KB, NTL, false>(stage[cur], lane, qa, c2, ref, l);
-            } else if (plain && s0 == key0) {
-                rowstat_fast_stage<KB, NTL, true>(stage[cur], lane, qa, c2, ref, l);
+            const int n_live = k_end - s0;   // live keys of this stage, >= 1
+            if (!exact && n_live >= kStageKeys) {
+                if (ref_ready) rowstat_fast_stage<KB, NTL, false, false>(stage[cur], lane, qa, c2, ref, l);
+                else rowstat_fast_stage<KB, NTL, true, false>(stage[cur], lane, qa, c2, ref, l);   // first stage of the block
+                ref_ready = true;
+            } else if (!exact) {   // the ragged last stage of the row
+                if (ref_ready) rowstat_fast_stage<KB, NTL, false, true>(stage[cur], lane, qa, c2, ref, l, n_live);
+                else rowstat_fast_stage<KB, NTL, true, true>(stage[cur], lane, qa, c2, ref, l, n_live);
                 ref_ready = true;
             } else {
 #pragma unroll 1
