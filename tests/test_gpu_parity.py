@@ -765,3 +765,83 @@ def test_attention_mass_redoes_a_key_block_whose_sums_overflow():
     assert np.all(np.abs(got - want) <= 2e-4 * want + 1e-9), f"mass error {np.abs(got - want).max():.3e}"
     assert np.abs(got_lse - want_lse).max() <= 1e-4 * np.maximum(1.0, np.abs(want_lse)).max()
     assert want[0, 0, 2300] > 0.99 * Tq * G and want[0, 1, 1500] > 0.99 * Tq * G
+
+
+# ------------------------------------------------------------------ the two attention-mass computations at the sizes bench.py times
+def test_attention_mass_at_the_benchmark_size_on_sampled_units():
+    """sv_score_visual_mass in the launch configuration bench.py --variants times (28 layers folded, 28q / 4kv heads,
+    D = 128, 50176 visual + 1024 text keys, a 32-token question): three sampled (layer, kv head) units in full
+    against the oracle, which computes a unit by itself (the units are independent)."""
+    import paper_2510_17777_amd as sv
+    B, Tq, Hq, Hkv, D, Nv, Nt = 28, 32, 28, 4, 128, 50176, 1024
+    G = Hq // Hkv
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(4242)
+    rn = lambda *s: torch.randn(s, device="cuda:0", dtype=torch.float32, generator=g).to(torch.float16)
+    dq, dkv, dkt = rn(B, Tq, Hq, D), rn(B, Hkv, Nv, D), rn(B, Hkv, Nt, D)
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, 1)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, Tq, Hq), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(scores).all()) and bool(torch.isfinite(lse).all())
+    for b, kvh in ((0, 0), (13, 2), (27, 3)):
+        hs = slice(kvh * G, (kvh + 1) * G)
+        want, want_lse = oracle.score_visual_mass(dq[b:b + 1, :, hs].cpu().numpy(), dkv[b:b + 1, kvh:kvh + 1].cpu().numpy(),
+                                                  dkt[b:b + 1, kvh:kvh + 1].cpu().numpy())
+        got = scores[b, kvh].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want[0, 0]) <= 2e-4 * want[0, 0] + 1e-9), (b, kvh, np.abs(got - want[0, 0]).max())
+        assert np.abs(lse[b, :, hs].cpu().numpy() - want_lse[0]).max() <= 1e-4, (b, kvh)
+
+
+def test_salience_self_at_the_benchmark_sizes():
+    """sv_salience_self in the two launch configurations bench.py --variants times (16 heads, head dims 72 / 80
+    zero-padded to 96).  256 frames x 729 tokens: three sampled frames in full against the oracle (frames are
+    independent).  One sequence of 16384 tokens: the salience sums to 1, is positive everywhere, and the lse of
+    sampled (token, head) rows equals scipy's logsumexp of the row's logits in float64."""
+    import paper_2510_17777_amd as sv
+    from scipy.special import logsumexp
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(4343)
+    def padded(shape, d_live):
+        t = torch.zeros(shape, dtype=torch.float16, device="cuda:0")
+        t[..., :d_live] = torch.randn(shape[:-1] + (d_live,), device="cuda:0", dtype=torch.float32, generator=g).to(torch.float16)
+        return t
+    # frames
+    B, N, H, D, d_live = 256, 729, 16, 96, 72
+    dq, dk = padded((B, N, H, D), d_live), padded((B, H, N, D), d_live)
+    scale = d_live ** -0.5
+    shape = sv.make_encoder_shape(dq, dk, scale=scale)
+    sal = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, N, H), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_salience_self(shape, dq, dk, sal, lse)
+    torch.cuda.synchronize()
+    for b in (0, 100, 255):
+        want, want_lse = oracle.salience_self(dq[b:b + 1].cpu().numpy(), dk[b:b + 1].cpu().numpy(), scale=scale)
+        got = sal[b].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want[0]) <= 2e-4 * want[0] + 1e-12), (b, np.abs(got - want[0]).max())
+        assert np.abs(lse[b].cpu().numpy() - want_lse[0]).max() <= 1e-4, b
+    assert float((sal.double().sum(dim=1) - 1.0).abs().max()) <= 1e-4
+    del dq, dk, sal, lse
+    # one long sequence
+    B, N, H, D, d_live = 1, 16384, 16, 96, 80
+    dq, dk = padded((B, N, H, D), d_live), padded((B, H, N, D), d_live)
+    scale = d_live ** -0.5
+    shape = sv.make_encoder_shape(dq, dk, scale=scale)
+    sal = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, N, H), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_salience_self(shape, dq, dk, sal, lse)
+    torch.cuda.synchronize()
+    assert abs(float(sal.double().sum()) - 1.0) <= 1e-4 and bool((sal > 0).all())
+    rng = np.random.default_rng(4344)
+    k_host = dk[0].cpu().numpy().astype(np.float64)                     # [H, N, D]
+    for i, h in zip(rng.integers(0, N, 48), rng.integers(0, H, 48)):
+        row = scale * k_host[h] @ dq[0, i, h].cpu().numpy().astype(np.float64)
+        assert abs(float(lse[0, i, h]) - logsumexp(row)) <= 1e-4, (i, h)
+    # the mean probability of a sampled key over all query tokens and heads, from the kernel's own (sample-checked) lse
+    lse_all = lse[0].double()                                            # [N, H]
+    qd, kd = dq[0].double(), dk[0].double()
+    for j in (0, 5000, 16383):
+        logits = scale * torch.einsum("ihd,hd->ih", qd, kd[:, j])       # [N, H]
+        want_j = float(torch.exp(logits - lse_all).mean())
+        assert abs(float(sal[0, j]) - want_j) <= 2e-4 * want_j, j
