@@ -845,3 +845,77 @@ def test_salience_self_at_the_benchmark_sizes():
         logits = scale * torch.einsum("ihd,hd->ih", qd, kd[:, j])       # [N, H]
         want_j = float(torch.exp(logits - lse_all).mean())
         assert abs(float(sal[0, j]) - want_j) <= 2e-4 * want_j, j
+
+
+# ------------------------------------------------------------------ a multi-turn conversation on one set of buffers
+def test_multi_turn_rounds_with_text_eviction_on_resident_buffers():
+    """The paper's multi-turn use (section 3.2 and the evaluation protocol of section 4.1): the visual cache stays
+    resident across rounds; each round appends its question to the text segment, retrieves once with the whole
+    question (attention mass -> top-k -> pack), decodes a few tokens -- every one appended to the text segment before
+    its step -- and is then evicted by resetting txt_len on the device (no reallocation; the shapes of the decode
+    steps are built once, only the retrieval's shape is rebuilt because its query strides describe the question).  Every
+    retrieval and every decoded token is checked against the oracle run on fresh host arrays that hold exactly what
+    is live; evicted rows are overwritten with a sentinel to show they are never read again."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9300)
+    B, Hq, Hkv, D, Nv, cap, k = 2, 8, 2, 128, 3000, 96, 300
+    prompt, q_lens, n_decode = 10, (7, 12, 5), 4
+    G = Hq // Hkv
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    k_vis, v_vis = f(B, Hkv, Nv, D), f(B, Hkv, Nv, D)
+    vis_len = np.array([Nv, 2500], np.int32)
+    k_txt, v_txt = np.full((B, Hkv, cap, D), 1e4, np.float16), np.full((B, Hkv, cap, D), 1e4, np.float16)
+    k_txt[:, :, :prompt], v_txt[:, :, :prompt] = f(B, Hkv, prompt, D), f(B, Hkv, prompt, D)
+    dev = "cuda:0"
+    dkv, dvv, dkt, dvt = (torch.from_numpy(x).to(dev) for x in (k_vis, v_vis, k_txt, v_txt))
+    d_txt_len = torch.full((B,), prompt, dtype=torch.int32, device=dev)
+    # one shape for the whole conversation: the device length array is updated in place
+    q0 = torch.zeros((B, Hq, D), dtype=torch.float16, device=dev)
+    shape = sv.make_shape(q0, dkv, dkt, k, vis_len=vis_len, txt_len=d_txt_len)
+    assert shape.txt_len.data_ptr() == d_txt_len.data_ptr()
+    buf = sv.DecodeBuffers(shape, dev)
+    k_pack = torch.empty((B, Hkv, k, D), dtype=torch.float16, device=dev)
+    v_pack = torch.empty_like(k_pack)
+    pshape = sv.make_shape(q0, k_pack, dkt, k, txt_len=d_txt_len)
+    pbuf = sv.DecodeBuffers(pshape, dev, with_scores=False)
+    masses = torch.empty((B, Hkv, Nv), dtype=torch.float32, device=dev)
+    for rnd, Tq in enumerate(q_lens):
+        n = prompt                                              # live text rows; the previous round is gone
+        kq, vq, qm = f(B, Hkv, Tq, D), f(B, Hkv, Tq, D), f(B, Tq, Hq, D)
+        k_txt[:, :, n:n + Tq], v_txt[:, :, n:n + Tq] = kq, vq
+        dkt[:, :, n:n + Tq], dvt[:, :, n:n + Tq] = torch.from_numpy(kq).to(dev), torch.from_numpy(vq).to(dev)
+        n += Tq
+        d_txt_len.fill_(n)
+        dqm = torch.from_numpy(qm).to(dev)
+        mshape = sv.make_shape(dqm[:, 0], dkv, dkt, k, vis_len=vis_len, txt_len=d_txt_len)   # strides of this question
+        sv.sv_score_visual_mass(mshape, dqm, dkv, dkt, masses)   # its workspace depends on the question's length
+        sv.sv_topk_select(shape, masses, buf.idx, buf.count, buf.workspace)
+        sv.sv_pack_selected(shape, dkv, dvv, buf.idx, buf.count, k_pack, v_pack)
+        torch.cuda.synchronize()
+        got_mass = masses.cpu().numpy().astype(np.float64)
+        idx, cnt = buf.idx.cpu().numpy(), buf.count.cpu().numpy()
+        want_mass, _ = oracle.score_visual_mass(qm, k_vis, np.ascontiguousarray(k_txt[:, :, :n]), vis_len=vis_len)
+        live = np.isfinite(want_mass)
+        assert np.array_equal(np.isneginf(got_mass), ~live)
+        err = np.abs(np.where(live, got_mass, 0.0) - np.where(live, want_mass, 0.0))
+        assert np.all(err <= 2e-4 * np.where(live, want_mass, 0.0) + 1e-9), rnd
+        want_idx, want_cnt = oracle.topk_select(got_mass, k, vis_len)
+        assert np.array_equal(cnt, want_cnt) and np.array_equal(idx, want_idx), rnd
+        assert check_index_sets(want_mass, k, vis_len, idx, cnt).ok, rnd
+        for t in range(n_decode):
+            kn, vn, q = f(B, Hkv, 1, D), f(B, Hkv, 1, D), f(B, Hq, D)     # the new token's own K/V go in first
+            k_txt[:, :, n:n + 1], v_txt[:, :, n:n + 1] = kn, vn
+            dkt[:, :, n:n + 1], dvt[:, :, n:n + 1] = torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev)
+            n += 1
+            d_txt_len.add_(1)
+            dq = torch.from_numpy(q).to(dev)
+            sv.sv_sparse_decode_attn(pshape, dq, k_pack, v_pack, dkt, dvt, None, buf.count, pbuf.out, pbuf.lse, pbuf.workspace)
+            torch.cuda.synchronize()
+            want_out, want_lse, _ = oracle.sparse_decode_attn(q, k_vis, v_vis, np.ascontiguousarray(k_txt[:, :, :n]),
+                                                              np.ascontiguousarray(v_txt[:, :, :n]), idx, cnt)
+            assert np.abs(pbuf.out.cpu().numpy() - want_out).max() <= 2e-3, (rnd, t)
+            assert np.abs(pbuf.lse.cpu().numpy() - want_lse).max() <= 2e-3, (rnd, t)
+        # eviction: the round's question and answer leave the cache; their rows are poisoned to prove it
+        d_txt_len.fill_(prompt)
+        k_txt[:, :, prompt:], v_txt[:, :, prompt:] = 1e4, 1e4
+        dkt[:, :, prompt:], dvt[:, :, prompt:] = 1e4, 1e4
