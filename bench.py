@@ -84,8 +84,9 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
         g.manual_seed(20251017)
         qm = torch.randn((B, Tq, shape.n_q_heads, D), device=dev, dtype=torch.float32, generator=g).to(torch.float16)
         mscores = torch.empty((B, Hkv, shape.n_vis_max), dtype=torch.float32, device=dev)
-        mws = sv.sv_score_visual_mass(shape, qm, d["k_vis"], d["k_txt"], mscores)
-        out["retrieval_mass_32tok_us"] = timed(lambda: sv.sv_score_visual_mass(shape, qm, d["k_vis"], d["k_txt"],
+        mshape = sv.make_shape(qm[:, 0], d["k_vis"], d["k_txt"], k, vis_len=shape.vis_len, txt_len=shape.txt_len)
+        mws = sv.sv_score_visual_mass(mshape, qm, d["k_vis"], d["k_txt"], mscores)
+        out["retrieval_mass_32tok_us"] = timed(lambda: sv.sv_score_visual_mass(mshape, qm, d["k_vis"], d["k_txt"],
                                                                                mscores, None, mws))
         rows = Tq * (shape.n_q_heads // Hkv)
         keys = int(shape.n_vis_max if shape.vis_len is None else shape.vis_len.sum().item() / B)

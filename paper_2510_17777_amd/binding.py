@@ -222,6 +222,8 @@ def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, cou
 def sv_score_visual_mass(shape: Shape, q_multi, k_vis, k_txt, scores, lse=None, workspace=None, stream=None):
     """q_multi [B, Tq, Hq, D] (any strides with D contiguous); shape built from q_multi[:, 0]."""
     Tq = q_multi.shape[1]
+    if (shape.c.q_stride_b, shape.c.q_stride_h) != (q_multi.stride(0), q_multi.stride(2)):
+        raise ValueError("the shape's query strides do not describe q_multi: build it from q_multi[:, 0]")
     if workspace is None:
         nbytes = int(load_library().sv_mass_workspace_bytes(ctypes.byref(shape.c), Tq))
         workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q_multi.device)
@@ -253,6 +255,9 @@ def make_encoder_shape(q_all: torch.Tensor, k_all: torch.Tensor, vis_len=None, s
 
 def sv_salience_self(shape: Shape, q_all, k_all, salience, lse=None, workspace=None, stream=None):
     """shape from make_encoder_shape; salience [B, N] fp32; returns the workspace it used."""
+    if (shape.c.q_stride_b, shape.c.q_stride_h) != (q_all.stride(0), q_all.stride(2)) or \
+            (shape.c.kv_vis_stride_b, shape.c.kv_vis_stride_h, shape.c.kv_vis_stride_n) != k_all.stride()[:3]:
+        raise ValueError("the shape's strides do not describe q_all / k_all: build it with make_encoder_shape")
     if workspace is None:
         nbytes = int(load_library().sv_salience_workspace_bytes(ctypes.byref(shape.c)))
         workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q_all.device)
