@@ -109,8 +109,9 @@ struct MassArgs {
     int64_t q_sb, q_st, q_sh;
     int64_t vis_sb, vis_sh, vis_sn;
     int64_t txt_sb, txt_sh, txt_sn;
-    // set by the launcher: keys per workgroup in pass 1, its text blocks and all its blocks
-    int32_t stat_block_keys, n_txt_blocks, n_stat_blocks;
+    // set by the launcher: visual / text keys per workgroup in pass 1 (pass 2 uses the visual length), the text blocks
+    // of a row and all its blocks
+    int32_t stat_block_keys, txt_block_keys, n_txt_blocks, n_stat_blocks;
 };
 hipError_t launch_mass(const MassArgs& a, hipStream_t stream);
 size_t mass_workspace_bytes(int B, int Hkv, int n_txt_max, int n_vis_max);

@@ -39,7 +39,8 @@
 namespace sv {
 namespace {
 
-constexpr int kMinBlockKeys = 1024;               // a workgroup streams at least this many keys (if the row has them)
+constexpr int kMinBlockKeys = 1024;               // a workgroup streams at least this many visual keys (if the row has them)
+constexpr int kTextBlockKeys = 256;               // text rows per workgroup: few rows, all on the slow masked path
 
 // The A operands of this wavefront: a row tile holds rows 16*tile + (lane & 15); lane (row, quad) supplies
 // dims 8*quad + 32*kb .. +8.  Row r is query token r / G, head g*G + r % G; rows >= R are zero.
@@ -66,22 +67,24 @@ __device__ __forceinline__ void load_query_tiles(const MassArgs& a, int b, int g
 // ---- pass 1: per key block, (reference, sum exp) of every query row over the block's keys ----
 // Key list of a (b, g): text rows [0, nt), then visual rows [0, nv).  Query token i sits at text row
 // nt - Tq + i and sees the text rows up to itself.
-template <int D>
-// Two wavefronts per SIMD: the query tiles, the two statistics of 16 rows and two key tiles in flight need more
-// than the 168 registers that three would leave.
-__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mass_rowstat_kernel(const MassArgs a) {
+// kText: this workgroup streams text rows (blocks of txt_block_keys rows, the causal mask, every tile on the masked
+// path); otherwise visual rows (blocks of stat_block_keys rows).  Two bodies, chosen per workgroup by the kernel below,
+// rather than one body with a block-uniform flag: each then fits the 168 registers of three wavefronts per SIMD.
+template <int D, bool kText>
+__device__ __forceinline__ void rowstat_body(const MassArgs& a, const int blk, KeyStage<D / 32> (&stage)[2],
+                                             int (&s_last_txt)[kMaxRowTiles * 16], int& s_flag) {
     constexpr int KB = D / 32;
-    __shared__ KeyStage<KB> stage[2];
-    __shared__ __align__(16) int s_last_txt[kMaxRowTiles * 16];
-    const int blk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int g = blockIdx.y, b = blockIdx.z;
+    // the wavefront's index in a scalar register, the lane from the lane counter: nothing here keeps the thread-index
+    // register alive, and what depends on the wavefront alone costs no vector register
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
     const int row = lane & 15, quad = lane >> 4;
     const int rot = blk & (kMassWaves - 1);
     const int nt = live_len(a.txt_len, b, a.n_txt_max), nv = live_len(a.vis_len, b, a.n_vis_max);
-    // The first n_txt_blocks key blocks cover the text rows, the others the visual rows: a workgroup streams one kind
-    // of key only, with one base address and one stride.
-    const bool is_txt = blk < a.n_txt_blocks;                                    // block-uniform
-    const int key0 = (is_txt ? blk : blk - a.n_txt_blocks) * a.stat_block_keys;   // within the text or the visual rows
+    constexpr bool is_txt = kText;
+    const int block_keys = is_txt ? a.txt_block_keys : a.stat_block_keys;
+    const int key0 = blk * block_keys;   // within the text or the visual rows
     const int n_keys = is_txt ? nt : nv;
     const int R = a.Tq * a.G;
     const int ntl = live_tiles_of(wave, rot, R);   // wave-uniform
@@ -90,7 +93,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     // last text row that query row r sees: its token i = r / G sits at text row nt - Tq + i (one division per
     // row here instead of one per logit in the masked tiles); read after the first barrier below
     static_assert(kMassThreads == kMaxRowTiles * 16, "one thread per query row");
-    s_last_txt[threadIdx.x] = nt - a.Tq + ((int)threadIdx.x < R ? (int)threadIdx.x / a.G : 0);
+    if (is_txt) s_last_txt[threadIdx.x] = nt - a.Tq + ((int)threadIdx.x < R ? (int)threadIdx.x / a.G : 0);
 
     half8_t qa[kTilesPerWave][KB];
     load_query_tiles<KB>(a, b, g, wave, rot, lane, qa);
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
                                   : static_cast<const _Float16*>(a.k_vis) + (int64_t)b * a.vis_sb + (int64_t)g * a.vis_sh;
     const int64_t key_sn = is_txt ? a.txt_sn : a.vis_sn;
 
-    const int k_end = min(key0 + a.stat_block_keys, n_keys);
+    const int k_end = min(key0 + block_keys, n_keys);
     half8_t kfetch[KB];
     auto fetch = [&](int s0) {   // this wavefront's key tile of the stage at s0; rows clamped, dead columns masked at use
         load_key_tile<KB>(keys, key_sn, min(s0 + wave * 16 + row, n_keys - 1), quad, kfetch);
@@ -109,6 +112,13 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
     auto put = [&](KeyStage<KB>& st) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
+    };
+    // The same fetch for the slow loop, from lane coordinates computed on the spot: sharing them with the fast loop
+    // keeps one more value alive across it than its register budget holds.
+    auto fetch_again = [&](int s0) {
+        int ln = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(ln));
+        load_key_tile<KB>(keys, key_sn, min(s0 + wave * 16 + (ln & 15), n_keys - 1), ln >> 4, kfetch);
     };
     // text tiles, ragged tiles, visual tiles met before every reference is set, and every tile of an exact sweep:
     // masked, exact running maximum
@@ -121,12 +131,12 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             float4_t sv = {0.f, 0.f, 0.f, 0.f};     // rows past R are zero rows: computed, never stored
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) sv = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], sv, 0, 0, 0);
-            const int4 last4 = *reinterpret_cast<const int4*>(&s_last_txt[row_tile_of(wave, rot, t) * 16 + 4 * quad]);
+            int4 last4 = {0, 0, 0, 0};
+            if (is_txt) last4 = *reinterpret_cast<const int4*>(&s_last_txt[row_tile_of(wave, rot, t) * 16 + 4 * quad]);
             const int last_of[4] = {last4.x, last4.y, last4.z, last4.w};
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int last_txt = last_of[rr];
-                const bool seen = key < n_keys && (!is_txt || key <= last_txt);
+                const bool seen = key < n_keys && (!is_txt || key <= last_of[rr]);
                 const float x = seen ? sv[rr] * c2 : -INFINITY;
                 const float mn = fmaxf(ref[t][rr], x);
                 if (mn > -INFINITY) {   // something seen so far
@@ -136,14 +146,20 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             }
         }
     };
-    // One sweep over the key block.  exact = false: full visual stages on the fast path once every reference is
-    // set; exact = true: every tile with the exact running maximum (taken only after a sweep whose sums left the
-    // trusted range).  Instantiated once per count of live row tiles and chosen outside the loop (a switch inside it
-    // makes the compiler shuffle the state registers between the arms at every stage).  No branch around the fetch
-    // and the store of the next stage: past the end they are harmless (clamped rows, a buffer nobody reads), and
-    // conditional blocks in the body keep the scheduler from placing the matrix and vector instructions together.
-    auto run = [&](auto ntl_c, bool exact) __attribute__((always_inline)) {
-        constexpr int NTL = decltype(ntl_c)::value;
+    // One sweep over the key block.  On the fast path the full stages run in a loop of their own -- references from
+    // the first 16 keys, then multiply-add, exponential, add per element -- and the ragged last stage follows on the
+    // masked path; the exact sweep (text blocks; blocks whose fast sums left the trusted range) takes the masked path
+    // for every tile.  The loops are separate and instantiated once per count of live row tiles, chosen outside them:
+    // a stage loop that can take either path, or a switch inside it, costs the registers that decide between two and
+    // three wavefronts per SIMD.  No branch around the fetch and the store of the next stage: past the end they are
+    // harmless (clamped rows, a buffer nobody reads), and conditional blocks in the body keep the scheduler from
+    // placing the matrix and vector instructions of a stage together.
+    auto masked_stage = [&](int s0, const KeyStage<KB>& st) {
+#pragma unroll 1
+        for (int kt = 0; kt < kMassWaves; ++kt)
+            if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, st, kt);
+    };
+    auto start = [&]() {   // statistics cleared, the first stage in LDS
 #pragma unroll
         for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
@@ -155,47 +171,68 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         wait_for_loads();
         put(stage[0]);
         __syncthreads();
+    };
+    auto run_exact = [&]() {   // one instance: the masked tiles do not depend on the count of live row tiles
+        start();
         int cur = 0;
-        bool ref_ready = false;   // block-uniform: every reference is finite
         for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
-            fetch(s0 + kStageKeys);
-            const bool plain = !exact && !is_txt && s0 + kStageKeys <= k_end;   // visual keys, all live, seen by every row
-            if (plain && ref_ready) {
-                rowstat_fast_stage<KB, NTL, false, false>(stage[cur], lane, qa, c2, ref, l);
-            } else if (plain && s0 == key0) {   // first stage of the block: nothing seen so far
-                rowstat_fast_stage<KB, NTL, true, false>(stage[cur], lane, qa, c2, ref, l);
-                ref_ready = true;
-            } else {   // text, the ragged last stage of the visual rows, an exact sweep
-#pragma unroll 1
-                for (int kt = 0; kt < kMassWaves; ++kt)
-                    if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);
-                if (plain) ref_ready = true;   // every row saw these 64 keys
-            }
-            put(stage[cur ^ 1]);
-            __syncthreads();
+            masked_stage(s0, stage[cur]);
+            fetch_again(s0 + kStageKeys);   // after the stage, not a stage ahead: this slow path (text rows, the rare redo of a
+            put(stage[cur ^ 1]);      // visual block) gives the registers of the key tile in flight back -- their spills
+            __syncthreads();          // would make the kernel use scratch
             cur ^= 1;
         }
     };
-    auto sweep = [&](bool exact) __attribute__((always_inline)) {
+    auto run_fast = [&](auto ntl_c) __attribute__((always_inline)) {
+        constexpr int NTL = decltype(ntl_c)::value;
+        start();
+        int cur = 0, s0 = key0;
+        if (s0 + kStageKeys <= k_end) {
+            const float ref_w = rowstat_init_ref<KB, NTL>(stage[0], lane, wave, rot, R, qa, c2);   // wave-uniform
+            for (; s0 + kStageKeys <= k_end; s0 += kStageKeys) {
+                fetch(s0 + kStageKeys);
+                rowstat_fast_stage<KB, NTL>(stage[cur], lane, qa, c2, ref_w, l);
+                put(stage[cur ^ 1]);
+                __syncthreads();
+                cur ^= 1;
+            }
+#pragma unroll
+            for (int t = 0; t < NTL; ++t)   // from here on every row carries its own reference
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) ref[t][rr] = ref_w;
+        }
+        if (s0 < k_end) masked_stage(s0, stage[cur]);   // the ragged last stage: already stored by the loop above
+    };
+    auto sweep_fast = [&]() __attribute__((always_inline)) {
         switch (ntl) {   // wave-uniform
-            case 4: run(std::integral_constant<int, 4>{}, exact); break;
-            case 3: run(std::integral_constant<int, 3>{}, exact); break;
-            case 2: run(std::integral_constant<int, 2>{}, exact); break;
-            case 1: run(std::integral_constant<int, 1>{}, exact); break;
-            default: run(std::integral_constant<int, 0>{}, exact); break;
+            case 4: run_fast(std::integral_constant<int, 4>{}); break;
+            case 3: run_fast(std::integral_constant<int, 3>{}); break;
+            case 2: run_fast(std::integral_constant<int, 2>{}); break;
+            case 1: run_fast(std::integral_constant<int, 1>{}); break;
+            default: run_fast(std::integral_constant<int, 0>{}); break;
         }
     };
-    sweep(false);
-    // did a sum leave the range in which it is trusted (inf, NaN, or huge: a logit far above its row's reference)?
+    if (is_txt) run_exact();   // text rows: the causal mask, every tile on the masked path
+    else sweep_fast();
+    // What follows takes its lane coordinates from the lane counter: values computed before the sweep -- the thread
+    // index register itself included -- would otherwise be kept alive across its loops, in registers that the
+    // three-wavefront budget does not have.
+    const int lane_m = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int quad_m = lane_m >> 4, row_m = lane_m & 15;
+    // did the sum of a live row leave the range in which it is trusted (inf, NaN, huge or tiny: logits far from the
+    // wavefront's reference)?
     bool bad = false;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < kSumLimit);
-    if (__syncthreads_or(bad)) sweep(true);   // block-uniform
+        for (int rr = 0; rr < 4; ++rr) {
+            const bool live_row = t < ntl && row_tile_of(wave, rot, t) * 16 + 4 * quad_m + rr < R;
+            bad |= live_row && !(l[t][rr] < kSumLimit && l[t][rr] >= 1.f / kSumLimit);
+        }
+    if (!is_txt && block_any(bad, &s_flag)) run_exact();   // block-uniform
     // merge the 16 key columns of a row (the lanes of a 16-lane row hold the same rows), store per block
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    float* part = a.part + ((unit * a.n_stat_blocks + blk) * (int64_t)(kMaxRowTiles * 16)) * 2;
+    float* part = a.part + ((unit * a.n_stat_blocks + (is_txt ? blk : a.n_txt_blocks + blk)) * (int64_t)(kMaxRowTiles * 16)) * 2;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
         const int tile = row_tile_of(wave, rot, t);
@@ -206,13 +243,24 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
             const float mx = row_max16(mine);
             const float e = mine > -INFINITY ? __builtin_amdgcn_exp2f(mine - mx) : 0.f;
             const float lt = group_sum<16>(lmine * e);
-            if (row == 0) {
-                const int r = tile * 16 + 4 * quad + rr;
+            if (row_m == 0) {
+                const int r = tile * 16 + 4 * quad_m + rr;
                 part[r * 2] = mx * kLn2;   // natural-log units from here on
                 part[r * 2 + 1] = lt;
             }
         }
     }
+}
+
+template <int D>
+__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void mass_rowstat_kernel(const MassArgs a) {
+    __shared__ KeyStage<D / 32> stage[2];
+    __shared__ __align__(16) int s_last_txt[kMaxRowTiles * 16];
+    __shared__ int s_flag;   // zero whenever block_any is entered
+    if (threadIdx.x == 0) s_flag = 0;   // the sweeps below start with a barrier
+    // the text blocks come first in the grid: they are few and slow (masked path) and run beside the visual ones
+    if ((int)blockIdx.x < a.n_txt_blocks) rowstat_body<D, true>(a, blockIdx.x, stage, s_last_txt, s_flag);
+    else rowstat_body<D, false>(a, (int)blockIdx.x - a.n_txt_blocks, stage, s_last_txt, s_flag);
 }
 
 // lse[b, i, h] = log sum over the live key blocks (text blocks first, then visual ones); one thread per query row.
@@ -225,7 +273,7 @@ __global__ __launch_bounds__(256) void mass_lse_kernel(const MassArgs a) {
     const int nt = live_len(a.txt_len, b, a.n_txt_max), nv = live_len(a.vis_len, b, a.n_vis_max);
     const float* part = a.part + (unit * a.n_stat_blocks * (int64_t)(kMaxRowTiles * 16)) * 2;
     auto live = [&](int s) {   // did pass 1 run this block?
-        return s < a.n_txt_blocks ? s * a.stat_block_keys < nt : (s - a.n_txt_blocks) * a.stat_block_keys < nv;
+        return s < a.n_txt_blocks ? s * a.txt_block_keys < nt : (s - a.n_txt_blocks) * a.stat_block_keys < nv;
     };
     float mx = -INFINITY;
     for (int s = 0; s < a.n_stat_blocks; ++s)
@@ -380,13 +428,14 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(3,
 }  // namespace
 
 namespace {
-struct MassPlan { int stat_block_keys, n_txt_blocks, n_stat_blocks, n_col_blocks; };
+struct MassPlan { int stat_block_keys, txt_block_keys, n_txt_blocks, n_stat_blocks, n_col_blocks; };
 MassPlan mass_plan(int B, int Hkv, int n_txt_max, int n_vis_max) {
     MassPlan p{};
     const int64_t units = (int64_t)B * Hkv;
     // one block length for both passes, planned on the visual rows (the text rows are few)
     p.stat_block_keys = planned_block_len(units, n_vis_max, kMinBlockKeys);
-    p.n_txt_blocks = (n_txt_max + p.stat_block_keys - 1) / p.stat_block_keys;
+    p.txt_block_keys = kTextBlockKeys;
+    p.n_txt_blocks = (n_txt_max + p.txt_block_keys - 1) / p.txt_block_keys;
     p.n_col_blocks = (n_vis_max + p.stat_block_keys - 1) / p.stat_block_keys;
     p.n_stat_blocks = p.n_txt_blocks + p.n_col_blocks;
     return p;
@@ -404,7 +453,8 @@ hipError_t launch_mass(const MassArgs& a, hipStream_t stream) {
     if (a.Tq * a.G > kMaxRowTiles * 16 || a.Tq < 1) return hipErrorInvalidValue;
     const MassPlan p = mass_plan(a.B, a.Hkv, a.n_txt_max, a.n_vis_max);
     MassArgs k = a;
-    k.stat_block_keys = p.stat_block_keys; k.n_txt_blocks = p.n_txt_blocks; k.n_stat_blocks = p.n_stat_blocks;
+    k.stat_block_keys = p.stat_block_keys; k.txt_block_keys = p.txt_block_keys; k.n_txt_blocks = p.n_txt_blocks;
+    k.n_stat_blocks = p.n_stat_blocks;
     const dim3 block(kMassThreads);
     const dim3 grid1((unsigned)p.n_stat_blocks, (unsigned)a.Hkv, (unsigned)a.B);
     const dim3 grid2((unsigned)((a.Tq * a.G + 255) / 256), (unsigned)a.Hkv, (unsigned)a.B);

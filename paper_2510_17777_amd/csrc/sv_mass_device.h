@@ -18,7 +18,7 @@ constexpr int kTilesPerWave = kMaxRowTiles / kMassWaves;
 constexpr int kStageKeys = 16 * kMassWaves;       // keys per LDS stage: one key tile per wavefront
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kSumLimit = 0x1p100f;             // pass 1: a sum at or above this (or NaN) sends its key block to the exact path
+constexpr float kSumLimit = 0x1p100f;             // pass 1: a row sum outside [1 / this, this) (or NaN) sends its key block to the exact path
 constexpr int kTargetGroups = 3072;               // the streamed side is cut into blocks until this many workgroups exist
 
 __device__ __forceinline__ int live_len(const int32_t* p, int i, int cap) {
@@ -84,19 +84,37 @@ __device__ __forceinline__ float row_max16(float x) {
 // for them there would also wait for the keys fetched one stage ahead.
 __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
-// Pass 1.  A stage of 64 live keys on the fast path.  The reference of a row is the largest of its first 16 logits of
-// the key block (kInit, shared by the row's 16 lanes) and is never raised: a later logit far above it makes a
-// large term, which fp32 sums as accurately as a small one; only a logit more than ~2^7 above it (in base 2)
-// would overflow, and the kernel checks the sums for that after the block and redoes the block on the exact path.
-// So an element costs a multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no
-// branch; the matrix instructions of the next key tile go between the vector instructions of this one.
-// kRagged: only the first n_live (1..63) keys of the stage are live (the last stage of a row); a lane whose key
-// column is dead takes -inf for its logits, one select more per element.
-template <int KB, int NTL, bool kInit, bool kRagged>
+// Pass 1 on the fast path.  One reference per wavefront -- the largest logit of its live rows against the first 16
+// keys of the key block (rowstat_init_ref), a scalar register -- that is never raised: a logit far above it makes a
+// large term and a row far below it small ones, which fp32 sums as accurately as terms near 1; only a distance of
+// more than ~2^100 would overflow or underflow, and the kernel checks every row sum for that after the block and
+// redoes the block on the exact path (a reference per row with a running maximum).  So an element costs a
+// multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no branch, and the loop holds
+// no reference registers: with 16 of them per lane, or with the references set by a variant of the stage code inside
+// the loop, or with a second variant of the stage for the ragged last stage of a row, the kernel needed more than
+// the 168 registers that three wavefronts per SIMD leave.
+// rows_live: rows of this workgroup below it exist (the others are zero rows and must not set the reference).
+template <int KB, int NTL>
+__device__ __forceinline__ float rowstat_init_ref(const KeyStage<KB>& st, int lane, int wave, int rot, int rows_live,
+                                                  const half8_t (&qa)[kTilesPerWave][KB], float c2) {
+    const int quad = lane >> 4;
+    half8_t kf[KB];
+    float4_t sv[kTilesPerWave];
+    read_key_tile<KB>(st, 0, lane, kf);
+    tile_logits<KB, NTL>(qa, kf, sv);
+    float m = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < NTL; ++t)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            if (row_tile_of(wave, rot, t) * 16 + 4 * quad + rr < rows_live) m = fmaxf(m, sv[t][rr] * c2);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, wave_max(m))));
+}
+
+// A stage of 64 live keys: the matrix instructions of the next key tile go between the vector instructions of this one.
+template <int KB, int NTL>
 __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
-                                                   float c2, float (&ref)[kTilesPerWave][4], float (&l)[kTilesPerWave][4],
-                                                   int n_live = kStageKeys) {
-    const int row = lane & 15;
+                                                   float c2, float ref, float (&l)[kTilesPerWave][4]) {
     half8_t kf[2][KB];
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, kf[0]);
@@ -113,21 +131,6 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
 #pragma unroll
             for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
         }
-        if (kInit && kt == 0) {   // once per key block: the references; the next tile's matrix instructions run meanwhile
-#pragma unroll
-            for (int m = 0; m < n_m; ++m)
-                sv[nxt][m % NT1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[m % NT1][m / NT1], kf[nxt][m / NT1], sv[nxt][m % NT1], 0, 0, 0);
-#pragma unroll
-            for (int t = 0; t < NTL; ++t)
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) {
-                    const float x = !kRagged || row < n_live ? sv[cur][t][rr] * c2 : -INFINITY;   // key 0 of the stage is live
-                    const float r0 = row_max16(x);
-                    ref[t][rr] = r0;
-                    l[t][rr] = __builtin_amdgcn_exp2f(x - r0);
-                }
-            continue;
-        }
         float y[n_e1], pr[n_e1];
 #pragma unroll
         for (int step = 0; step < n_e + 2; ++step) {
@@ -138,15 +141,24 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
                     sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
                 }
             }
-            if (step < n_e) {
-                y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref[step / 4][step % 4]);
-                if (kRagged) y[step] = kt * 16 + row < n_live ? y[step] : -INFINITY;
-            }
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref);
             if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
             if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
             SV_STAGE_FENCE();
         }
     }
+}
+
+// Block-wide OR of a per-thread flag through one LDS word that is zero on entry (every thread of the workgroup
+// calls it; the word is left zero again).  The library's __syncthreads_or keeps the thread-index register alive
+// across everything before it, a register that pass 1 does not have to spare.
+__device__ __forceinline__ bool block_any(bool mine, int* s_word) {
+    if (__ballot(mine) != 0ull) *s_word = 1;   // wave-uniform branch; every lane stores the same value
+    __syncthreads();
+    const bool any = *s_word != 0;
+    __syncthreads();
+    *s_word = 0;
+    return any;
 }
 
 // Length of the blocks the streamed side (n rows) is cut into when `units` workgroup rows stream it: cut only as far

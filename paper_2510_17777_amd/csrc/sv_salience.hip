@@ -57,10 +57,15 @@ __device__ __forceinline__ void load_held_tiles(const _Float16* base, int64_t st
 }
 
 // ---- pass 1 ----
+// Wavefronts per SIMD that the registers of a head dim allow without spilling: the held query tiles take D / 2
+// registers, the statistics of 16 rows 32, two key tiles in flight D / 4 + 32.
+#define SV_ROWSTAT_W(D) 3
 template <int D>
-__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void salience_rowstat_kernel(const SalienceArgs a) {
+__global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV_ROWSTAT_W(D), SV_ROWSTAT_W(D)))) void salience_rowstat_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
     __shared__ KeyStage<KB> stage[2];
+    __shared__ int s_flag;   // zero whenever block_any is entered
+    if (threadIdx.x == 0) s_flag = 0;   // the sweep below starts with a barrier
     const int blk = blockIdx.x, b = blockIdx.z;
     const int h = blockIdx.y / a.n_row_chunks, qc = blockIdx.y - h * a.n_row_chunks;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -92,28 +97,36 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         half8_t kf[KB];
         read_key_tile<KB>(st, kt, lane, kf);
         const bool seen = k0 + row < n;   // this lane's key column
-        float4_t sv[kTilesPerWave];
-        tile_logits<KB, kTilesPerWave>(qa, kf, sv);   // rows past n are zero rows: computed, never stored
 #pragma unroll
-        for (int t = 0; t < kTilesPerWave; ++t)
+        for (int t = 0; t < kTilesPerWave; ++t) {   // one row tile at a time: this path is rare and is kept light on registers
+            float4_t sv = {0.f, 0.f, 0.f, 0.f};     // rows past n are zero rows: computed, never stored
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) sv = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[kb], sv, 0, 0, 0);
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const float x = seen ? sv[t][rr] * c2 : -INFINITY;
+                const float x = seen ? sv[rr] * c2 : -INFINITY;
                 const float mn = fmaxf(ref[t][rr], x);
                 if (mn > -INFINITY) {
                     l[t][rr] = l[t][rr] * __builtin_amdgcn_exp2f(ref[t][rr] - mn) + __builtin_amdgcn_exp2f(x - mn);
                     ref[t][rr] = mn;
                 }
             }
+        }
     };
-    // One sweep over the key block.  exact = false: full stages on the fast path; exact = true: every tile with the
-    // exact running maximum (taken only after a sweep whose sums overflowed).  Instantiated once per count of live
-    // row tiles and chosen outside the loop (a switch inside it makes the compiler shuffle the state registers
-    // between the arms at every stage).  No branch around the fetch and the store of the next stage: past the end
-    // they are harmless (clamped rows, a buffer nobody reads), and conditional blocks in the body keep the scheduler
-    // from placing the matrix and vector instructions of a stage together.
-    auto run = [&](auto ntl_c, bool exact) __attribute__((always_inline)) {
-        constexpr int NTL = decltype(ntl_c)::value;
+    // One sweep over the key block.  On the fast path the full stages run in a loop of their own -- references from
+    // the first 16 keys, then multiply-add, exponential, add per element -- and the ragged last stage follows on the
+    // masked path; the exact sweep (text blocks; blocks whose fast sums left the trusted range) takes the masked path
+    // for every tile.  The loops are separate and instantiated once per count of live row tiles, chosen outside them:
+    // a stage loop that can take either path, or a switch inside it, costs the registers that decide between two and
+    // three wavefronts per SIMD.  No branch around the fetch and the store of the next stage: past the end they are
+    // harmless (clamped rows, a buffer nobody reads), and conditional blocks in the body keep the scheduler from
+    // placing the matrix and vector instructions of a stage together.
+    auto masked_stage = [&](int s0, const KeyStage<KB>& st) {
+#pragma unroll 1
+        for (int kt = 0; kt < kMassWaves; ++kt)
+            if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, st, kt);
+    };
+    auto start = [&]() {   // statistics cleared, the first stage in LDS
 #pragma unroll
         for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
@@ -125,46 +138,59 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(2,
         wait_for_loads();
         put(stage[0]);
         __syncthreads();
+    };
+    auto run_exact = [&]() {   // one instance: the masked tiles do not depend on the count of live row tiles
+        start();
         int cur = 0;
-        bool ref_ready = false;   // block-uniform: every reference is finite
         for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {
-            fetch(s0 + kStageKeys);
-            const int n_live = k_end - s0;   // live keys of this stage, >= 1
-            if (!exact && n_live >= kStageKeys) {
-                if (ref_ready) rowstat_fast_stage<KB, NTL, false, false>(stage[cur], lane, qa, c2, ref, l);
-                else rowstat_fast_stage<KB, NTL, true, false>(stage[cur], lane, qa, c2, ref, l);   // first stage of the block
-                ref_ready = true;
-            } else if (!exact) {   // the ragged last stage of the row
-                if (ref_ready) rowstat_fast_stage<KB, NTL, false, true>(stage[cur], lane, qa, c2, ref, l, n_live);
-                else rowstat_fast_stage<KB, NTL, true, true>(stage[cur], lane, qa, c2, ref, l, n_live);
-                ref_ready = true;
-            } else {
-#pragma unroll 1
-                for (int kt = 0; kt < kMassWaves; ++kt)
-                    if (s0 + kt * 16 < k_end) masked_tile(s0 + kt * 16, stage[cur], kt);
-            }
-            put(stage[cur ^ 1]);
+            masked_stage(s0, stage[cur]);
+            fetch(s0 + kStageKeys);   // after the stage, not a stage ahead: this rare path gives the registers of
+            put(stage[cur ^ 1]);      // the key tile in flight back (its spills would make the kernel use scratch)
             __syncthreads();
             cur ^= 1;
         }
     };
-    auto sweep = [&](bool exact) __attribute__((always_inline)) {
+    auto run_fast = [&](auto ntl_c) __attribute__((always_inline)) {
+        constexpr int NTL = decltype(ntl_c)::value;
+        start();
+        int cur = 0, s0 = key0;
+        if (s0 + kStageKeys <= k_end) {
+            const float ref_w = rowstat_init_ref<KB, NTL>(stage[0], lane, wave, rot, min(n - row0, kRowsPerGroup), qa, c2);   // wave-uniform
+            for (; s0 + kStageKeys <= k_end; s0 += kStageKeys) {
+                fetch(s0 + kStageKeys);
+                rowstat_fast_stage<KB, NTL>(stage[cur], lane, qa, c2, ref_w, l);
+                put(stage[cur ^ 1]);
+                __syncthreads();
+                cur ^= 1;
+            }
+#pragma unroll
+            for (int t = 0; t < NTL; ++t)   // from here on every row carries its own reference
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) ref[t][rr] = ref_w;
+        }
+        if (s0 < k_end) masked_stage(s0, stage[cur]);   // the ragged last stage: already stored by the loop above
+    };
+    auto sweep_fast = [&]() __attribute__((always_inline)) {
         switch (ntl) {   // wave-uniform
-            case 4: run(std::integral_constant<int, 4>{}, exact); break;
-            case 3: run(std::integral_constant<int, 3>{}, exact); break;
-            case 2: run(std::integral_constant<int, 2>{}, exact); break;
-            case 1: run(std::integral_constant<int, 1>{}, exact); break;
-            default: run(std::integral_constant<int, 0>{}, exact); break;
+            case 4: run_fast(std::integral_constant<int, 4>{}); break;
+            case 3: run_fast(std::integral_constant<int, 3>{}); break;
+            case 2: run_fast(std::integral_constant<int, 2>{}); break;
+            case 1: run_fast(std::integral_constant<int, 1>{}); break;
+            default: run_fast(std::integral_constant<int, 0>{}); break;
         }
     };
-    sweep(false);
-    // did a sum leave the range in which it is trusted?  (inf, NaN or above 2^100: a logit far above its row's reference)
+    sweep_fast();
+    // did the sum of a live row leave the range in which it is trusted (inf, NaN, huge or tiny: logits far from the
+    // wavefront's reference)?
     bool bad = false;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) bad |= t < ntl && !(l[t][rr] < kSumLimit);
-    if (__syncthreads_or(bad)) sweep(true);   // block-uniform
+        for (int rr = 0; rr < 4; ++rr) {
+            const bool live_row = t < ntl && row0 + row_tile_of(wave, rot, t) * 16 + 4 * quad + rr < n;
+            bad |= live_row && !(l[t][rr] < kSumLimit && l[t][rr] >= 1.f / kSumLimit);
+        }
+    if (block_any(bad, &s_flag)) run_exact();   // block-uniform
     // merge the 16 key columns of a row, store per key block (natural-log units from here on)
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t) {
