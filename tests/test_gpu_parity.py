@@ -919,3 +919,34 @@ def test_multi_turn_rounds_with_text_eviction_on_resident_buffers():
         d_txt_len.fill_(prompt)
         k_txt[:, :, prompt:], v_txt[:, :, prompt:] = 1e4, 1e4
         dkt[:, :, prompt:], dvt[:, :, prompt:] = 1e4, 1e4
+
+
+def test_pass_one_redoes_a_block_whose_rows_lie_far_below_their_wavefront_reference():
+    """Pass 1 of both attention-mass computations keeps one reference per wavefront (the largest logit its rows meet on
+    the first keys of a block).  One query row with logits hundreds of units above those of the rows beside it makes
+    their sums underflow; the kernels must notice and redo the block with a reference per row."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9400)
+    # salience: token 5 of head 0 asks a very loud question
+    B, N, H, D = 1, 600, 2, 64
+    k = (1.0 + 0.1 * rng.standard_normal((B, H, N, D), dtype=np.float32)).astype(np.float16)
+    q = (0.1 * rng.standard_normal((B, N, H, D), dtype=np.float32)).astype(np.float16)
+    q[0, 5, 0] = 30.0                         # logits ~ 0.125 * 64 * 30 = 240 against ~ 0 for its neighbours
+    sal, lse = _salience_on_gpu(q, k)
+    _assert_salience_matches(q, k, None, 0.0, sal.cpu().numpy(), lse.cpu().numpy())
+    # retrieval: the same with one question token of one head
+    Tq, Hkv, G, Nv, Nt = 6, 2, 4, 2100, 30
+    kv = (1.0 + 0.1 * rng.standard_normal((B, Hkv, Nv, D), dtype=np.float32)).astype(np.float16)
+    kt = (1.0 + 0.1 * rng.standard_normal((B, Hkv, Nt, D), dtype=np.float32)).astype(np.float16)
+    qm = (0.1 * rng.standard_normal((B, Tq, Hkv * G, D), dtype=np.float32)).astype(np.float16)
+    qm[0, 2, 5] = 30.0
+    want, want_lse = oracle.score_visual_mass(qm, kv, kt)
+    dq, dkv, dkt = (torch.from_numpy(x).to("cuda:0") for x in (qm, kv, kt))
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, 1)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    mlse = torch.full((B, Tq, Hkv * G), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, mlse)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2e-4 * want + 1e-9), f"mass error {np.abs(got - want).max():.3e}"
+    assert np.abs(mlse.cpu().numpy() - want_lse).max() <= 1e-4 * np.maximum(1.0, np.abs(want_lse)).max()
