@@ -58,8 +58,8 @@ __device__ __forceinline__ void load_held_tiles(const _Float16* base, int64_t st
 
 // ---- pass 1 ----
 // Wavefronts per SIMD that the registers of a head dim allow without spilling: the held query tiles take D / 2
-// registers, the statistics of 16 rows 32, two key tiles in flight D / 4 + 32.
-#define SV_ROWSTAT_W(D) 3
+// registers, the sums of 16 rows 16, two key tiles in flight D / 4 + 32.
+#define SV_ROWSTAT_W(D) ((D) <= 64 ? 4 : 3)
 template <int D>
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV_ROWSTAT_W(D), SV_ROWSTAT_W(D)))) void salience_rowstat_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
