@@ -201,6 +201,9 @@ sv_status sv_score_visual_mass(const sv_shape *shape, const void *q_multi, int32
  *          row's normaliser, +inf past vis_len)
  * The workspace must hold sv_salience_workspace_bytes(shape) bytes (0 for an invalid shape).
  * Deterministic: the same inputs give the same bits.
+ * Encoders WITH summary tokens (the same paragraph: attention directed toward one or a few summary
+ * rows) need no call of their own: sv_score_visual_mass with those rows as q_multi and
+ * n_txt_max = 0 gives the attention each patch token receives from them.
  */
 size_t sv_salience_workspace_bytes(const sv_shape *shape);
 sv_status sv_salience_self(const sv_shape *shape, const void *q_all, int64_t q_stride_t,
