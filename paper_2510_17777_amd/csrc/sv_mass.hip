@@ -28,8 +28,8 @@
 // The work is a contraction plus one exponential per (row, key) and pass: bound by the vector and
 // matrix pipes, not by HBM.  Everything runs in base 2 (scale * log2(e) folded into one multiply-add
 // before v_exp_f32), and an element costs a multiply-add, an exponential and an add in both passes.
-// Pass 1 takes a row's reference from its first visual keys of the block and never raises it; sums
-// that leave the trusted range send the block through an exact sweep.  The matrix instructions of
+// Pass 1 takes one reference per wavefront from the first visual keys of the block and never raises it;
+// row sums that leave the trusted range send the block through an exact sweep (a reference per row).  The matrix instructions of
 // the next key tile are placed between the vector instructions of the current one.
 #include <type_traits>
 
@@ -120,8 +120,8 @@ __device__ __forceinline__ void rowstat_body(const MassArgs& a, const int blk, K
         asm volatile("" : "+v"(ln));
         load_key_tile<KB>(keys, key_sn, min(s0 + wave * 16 + (ln & 15), n_keys - 1), ln >> 4, kfetch);
     };
-    // text tiles, ragged tiles, visual tiles met before every reference is set, and every tile of an exact sweep:
-    // masked, exact running maximum
+    // text tiles, the ragged last stage of the visual rows, and every tile of an exact sweep: masked, a reference per
+    // row kept as the exact running maximum
     auto masked_tile = [&](int k0, const KeyStage<KB>& st, int kt) {
         half8_t kf[KB];
         read_key_tile<KB>(st, kt, lane, kf);

@@ -11,7 +11,8 @@
 // operand staged through LDS 64 rows at a time (one barrier per stage, the next stage fetched into
 // registers while the current one is used):
 //   pass 1 (salience_rowstat_kernel)  a workgroup holds 256 query rows in registers and streams a block of
-//          keys: per query row a reference value and the sum of exponentials relative to it;
+//          keys: per query row the sum of exponentials relative to a reference (one per wavefront on the fast
+//          path, one per row on the exact path);
 //          salience_lse_kernel merges the key blocks into lse[b, i, h];
 //   pass 2 (salience_colsum_kernel)   the roles are swapped: a workgroup holds 256 KEYS in registers (as
 //          the A operand) and streams a segment of the query tokens, each with its lse: the tile is
@@ -92,7 +93,8 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
     };
-    // the ragged last stage of the keys (or a block shorter than one stage): exact running maximum, dead columns masked
+    // the ragged last stage of the keys (or a block shorter than one stage) and every tile of an exact sweep: a
+    // reference per row kept as the exact running maximum, dead columns masked
     auto masked_tile = [&](int k0, const KeyStage<KB>& st, int kt) {
         half8_t kf[KB];
         read_key_tile<KB>(st, kt, lane, kf);
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
         const int tile = row_tile_of(wave, rot, t);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the plain stages leave dead tiles untouched,
+            const float mine = t < ntl ? ref[t][rr] : -INFINITY;   // the fast stages leave dead tiles untouched,
             const float lmine = t < ntl ? l[t][rr] : 0.f;          // the masked ones compute them: drop both
             const float mx = row_max16(mine);
             const float e = mine > -INFINITY ? __builtin_amdgcn_exp2f(mine - mx) : 0.f;
