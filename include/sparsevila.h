@@ -165,7 +165,8 @@ sv_status sv_sparse_decode_attn(const sv_shape *shape, const void *q,
  *   scores[b,g,j] = sum_{i < Tq} sum_{h in group g} softmax_(i,h)[j]     (attention mass),
  * -inf for vis_len[b] <= j < n_vis_max, and lse[b,i,h] (optional output, [B, Tq, Hq]) is the
  * log of the row's normaliser.  The scores feed sv_topk_select unchanged.  fp16 only
- * (SV_ERR_DTYPE otherwise); Tq * (Hq / Hkv) <= 256 (SV_ERR_SHAPE otherwise; the mass is
+ * (SV_ERR_DTYPE otherwise); head_dim may also be 96 here (dims 72 or 80 zero-padded, the
+ * caller's own scale); Tq * (Hq / Hkv) <= 256 (SV_ERR_SHAPE otherwise; the mass is
  * additive over groups of query tokens).  k is ignored.  The workspace must hold
  * sv_mass_workspace_bytes(shape, Tq) bytes.
  * For the sum-of-logits aggregate of a multi-token query no separate call is needed: the sum

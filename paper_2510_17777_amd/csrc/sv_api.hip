@@ -41,7 +41,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int elem_size(int dtype) { return dtype == SV_F16 ? 2 : 4; }
 
 // Which parts of the shape a call depends on.
-enum : unsigned { kNeedQ = 1, kNeedVis = 2, kNeedTxt = 4 };
+enum : unsigned { kNeedQ = 1, kNeedVis = 2, kNeedTxt = 4, kAllowD96 = 8 };   // kAllowD96: the two attention-mass calls
 
 sv_status check_shape(const sv_shape* s, unsigned need) {
     if (!s) return SV_ERR_NULL;
@@ -51,7 +51,7 @@ sv_status check_shape(const sv_shape* s, unsigned need) {
     if (s->n_kv_heads < 1 || s->n_q_heads < 1 || s->n_q_heads % s->n_kv_heads != 0) return SV_ERR_SHAPE;
     if ((int64_t)s->n_kv_heads * ((s->n_q_heads / s->n_kv_heads + 7) / 8) > kMaxGridYZ) return SV_ERR_SHAPE;
     if (s->n_q_heads > kMaxGridYZ) return SV_ERR_SHAPE;
-    if (s->head_dim != 64 && s->head_dim != 128) return SV_ERR_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128 && !((need & kAllowD96) && s->head_dim == 96)) return SV_ERR_SHAPE;
     if (s->n_vis_max < 0 || s->n_txt_max < 0 || s->k < 0) return SV_ERR_SHAPE;
     if (!(s->scale >= 0.f) || std::isinf(s->scale)) return SV_ERR_SHAPE;
     const int64_t D = s->head_dim;
@@ -316,7 +316,7 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
 }
 
 size_t sv_mass_workspace_bytes(const sv_shape* s, int32_t n_query_tokens) {
-    if (check_shape(s, 0) != SV_OK || n_query_tokens < 1) return 0;
+    if (check_shape(s, kAllowD96) != SV_OK || n_query_tokens < 1) return 0;
     const size_t lse = align_up((size_t)s->batch * n_query_tokens * s->n_q_heads * sizeof(float));
     const size_t part = align_up(sv::mass_workspace_bytes(s->batch, s->n_kv_heads, s->n_txt_max, s->n_vis_max));
     return lse + part + kAlign;
@@ -325,7 +325,7 @@ size_t sv_mass_workspace_bytes(const sv_shape* s, int32_t n_query_tokens) {
 sv_status sv_score_visual_mass(const sv_shape* s, const void* q_multi, int32_t n_query_tokens, int64_t q_stride_t,
                                const void* k_vis, const void* k_txt, float* scores, float* lse, void* workspace,
                                size_t workspace_bytes, void* stream) {
-    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt | kAllowD96);
     if (st != SV_OK) return st;
     if (s->dtype != SV_F16) return SV_ERR_DTYPE;
     const int G = s->n_q_heads / s->n_kv_heads;

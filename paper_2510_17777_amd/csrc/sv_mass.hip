@@ -463,6 +463,10 @@ hipError_t launch_mass(const MassArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL((mass_rowstat_kernel<128>), grid1, block, 0, stream, k);
         hipLaunchKernelGGL(mass_lse_kernel, grid2, dim3(256), 0, stream, k);
         hipLaunchKernelGGL((mass_colsum_kernel<128>), grid3, block, 0, stream, k);
+    } else if (a.D == 96) {
+        hipLaunchKernelGGL((mass_rowstat_kernel<96>), grid1, block, 0, stream, k);
+        hipLaunchKernelGGL(mass_lse_kernel, grid2, dim3(256), 0, stream, k);
+        hipLaunchKernelGGL((mass_colsum_kernel<96>), grid3, block, 0, stream, k);
     } else if (a.D == 64) {
         hipLaunchKernelGGL((mass_rowstat_kernel<64>), grid1, block, 0, stream, k);
         hipLaunchKernelGGL(mass_lse_kernel, grid2, dim3(256), 0, stream, k);

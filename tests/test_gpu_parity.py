@@ -542,7 +542,7 @@ def test_attention_mass_seeded_random_shapes(case):
     lengths, a question longer than the live text): masses within 2e-4 relative, lse within 1e-4."""
     import paper_2510_17777_amd as sv
     rng = np.random.default_rng(7700 + case)
-    D = int(rng.choice([64, 128]))
+    D = int(rng.choice([64, 96, 128]))
     G = int(rng.choice([1, 2, 4, 7, 8, 16]))
     Tq = int(rng.integers(1, 256 // G + 1))
     Hkv, B = int(rng.integers(1, 3)), int(rng.integers(1, 4))
@@ -950,3 +950,30 @@ def test_pass_one_redoes_a_block_whose_rows_lie_far_below_their_wavefront_refere
     got = scores.cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - want) <= 2e-4 * want + 1e-9), f"mass error {np.abs(got - want).max():.3e}"
     assert np.abs(mlse.cpu().numpy() - want_lse).max() <= 1e-4 * np.maximum(1.0, np.abs(want_lse)).max()
+
+
+def test_summary_token_salience_is_the_attention_mass_of_the_summary_rows_without_text():
+    """Section 3.1 for encoders with summary tokens: the salience of a patch token is the attention the summary
+    row(s) direct at it (one row: CLIP-style; the mean over a few: RADIO-style).  That is sv_score_visual_mass with
+    the summary rows as the query, no text segment, one query head per kv head; head dim 80 zero-padded to 96 with
+    the encoder's own scale.  Against scipy's softmax of the explicit rows."""
+    from scipy.special import softmax
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9500)
+    B, H, N, D, d_live = 3, 16, 1370, 96, 80
+    scale = float(d_live) ** -0.5
+    for n_summary in (1, 4):
+        q = np.zeros((B, n_summary, H, D), np.float16)
+        k = np.zeros((B, H, N, D), np.float16)
+        q[..., :d_live] = rng.standard_normal((B, n_summary, H, d_live), dtype=np.float32).astype(np.float16)
+        k[..., :d_live] = rng.standard_normal((B, H, N, d_live), dtype=np.float32).astype(np.float16)
+        dq, dk = torch.from_numpy(q).to("cuda:0"), torch.from_numpy(k).to("cuda:0")
+        shape = sv.make_shape(dq[:, 0], dk, None, 1, scale=scale)
+        mass = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        sv.sv_score_visual_mass(shape, dq, dk, None, mass)
+        torch.cuda.synchronize()
+        got = mass.cpu().numpy().astype(np.float64).mean(axis=1) / n_summary          # mean over heads and summary rows
+        logits = scale * np.einsum("bshd,bhjd->bshj", q.astype(np.float64), k.astype(np.float64))
+        want = softmax(logits, axis=-1).mean(axis=(1, 2))
+        assert np.all(np.abs(got - want) <= 2e-4 * want), n_summary
+        assert np.abs(got.sum(axis=1) - 1.0).max() <= 1e-5
