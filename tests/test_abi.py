@@ -235,3 +235,14 @@ def test_salience_entry_point_checks_its_arguments():
     # the workspace grows with the layer
     big = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=20000)
     assert lib.sv_salience_workspace_bytes(ctypes.byref(big)) > need
+
+
+def test_head_dim_96_is_for_the_two_attention_mass_calls_only():
+    lib = sv.load_library()
+    s = good_shape(head_dim=96)
+    sp = ctypes.byref(s)
+    assert lib.sv_mass_workspace_bytes(sp, 8) > 0
+    assert lib.sv_score_visual_mass(sp, FAKE, 8, 28 * 96, FAKE, FAKE, FAKE, None, FAKE, 16, None) == E_WS   # past the shape check
+    assert lib.sv_workspace_bytes(sp) == 0
+    assert lib.sv_score_visual(sp, FAKE, FAKE, FAKE, None) == E_SHAPE
+    assert lib.sv_decode_step(sp, *([FAKE] * 10), FAKE, 1 << 40, None) == E_SHAPE
