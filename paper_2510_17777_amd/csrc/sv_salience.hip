@@ -117,8 +117,8 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
     };
     // One sweep over the key block.  On the fast path the full stages run in a loop of their own -- references from
     // the first 16 keys, then multiply-add, exponential, add per element -- and the ragged last stage follows on the
-    // masked path; the exact sweep (text blocks; blocks whose fast sums left the trusted range) takes the masked path
-    // for every tile.  The loops are separate and instantiated once per count of live row tiles, chosen outside them:
+    // masked path; the exact sweep (blocks whose fast sums left the trusted range) takes the masked path for every
+    // tile.  The loops are separate and instantiated once per count of live row tiles, chosen outside them:
     // a stage loop that can take either path, or a switch inside it, costs the registers that decide between two and
     // three wavefronts per SIMD.  No branch around the fetch and the store of the next stage: past the end they are
     // harmless (clamped rows, a buffer nobody reads), and conditional blocks in the body keep the scheduler from
