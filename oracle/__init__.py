@@ -8,6 +8,12 @@ this package imports nothing from them.
 
 Arrays are numpy, contiguous, ``[B, Hkv, N, D]`` for K/V and ``[B, Hq, D]``
 for q; dtype float16 or float32 decides how the C code widens the bits.
+
+Three further definitions are written out here in numpy float64 with the
+attention matrix formed explicitly: ``pack_selected`` (section 3.2, packing),
+``score_visual_mass`` (section 3.2, retrieval with a multi-token question)
+and ``salience_self`` (section 3.1, query-agnostic salience of an encoder
+layer).  Every function is pinned in ``tests/test_oracle_pins.py``.
 """
 from __future__ import annotations
 
