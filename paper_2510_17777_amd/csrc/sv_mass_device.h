@@ -5,9 +5,8 @@
 #pragma once
 #include "sv_device.h"
 
-#ifndef SV_STAGE_FENCE
+// Between the steps of a stage: the scheduler may not move instructions across it.
 #define SV_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
 
 namespace sv {
 

@@ -286,9 +286,7 @@ __device__ __forceinline__ void colsum_swapped_stage(const KeyStage<KB>& st, con
 
 // Wavefronts per SIMD the register budget of a head dim allows without spilling (more of them: more chances that one
 // issues vector instructions while another's matrix instruction runs).
-#ifndef SV_COLSUM_W
 #define SV_COLSUM_W(D) ((D) <= 64 ? 4 : 3)
-#endif
 template <int D>
 __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV_COLSUM_W(D), SV_COLSUM_W(D)))) void salience_colsum_kernel(const SalienceArgs a) {
     constexpr int KB = D / 32;
