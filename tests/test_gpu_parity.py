@@ -519,8 +519,8 @@ def test_attention_mass_scores_match_the_oracle(D, G, Tq, Nv, Nt):
     got, got_lse = scores.cpu().numpy(), lse.cpu().numpy()
     live = np.isfinite(want)
     assert np.array_equal(np.isneginf(got), ~live)
-    err = np.abs(got.astype(np.float64) - want)[live]
-    bound = (2e-4 * want + 1e-9)[live]
+    err = np.abs(np.where(live, got, 0.0).astype(np.float64) - np.where(live, want, 0.0))[live]
+    bound = (2e-4 * np.where(live, want, 0.0) + 1e-9)[live]
     assert np.all(err <= bound), f"mass error {err.max():.3e} (rel {np.max(err / want[live]):.3e})"
     fin = np.isfinite(want_lse)
     assert np.array_equal(np.isfinite(got_lse), fin)
@@ -977,3 +977,44 @@ def test_summary_token_salience_is_the_attention_mass_of_the_summary_rows_withou
         want = softmax(logits, axis=-1).mean(axis=(1, 2))
         assert np.all(np.abs(got - want) <= 2e-4 * want), n_summary
         assert np.abs(got.sum(axis=1) - 1.0).max() <= 1e-5
+
+
+@pytest.mark.parametrize("N", [1, 15, 16, 17, 63, 64, 65, 127, 128, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 1537])
+def test_salience_self_at_the_edges_of_stages_groups_and_segments(N):
+    """Token counts at and next to the 16-row tile, the 64-row stage, the 256-row group and the 512-token segment."""
+    rng = np.random.default_rng(9600 + N)
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    q, k = f(2, N, 2, 64), f(2, 2, N, 64)
+    vis_len = np.array([N, max(N - 1, 0)], np.int32)
+    sal, lse = _salience_on_gpu(q, k, vis_len)
+    _assert_salience_matches(q, k, vis_len, 0.0, sal.cpu().numpy(), lse.cpu().numpy(), f"N={N}")
+
+
+@pytest.mark.parametrize("Nv,Nt", [(1, 1), (63, 5), (64, 0), (65, 255), (1023, 256), (1024, 257), (1025, 1), (2047, 64),
+                                   (2048, 300), (2049, 513)])
+def test_attention_mass_at_the_edges_of_stages_and_key_blocks(Nv, Nt):
+    """Visual and text key counts at and next to the 64-key stage, the 256-key text block and the 1024-key visual
+    block (Nt = 0: no text segment at all); a question of 5 tokens, longer than the text where Nt < 5."""
+    import paper_2510_17777_amd as sv
+    rng = np.random.default_rng(9700 + Nv + Nt)
+    B, Tq, Hkv, G, D = 2, 5, 2, 3, 64
+    f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
+    qm, kv = f(B, Tq, Hkv * G, D), f(B, Hkv, Nv, D)
+    kt = f(B, Hkv, Nt, D) if Nt else None
+    vis_len = np.array([Nv, Nv - 1], np.int32)
+    want, want_lse = oracle.score_visual_mass(qm, kv, kt if Nt else np.zeros((B, Hkv, 0, D), np.float16), vis_len=vis_len)
+    dq, dkv = torch.from_numpy(qm).to("cuda:0"), torch.from_numpy(kv).to("cuda:0")
+    dkt = torch.from_numpy(kt).to("cuda:0") if Nt else None
+    shape = sv.make_shape(dq[:, 0], dkv, dkt, 1, vis_len=vis_len)
+    scores = torch.full((B, Hkv, Nv), float("nan"), dtype=torch.float32, device="cuda:0")
+    lse = torch.full((B, Tq, Hkv * G), float("nan"), dtype=torch.float32, device="cuda:0")
+    sv.sv_score_visual_mass(shape, dq, dkv, dkt, scores, lse)
+    torch.cuda.synchronize()
+    got, got_lse = scores.cpu().numpy(), lse.cpu().numpy()
+    live = np.isfinite(want)
+    assert np.array_equal(np.isneginf(got), ~live)
+    err = np.abs(np.where(live, got, 0.0).astype(np.float64) - np.where(live, want, 0.0))
+    assert np.all(err <= 2e-4 * np.where(live, want, 0.0) + 1e-9), f"mass error {err.max():.3e}"
+    fin = np.isfinite(want_lse)
+    assert np.array_equal(np.isfinite(got_lse), fin)
+    assert np.abs(np.where(fin, got_lse, 0.0) - np.where(fin, want_lse, 0.0)).max(initial=0.0) <= 1e-4
