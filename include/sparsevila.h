@@ -269,9 +269,11 @@ const char *sv_strerror(sv_status status);
  *                           call from the shape so that the workgroups fill the chip in whole rounds
  *   "select_filter"         sv_decode_step on long rows: 1 = the scoring kernel hands the selection only the
  *                           scores above a sampled threshold, 0 = the selection re-reads every score, -1 = default
- *   "filter_rank"           which order statistic of the 512-row sample is that threshold, 1..448; 0 = derived
+ *   "filter_rank"           which order statistic of the sampled rows is that threshold, 1..448; 0 = derived
  *                           from k / vis_len.  Any value gives the same result (a threshold that admits too
  *                           few or too many candidates makes the row fall back to the full selection)
+ *   "filter_samples"        rows of that sample: 256 or 512; 0 = by the size of the scoring launch (a launch of
+ *                           few tiles waits for its samplers and takes 256).  Any value gives the same result
  *   "filter_test_mode"      0; 1 / 2 make every third tile of the scoring kernel ignore the threshold and hand
  *                           over none / all of its scores (tests of the selection's consistency check)
  *   "step_stages"           measurement aid: sv_decode_step returns after its first 1 (scoring launch) or 2

@@ -25,6 +25,7 @@ struct Tuning {
     int32_t select_filter = -1;         // -1 = default
     int32_t filter_rank = 0;            // 0 = derived from k / n
     int32_t filter_test_mode = 0;
+    int32_t filter_samples = 0;         // 0 = by the size of the launch; 256 or 512
     int32_t step_stages = 3;            // measurement aid: sv_decode_step stops after this many stages
 };
 Tuning g_tuning;
@@ -250,6 +251,7 @@ sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, i
                                                                                : kDefaultScoreRows);
         sa.filt.rank_override = g_tuning.filter_rank;
         sa.filt.test_mode = g_tuning.filter_test_mode;
+        if (g_tuning.filter_samples > 0) sa.filt.n_samples = g_tuning.filter_samples;
         sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
         if (sv::launch_scores_filter(sa, hs) != hipSuccess) return SV_ERR_LAUNCH;
         return from_hip(sv::launch_select_filtered(sel, sa, hs));
@@ -296,6 +298,7 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
                                                  s->batch, s->n_kv_heads, s->n_vis_max, s->k, sa.rows_per_block);
             sa.filt.rank_override = g_tuning.filter_rank;
             sa.filt.test_mode = g_tuning.filter_test_mode;
+            if (g_tuning.filter_samples > 0) sa.filt.n_samples = g_tuning.filter_samples;
             sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
             sa.write_scores = scores != nullptr;   // nobody asked for the scores: do not spend HBM writes on them
         }
@@ -497,6 +500,11 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         g_tuning.filter_test_mode = value;
         return SV_OK;
     }
+    if (!std::strcmp(name, "filter_samples")) {
+        if (value != 0 && value != 256 && value != 512) return SV_ERR_SHAPE;
+        g_tuning.filter_samples = value;
+        return SV_OK;
+    }
     if (!std::strcmp(name, "step_stages")) {
         if (value < 1 || value > 3) return SV_ERR_SHAPE;
         g_tuning.step_stages = value;
@@ -518,6 +526,7 @@ int32_t sv_get_tuning(const char* name) {
         return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
     if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;
     if (!std::strcmp(name, "filter_test_mode")) return g_tuning.filter_test_mode;
+    if (!std::strcmp(name, "filter_samples")) return g_tuning.filter_samples;
     if (!std::strcmp(name, "step_stages")) return g_tuning.step_stages;
     return -1;
 }

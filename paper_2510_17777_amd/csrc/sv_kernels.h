@@ -30,6 +30,7 @@ struct FilterArgs {
     uint32_t* gen;          // [1] bumped by every filtered selection: added to epoch on the device, so that replays
                             // of a captured call (same arguments, same epoch) still tag their hint words apart
     int32_t test_mode;      // 0; tests: every third tile ignores the hint (1: keeps nothing, 2: keeps all)
+    int32_t n_samples;      // rows a sampler scores: 512, or 256 in a launch so small that it waits for its samplers
 };
 
 struct ScoreArgs {

@@ -38,7 +38,7 @@ constexpr int kScoreWaves = 4;    // wavefronts per workgroup
 constexpr int kScoreThreads = kScoreWaves * kWave;
 constexpr int kFilterMaxTileRows = 512;   // rows of one scoring workgroup when it emits candidates
 constexpr int kFilterPrimary = kFilterRecordPairs;
-constexpr int kSample = 512;              // sampled rows per (b, g)
+constexpr int kSample = 512;              // sampled rows per (b, g), at most (FilterArgs::n_samples: this or half of it)
 constexpr int kHintPolls = 64;            // bounded wait for t_lo
 constexpr int kFilterTilesPerWave = 4;    // scores_filter_kernel: tiles one wavefront turns into records
 
@@ -52,8 +52,8 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {   // integer finaliser, 
 // Sample rank whose score serves as t_lo: with p = kb/n the number of sampled rows among the
 // row's true top kb is about Binomial(S, p) (less spread, since the sample is stratified);
 // t_lo exceeds the kb-th largest score only if that number reaches the rank.
-__device__ __forceinline__ int sample_rank(int n, int kb) {
-    const float m = (float)kSample * (float)kb / (float)n;
+__device__ __forceinline__ int sample_rank(int n, int kb, int n_samples = kSample) {
+    const float m = (float)n_samples * (float)kb / (float)n;
     return (int)ceilf(m + 5.f * sqrtf(m) + 4.f);
 }
 
@@ -66,7 +66,8 @@ __device__ __forceinline__ void publish_hint(const ScoreArgs& a, int64_t unit, f
 }
 
 // The rank-th largest of the kSample scores in samp (LDS), by one wavefront: binary search on the
-// order-preserving key, most significant bit first, all keys in registers (kSample/64 per lane): a bit
+// order-preserving key, most significant bit first, all keys in registers (kSample/64 per lane; slots past a
+// smaller sample hold -inf and never count): a bit
 // stays set if at least `rank` keys are >= the probe.  No barrier, no LDS traffic in the loop.  The search
 // stops after kSearchBits bits; the bits below stay zero, i.e. the result comes out a hair lower (relative
 // 2^-15 of its magnitude): still a valid threshold, a handful more candidates.
@@ -89,9 +90,9 @@ __device__ __forceinline__ float rank_statistic(const float* samp, int rank, int
 }
 
 // Row number of sample i of a (b, g) with n live rows: stratified, with a jitter that differs per (b, g).
-__device__ __forceinline__ int sample_row_of(int i, int n, int64_t unit) {
-    const int stratum = n / kSample;   // >= 1 unless the row is shorter than the sample
-    int row = (int)(((int64_t)i * n) / kSample);
+__device__ __forceinline__ int sample_row_of(int i, int n, int64_t unit, int n_samples = kSample) {
+    const int stratum = n / n_samples;   // >= 1 unless the row is shorter than the sample
+    int row = (int)(((int64_t)i * n) / n_samples);
     if (stratum > 1) row += (int)(mix32((uint32_t)unit * 0x9E3779B9u + (uint32_t)i) % (uint32_t)stratum);
     return row < n ? row : n - 1;
 }
@@ -105,8 +106,7 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
     constexpr int U = kScoreUnroll / 2;                 // fewer loads in flight than the streaming loop: the
                                                         // sampler must fit the register budget of that loop
     constexpr int ROUND_ROWS = kScoreWaves * U * RPW;   // samples per round of loads
-    constexpr int ROUNDS = kSample / ROUND_ROWS;
-    static_assert(ROUNDS >= 1 && ROUNDS * ROUND_ROWS == kSample, "sample must divide over the workgroup");
+    static_assert(kSample % (2 * ROUND_ROWS) == 0, "the sample and its half must divide over the workgroup");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int c = lane % LPR, grp = lane / LPR;
     const int64_t unit = (int64_t)b * a.Hkv + g;
@@ -116,18 +116,21 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
         if (tid == 0) publish_hint(a, unit, INFINITY);
         return;
     }
-    const int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb);
-    if (rank > kSample - kSample / 8) {   // the sample cannot separate the top kb: every row is a candidate
+    const int ns = a.filt.n_samples == kSample / 2 ? kSample / 2 : kSample;   // block-uniform
+    const int rounds = ns / ROUND_ROWS;
+    const int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb, ns);
+    if (rank > ns - ns / 8) {   // the sample cannot separate the top kb: every row is a candidate
         if (tid == 0) publish_hint(a, unit, -INFINITY);
         return;
     }
+    for (int i = ns + tid; i < kSample; i += kScoreThreads) samp[i] = -INFINITY;   // the rank search reads kSample slots
     const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
     Chunk<T> kc[U];
     auto request = [&](int r) {   // the U sample rows of this lane group in round r
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = r * ROUND_ROWS + (wave * U + u) * RPW + grp;   // sample number
-            kc[u] = load_chunk(kbase + (int64_t)sample_row_of(i, n, unit) * a.k_sn);
+            kc[u] = load_chunk(kbase + (int64_t)sample_row_of(i, n, unit, ns) * a.k_sn);
         }
     };
     // The rounds are a chain of dependent memory trips (the register budget of the streaming loop allows
@@ -135,7 +138,7 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
     request(0);
     float qs[EPL];
     summed_query<T>(a, b, g, c, qs);
-    for (int r = 0; r < ROUNDS; ++r) {
+    for (int r = 0; r < rounds; ++r) {
         float sc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -144,7 +147,7 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
             for (int i = 0; i < EPL; ++i) s = fmaf(kc[u].at(i), qs[i], s);
             sc[u] = s;
         }
-        if (r + 1 < ROUNDS) request(r + 1);   // the next trip starts before the lane-group sums of this one
+        if (r + 1 < rounds) request(r + 1);   // the next trip starts before the lane-group sums of this one
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float s = group_sum<LPR>(sc[u]) * a.scale;

@@ -425,6 +425,7 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
 // LDS; then the same on-chip selection as for a short row runs on them, positions renamed to the
 // original rows.  If fewer than k_b candidates exist (t_lo was too high) or more than fit, the
 // workgroup selects from the full score row.
+constexpr int kSmallLaunchTiles = 1536;   // scoring launches up to this many tiles sample 256 rows per (b, g) instead of 512
 constexpr int kFiltCap = 16384;                      // candidates ranked on chip (their scores and rows fill most of the LDS)
 constexpr int kFiltMaxTiles = 256;
 constexpr int kFiltPrimary = kFilterRecordPairs;     // pairs in a primary record
@@ -980,6 +981,10 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     f.rank_override = 0;
     f.epoch = 0;
     f.test_mode = 0;
+    // A sampler reaches its threshold through a chain of dependent memory trips (64 sample rows per trip).  A launch
+    // of a few hundred tiles has streamed its keys before eight trips are over and then waits for the threshold: it
+    // gets half the sample -- a lower threshold, a quarter more candidates for the selection, four trips less.
+    f.n_samples = (int64_t)B * Hkv * f.n_tiles <= kSmallLaunchTiles ? presample_rows() / 2 : presample_rows();
     return f;
 }
 

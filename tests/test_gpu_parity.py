@@ -206,26 +206,30 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     vis_len = np.array([Nv, Nv - 13, Nv // 3], np.int32)
     base = None
     try:
-        for filt, rank, rows, mode in [(1, 0, 0, 0), (0, 0, 0, 0), (1, 1, 0, 0), (1, 440, 0, 0), (1, 0, 128, 0),
-                                       (1, 0, 1024, 0), (1, 0, 0, 1), (1, 0, 0, 2), (1, 300, 128, 2)]:
+        for filt, rank, rows, mode, samples in [(1, 0, 0, 0, 0), (0, 0, 0, 0, 0), (1, 1, 0, 0, 0), (1, 440, 0, 0, 0),
+                                                (1, 0, 128, 0, 0), (1, 0, 1024, 0, 0), (1, 0, 0, 1, 0), (1, 0, 0, 2, 0),
+                                                (1, 300, 128, 2, 0), (1, 0, 0, 0, 256), (1, 0, 0, 0, 512),
+                                                (1, 1, 0, 0, 256), (1, 200, 64, 1, 256), (1, 230, 0, 0, 256)]:
             sv.sv_set_tuning("select_filter", filt)
             sv.sv_set_tuning("filter_rank", rank)
             sv.sv_set_tuning("score_rows_per_block", rows)
             sv.sv_set_tuning("filter_test_mode", mode)
+            sv.sv_set_tuning("filter_samples", samples)   # 0: by the size of the launch (256 rows for these shapes)
             r = run_step(inp, k, vis_len=vis_len, dev=None if base is None else base["dev"])
-            assert _exact_sets(r, k, vis_len), (filt, rank, rows, mode)
+            assert _exact_sets(r, k, vis_len), (filt, rank, rows, mode, samples)
             if base is None:
                 base = r
             else:
                 for key in ("scores", "idx", "count", "out", "lse"):
-                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode)
+                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode, samples)
             # without a scores buffer the scoring launch stores no scores at all; a row whose candidates
             # do not suffice is then re-scored by the selection itself
             r2 = run_step(inp, k, vis_len=vis_len, dev=base["dev"], with_scores=False)
             for key in ("idx", "count", "out", "lse"):
-                assert np.array_equal(r2[key], base[key]), (key, filt, rank, rows, mode, "no scores buffer")
+                assert np.array_equal(r2[key], base[key]), (key, filt, rank, rows, mode, samples, "no scores buffer")
     finally:
         sv.sv_set_tuning("select_filter", -1)
+        sv.sv_set_tuning("filter_samples", 0)
         sv.sv_set_tuning("filter_rank", 0)
         sv.sv_set_tuning("score_rows_per_block", 0)
         sv.sv_set_tuning("filter_test_mode", 0)
