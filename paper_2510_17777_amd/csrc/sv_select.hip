@@ -950,16 +950,22 @@ FilterLayout layout_filter_ws(int dtype, int D, size_t units, int n_vis_max) {
 
 // Long rows whose expected candidate count (the sample-rank fraction of the row, plus four standard
 // deviations of that fraction) fits the on-chip ranking.
-bool filtered_select_applies(int dtype, int D, int n_vis_max, int k) {
-    if (n_vis_max <= kFilterMinN || k <= 0 || k >= n_vis_max) return false;
-    if (filter_tile_rows(dtype, D, 0, n_vis_max, kFiltMaxTiles) == 0) return false;
-    const double S = presample_rows();
+namespace {
+// Will the rows above the threshold of an S-row sample fit the on-chip ranking (expected count plus four sigma)?
+bool candidates_fit(double S, int n_vis_max, int k) {
     const double mean = S * (double)k / (double)n_vis_max;
     const double frac = (mean + 5.0 * std::sqrt(mean) + 4.0) / S;
     if (frac >= 0.5) return false;
     const double expect = frac * n_vis_max;
     const double sigma = n_vis_max * std::sqrt(frac * (1.0 - frac) / S);
     return expect + 4.0 * sigma <= (double)kFiltCap;
+}
+}  // namespace
+
+bool filtered_select_applies(int dtype, int D, int n_vis_max, int k) {
+    if (n_vis_max <= kFilterMinN || k <= 0 || k >= n_vis_max) return false;
+    if (filter_tile_rows(dtype, D, 0, n_vis_max, kFiltMaxTiles) == 0) return false;
+    return candidates_fit(presample_rows(), n_vis_max, k);
 }
 
 size_t filtered_workspace_bytes(int dtype, int D, int B, int Hkv, int n_vis_max) {
@@ -984,7 +990,9 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     // A sampler reaches its threshold through a chain of dependent memory trips (64 sample rows per trip).  A launch
     // of a few hundred tiles has streamed its keys before eight trips are over and then waits for the threshold: it
     // gets half the sample -- a lower threshold, a quarter more candidates for the selection, four trips less.
-    f.n_samples = (int64_t)B * Hkv * f.n_tiles <= kSmallLaunchTiles ? presample_rows() / 2 : presample_rows();
+    // (if the candidates of the smaller sample still fit the on-chip ranking).
+    const bool small_launch = (int64_t)B * Hkv * f.n_tiles <= kSmallLaunchTiles;
+    f.n_samples = small_launch && candidates_fit(presample_rows() / 2, n_vis_max, k) ? presample_rows() / 2 : presample_rows();
     return f;
 }
 
