@@ -245,6 +245,23 @@ def test_step_on_rows_beyond_the_reach_of_the_candidate_filter():
     assert_step_matches(inp, k, vis_len=vis_len, label="beyond the filter")
 
 
+@pytest.mark.parametrize("B,Hkv,G,D,dtype,Nv,Nt,k,last_len", [
+    (1, 2, 4, 64, np.float16, 524289, 100, 1000, None),        # half a million tokens, a sliver kept
+    (1, 1, 2, 64, np.float32, 300001, 17, 299000, None),       # nearly everything kept
+    (2, 1, 7, 128, np.float16, 200000, 1, 10000, 123457),      # two sequences, the second much shorter
+    (1, 1, 7, 128, np.float16, 1000003, 1024, 50000, None),    # a million tokens (hour-long video), 5 % kept
+])
+def test_rows_of_hundreds_of_thousands_of_tokens(B, Hkv, G, D, dtype, Nv, Nt, k, last_len):
+    """Very long rows, whole rule set: grids, offsets and the streaming selection at sizes far past the
+    benchmark's 50 176 tokens per row."""
+    inp = rand_inputs(9000 + Nv % 97, B, Hkv * G, Hkv, D, Nv, Nt, dtype)
+    vis_len = None
+    if last_len is not None:
+        vis_len = np.full(B, Nv, np.int32)
+        vis_len[-1] = last_len
+    assert_step_matches(inp, k, vis_len=vis_len, label=f"long rows Nv={Nv} k={k}")
+
+
 def test_filtered_selection_degenerate_rows():
     """All keys equal (every row is a candidate: more than fit on chip -> whole-row fallback), rows
     shorter than k, shorter than the sample, and empty rows, on a shape that takes the filtered path."""
