@@ -511,7 +511,8 @@ def test_pack_selected_is_a_byte_exact_gather_and_packed_attention_matches(dtype
 
 # ------------------------------------------------------------------ attention-mass retrieval with the whole question
 @pytest.mark.parametrize("D,G,Tq,Nv,Nt", [(128, 7, 32, 5000, 300), (64, 4, 9, 777, 40), (128, 1, 1, 300, 1),
-                                          (128, 8, 32, 1030, 33), (64, 2, 17, 2049, 600)])
+                                          (128, 8, 32, 1030, 33), (64, 2, 17, 2049, 600),
+                                          (128, 7, 32, 300001, 300)])   # the last: rows six times the benchmark's
 def test_attention_mass_scores_match_the_oracle(D, G, Tq, Nv, Nt):
     """sv_score_visual_mass against the oracle's explicit attention matrix: per element within the fp32
     bound below, lse within 1e-4, then the top-k set chosen from the GPU's masses bit-exact against a
