@@ -245,7 +245,11 @@ hipError_t launch_one(const AttnArgs& a, int hblk, hipStream_t stream) {
 // workgroup: its batches plus about one batch-time to reach the first rows (lengths, idx, rows).  The
 // plan minimises rounds * (batches + 1): one round that fills most of the chip beats a full round and a
 // nearly empty one (long-video shape: 4 text + 5 visual batches, 672 workgroups, 41.7 us, against
-// 4 + 4, 784 workgroups of which 16 wait for a free slot, 43.5 us).
+// 4 + 4, 784 workgroups of which 16 wait for a free slot, 43.5 us).  A launch that needs three rounds or
+// more whatever the batches (dense attention, a quarter of a long video kept) does not run in rounds any
+// more -- a slot is refilled as soon as its workgroup ends -- so there the plan minimises the summed
+// workgroup time, chunks * (batches + 1): the longest workgroups, which pay the first trip least often
+// (dense attention over 51 200 tokens x 112 units: 8 batches 494 us, 5 batches 525 us).
 void attn_flash_plan(int64_t units, int n_txt, int n_kept, int forced_batches, int* chunk_txt, int* chunk_vis) {
     if (forced_batches > 0) {
         const int nb = forced_batches < kMaxBatches ? forced_batches : kMaxBatches;
@@ -262,16 +266,26 @@ void attn_flash_plan(int64_t units, int n_txt, int n_kept, int forced_batches, i
         cached_cus.store(cus, std::memory_order_relaxed);
     }
     const int64_t slots = 3 * (int64_t)cus;
+    const int longest_chunk = kMaxBatches * kGroupTokens;
+    const int64_t fewest = units * (((int64_t)n_txt + longest_chunk - 1) / longest_chunk +
+                                    ((int64_t)n_kept + longest_chunk - 1) / longest_chunk);
+    const bool many_rounds = fewest > 2 * slots;   // three rounds or more with any batch count
     int64_t best_cost = -1;
     int best_t = 1, best_v = 1;
     for (int bt = 1; bt <= kMaxBatches; ++bt) {
         for (int bv = 1; bv <= kMaxBatches; ++bv) {
             const int64_t ct = ((int64_t)n_txt + bt * kGroupTokens - 1) / (bt * kGroupTokens);
             const int64_t cv = ((int64_t)n_kept + bv * kGroupTokens - 1) / (bv * kGroupTokens);
-            const int64_t wgs = units * (ct + cv);
-            const int64_t rounds = (wgs + slots - 1) / slots;
-            const int longest = (n_txt > 0 && bt > bv) || n_kept == 0 ? bt : bv;
-            const int64_t cost = (rounds * (longest + 1)) * 32 + bt + bv;   // ties: the shorter workgroups
+            int64_t cost;
+            if (many_rounds) {
+                cost = ct * (bt + 1) + cv * (bv + 1);
+            } else {
+                const int64_t wgs = units * (ct + cv);
+                const int64_t rounds = (wgs + slots - 1) / slots;
+                const int longest = (n_txt > 0 && bt > bv) || n_kept == 0 ? bt : bv;
+                cost = rounds * (longest + 1);
+            }
+            cost = cost * 32 + bt + bv;   // ties: the shorter workgroups
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_t = bt; best_v = bv; }
         }
     }
