@@ -1040,3 +1040,27 @@ def test_attention_mass_at_the_edges_of_stages_and_key_blocks(Nv, Nt):
     fin = np.isfinite(want_lse)
     assert np.array_equal(np.isfinite(got_lse), fin)
     assert np.abs(np.where(fin, got_lse, 0.0) - np.where(fin, want_lse, 0.0)).max(initial=0.0) <= 1e-4
+
+
+# ------------------------------------------------------------------ measurement aids
+@pytest.mark.parametrize("nbytes", [16, 4096 + 16, 256 * 16 * 3 + 48, (1 << 24) + 16 * 7])
+def test_copy_and_read_probes_move_exactly_the_stated_bytes(nbytes):
+    """The counter calibration divides by the size of this copy and the read probe's rate by its byte
+    count: the copy must be byte-exact over exactly nbytes (guard bytes behind it untouched) and the
+    read probe must write nothing but its sink."""
+    import paper_2510_17777_amd as sv
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda:0", generator=g)
+    dst = torch.full((nbytes + 64,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    sv.sv_copy_bytes(dst, src, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:nbytes], src[:nbytes])
+    assert bool((dst[nbytes:] == 0xA5).all())
+    before = src.clone()
+    sink = torch.zeros(sv.binding.READ_SINK_BYTES // 4 + 16, dtype=torch.int32, device="cuda:0")
+    sink[-16:] = 77
+    sv.sv_read_bytes(src, nbytes, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, before)
+    assert bool((sink[-16:] == 77).all())
