@@ -178,7 +178,15 @@ void attn_partial_flash_kernel(const AttnArgs a, const int hblk) {
         __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
         const half8_t pa = *reinterpret_cast<const half8_t*>(&s_p[wave][row][8 * quad]);
         __builtin_amdgcn_wave_barrier();
-        // ---- acc = acc * alpha + p * V   (p = 0 for the tokens past the end, whose rows are clamped copies)
+        // ---- acc = acc * alpha + p * V.  Tokens past the end of the part have p = 0, but their rows were
+        // still fetched (row clamped to the capacity, not to the length) and may hold anything: unused
+        // cache capacity is uninitialised memory, and 0 * NaN or 0 * Inf would poison the whole head.
+        // Their value registers are cleared; only a ragged last batch pays for it (wave-uniform test).
+        if (n_live < kBatchTokens) {
+#pragma unroll
+            for (int u = 0; u < kVLoads; ++u)
+                if (4 * u + quad >= n_live) vf[u] = 0;
+        }
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
             half8_t vb;

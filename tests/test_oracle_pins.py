@@ -15,7 +15,8 @@ transposed operand fails at least one of them:
   order      : permutation of the visual / text cache rows
   ragged     : padding rows are never read; k = 0, Nt = 0, k >= Nv
   widening   : all 65536 binary16 patterns against numpy's float16 -> float64
-  mass       : library softmax of the masked matrix; probability conservation; Tq = G = 1 is the attention weight
+  mass       : library softmax of the masked matrix; probability conservation; Tq = G = 1 is the attention weight;
+               hand-worked causal offsets (tests/golden/mass_causal_2q_3t.txt)
   salience   : library attention with V = I; two-token logistic closed form; one shared query -> its softmax;
                uniform / conservation / key-shift / permutation invariants; dominant key
 """
@@ -467,6 +468,31 @@ def test_mass_of_one_token_one_head_ranks_like_the_logit_and_matches_attention_w
         wt = np.exp(sc * kt[0, h].astype(np.float64) @ q[0, h].astype(np.float64) - lse[0, 0, h])
         out = wt @ vt[0, h].astype(np.float64) + mass[0, h] @ vv[0, h].astype(np.float64)
         assert np.allclose(out, dense["out"][0, h], rtol=1e-10, atol=1e-12)
+
+
+def test_mass_hand_worked_causal_offsets_from_golden_file():
+    """The causal offset of the question's tokens against numbers worked out by hand (ratios of small
+    integers, tests/golden/mass_causal_2q_3t.txt): a question that fits the text, and one longer than
+    the live text, whose first token sees no text row and where a row past txt_len lies in memory."""
+    from fractions import Fraction
+    ln = np.array([np.log(2.0), np.log(3.0)])
+    kt = np.array([[[[1, 0], [0, 1], [2, 1]]]], dtype=np.float64)
+    kv = np.array([[[[1, 1], [0, 2]]]], dtype=np.float64)
+    seen = set()
+    for line in open(os.path.join(GOLDEN, "mass_causal_2q_3t.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, tq, nt, q_txt, mass_txt, z_txt = [x.strip() for x in line.split("|")]
+        tq, nt = int(tq), int(nt)
+        q = np.array([[float(x) for x in pair.split(",")] for pair in q_txt.split()]) * ln   # [Tq, 2]
+        want_mass = np.array([float(Fraction(x)) for x in mass_txt.split()])
+        want_z = np.array([float(x) for x in z_txt.split()])
+        assert q.shape == (tq, 2) and want_z.shape == (tq,)
+        mass, lse = oracle.score_visual_mass(q[None, :, None, :], kv, kt, txt_len=np.array([nt]), scale=1.0)
+        np.testing.assert_allclose(mass[0, 0], want_mass, rtol=1e-14, err_msg=name)
+        np.testing.assert_allclose(np.exp(lse[0, :, 0]), want_z, rtol=1e-14, err_msg=name)
+        seen.add(name)
+    assert seen == {"A", "B"}
 
 
 # ------------------------------------------------------------------ query-agnostic salience of an encoder layer
