@@ -30,8 +30,10 @@
  *   must be a multiple of 16 bytes: rows are read with 128-bit loads.
  * Groups.  Query head h reads kv head h / (Hq / Hkv).
  * Ragged batches.  vis_len[b] <= n_vis_max and txt_len[b] <= n_txt_max give the
- *   live rows of sequence b; NULL means "all rows".  Rows past the length are
- *   never read.
+ *   live rows of sequence b; NULL means "all rows".  Rows past the length never
+ *   influence a result and may hold anything (uninitialised memory, NaN bit
+ *   patterns); a kernel may still fetch them, so the whole capacity must be
+ *   mapped device memory.
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
  *   stream).  All work is enqueued asynchronously; nothing synchronises the
  *   host.  Results are valid once the caller has synchronised the stream.

@@ -190,7 +190,29 @@ def _check(st: int, where: str) -> None:
         raise SVError(st, where)
 
 
+def _check_layout(shape: Shape, k_vis=None, v_vis=None, k_txt=None, v_txt=None) -> None:
+    """The C ABI addresses K and V of a segment with ONE set of strides (the shape's): a tensor laid out
+    differently would be read with the wrong strides, silently.  Compared here, where the tensors are known."""
+    c = shape.c
+    vis = (c.kv_vis_stride_b, c.kv_vis_stride_h, c.kv_vis_stride_n, 1)
+    txt = (c.kv_txt_stride_b, c.kv_txt_stride_h, c.kv_txt_stride_n, 1)
+    for name, t, rows, strides in (("k_vis", k_vis, c.n_vis_max, vis), ("v_vis", v_vis, c.n_vis_max, vis),
+                                   ("k_txt", k_txt, c.n_txt_max, txt), ("v_txt", v_txt, c.n_txt_max, txt)):
+        if t is None or rows == 0:
+            continue
+        if tuple(t.shape) != (c.batch, c.n_kv_heads, rows, c.head_dim):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, the sv_shape says "
+                             f"{(c.batch, c.n_kv_heads, rows, c.head_dim)}")
+        # a dimension of size 1 has no meaningful stride
+        if any(n > 1 and a != b for n, a, b in zip(t.shape, t.stride(), strides)):
+            raise ValueError(f"{name} has strides {t.stride()}, the sv_shape says {strides}: K and V of a "
+                             "segment must share one layout")
+        if _dtype_code(t) != c.dtype:
+            raise TypeError(f"{name} has dtype {t.dtype}, the sv_shape says code {c.dtype}")
+
+
 def sv_score_visual(shape: Shape, q, k_vis, scores, stream=None) -> None:
+    _check_layout(shape, k_vis=k_vis)
     _check(load_library().sv_score_visual(ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(scores),
                                           _stream(stream)), "sv_score_visual")
 
@@ -204,6 +226,7 @@ def sv_topk_select(shape: Shape, scores, idx, count, workspace=None, stream=None
 def sv_sparse_decode_attn(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse,
                           workspace, stream=None) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check_layout(shape, k_vis, v_vis, k_txt, v_txt)
     _check(load_library().sv_sparse_decode_attn(
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes, _stream(stream)),
@@ -213,6 +236,7 @@ def sv_sparse_decode_attn(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, idx, coun
 def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, count, out, lse,
                    workspace, stream=None) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check_layout(shape, k_vis, v_vis, k_txt, v_txt)
     _check(load_library().sv_decode_step(
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
@@ -268,6 +292,11 @@ def sv_salience_self(shape: Shape, q_all, k_all, salience, lse=None, workspace=N
 
 
 def sv_pack_selected(shape: Shape, k_vis, v_vis, idx, count, k_pack, v_pack, stream=None) -> None:
+    _check_layout(shape, k_vis, v_vis)
+    c = shape.c
+    for name, t in (("k_pack", k_pack), ("v_pack", v_pack)):
+        if c.k > 0 and (tuple(t.shape) != (c.batch, c.n_kv_heads, c.k, c.head_dim) or not t.is_contiguous()):
+            raise ValueError(f"{name} must be a dense [B, Hkv, k, D] tensor")
     _check(load_library().sv_pack_selected(ctypes.byref(shape.c), _ptr(k_vis), _ptr(v_vis), _ptr(idx), _ptr(count),
                                            _ptr(k_pack), _ptr(v_pack), _stream(stream)), "sv_pack_selected")
 

@@ -205,6 +205,32 @@ def test_binding_refuses_host_tensors():
         sv.sv_score_visual(shape, q, k, torch.zeros((1, 1, 8)))
 
 
+def test_binding_refuses_value_tensors_laid_out_differently_from_the_keys():
+    """K and V of a segment share the shape's strides: a V tensor in another layout (or of another size or
+    dtype) would be read with K's strides, so the binding refuses it before any pointer is taken."""
+    import torch
+    B, Hq, Hkv, D, Nv, Nt = 2, 4, 2, 64, 24, 8
+    q = torch.zeros((B, Hq, D), dtype=torch.float16)
+    k_vis = torch.zeros((B, Hkv, Nv, D), dtype=torch.float16)
+    k_txt = torch.zeros((B, Hkv, Nt, D), dtype=torch.float16)
+    shape = sv.make_shape(q, k_vis, k_txt, 4)
+    token_major = torch.zeros((B, Nv, Hkv, D), dtype=torch.float16).permute(0, 2, 1, 3)     # same sizes, other strides
+    args = dict(idx=None, count=None, out=None, lse=None, workspace=None)
+    with pytest.raises(ValueError, match="strides"):
+        sv.sv_sparse_decode_attn(shape, q, k_vis, token_major, k_txt, k_txt, **args)
+    with pytest.raises(ValueError, match="strides"):
+        sv.sv_decode_step(shape, q, k_vis, k_vis, k_txt, torch.zeros((B, Nt, Hkv, D), dtype=torch.float16).permute(0, 2, 1, 3),
+                          None, None, None, None, None, None)
+    with pytest.raises(ValueError, match="shape"):
+        sv.sv_sparse_decode_attn(shape, q, k_vis, k_vis[:, :, :-1], k_txt, k_txt, **args)
+    with pytest.raises(TypeError):
+        sv.sv_sparse_decode_attn(shape, q, k_vis, k_vis.float(), k_txt, k_txt, **args)
+    with pytest.raises(ValueError, match="strides"):
+        sv.sv_pack_selected(shape, k_vis, token_major, None, None, None, None)
+    with pytest.raises(ValueError, match="device"):         # matching layouts get as far as the pointer check
+        sv.sv_sparse_decode_attn(shape, q, k_vis, k_vis.clone(), k_txt, k_txt.clone(), **args)
+
+
 def test_salience_entry_point_checks_its_arguments():
     lib = sv.load_library()
     s = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=5000)

@@ -27,6 +27,17 @@ def rand_inputs(seed, B, Hq, Hkv, D, Nv, Nt, dtype):
                 k_txt=f(B, Hkv, Nt, D), v_txt=f(B, Hkv, Nt, D))
 
 
+def poison_dead_rows(inp, vis_len, txt_len, fill=np.nan):
+    """Rows past the lengths are unused cache capacity: whatever they hold must not reach any output."""
+    for b in range(inp["q"].shape[0]):
+        if vis_len is not None:
+            inp["k_vis"][b, :, vis_len[b]:] = fill
+            inp["v_vis"][b, :, vis_len[b]:] = fill
+        if txt_len is not None:
+            inp["k_txt"][b, :, txt_len[b]:] = fill
+            inp["v_txt"][b, :, txt_len[b]:] = fill
+
+
 def assert_step_matches(inp, k, vis_len=None, txt_len=None, scale=0.0, label=""):
     """Full rule set for one sv_decode_step call; returns the set report."""
     dtype = inp["q"].dtype
@@ -54,6 +65,7 @@ def assert_step_matches(inp, k, vis_len=None, txt_len=None, scale=0.0, label="")
     tol = out_tolerance(dtype)
     oa, ol, _ = oracle.sparse_decode_attn(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"],
                                           r["idx"], r["count"], txt_len=txt_len, scale=sc)
+    assert np.all(np.isfinite(r["out"])), f"{label}: out is not finite"
     assert np.abs(r["out"] - oa).max() <= tol, f"{label}: out err {np.abs(r['out'] - oa).max():.3e}"
     fin = np.isfinite(ol)
     assert np.array_equal(np.isneginf(r["lse"]), ~fin), label
@@ -93,7 +105,7 @@ def test_config5_ragged_batch_with_sentinel_padding_and_rounds():
     w = sv_inputs.workload(5)
     inp = sv_inputs.make_inputs(w)
     assert inp["vis_len"].min() >= 4096 and inp["vis_len"].max() <= 8192
-    for rnd in range(2):
+    for rnd in range(w.rounds):
         if rnd:
             inp = dict(inp, q=sv_inputs.round_query(w, rnd))
         assert_step_matches(inp, w.k, vis_len=inp["vis_len"], txt_len=inp["txt_len"], label=f"cfg5 r{rnd}")
@@ -371,12 +383,51 @@ def test_ragged_lengths_including_empty_sequences():
     inp = rand_inputs(23, 4, 8, 2, 64, 513, 70, np.float32)
     vis_len = np.array([513, 100, 0, 1], np.int32)
     txt_len = np.array([70, 0, 0, 3], np.int32)
-    for a in ("k_vis", "v_vis"):
-        for b in range(4):
-            inp[a][b, :, vis_len[b]:] = 1e4
-    r = run_step(inp, 64, vis_len=vis_len, txt_len=txt_len)
-    assert np.all(r["out"][2] == 0) and np.all(np.isneginf(r["lse"][2]))   # nothing to attend to
-    assert_step_matches(inp, 64, vis_len=vis_len, txt_len=txt_len, label="ragged")
+    for fill in (1e4, np.nan):      # a huge finite value would win a maximum, a NaN would survive a zero weight
+        poison_dead_rows(inp, vis_len, txt_len, fill)
+        r = run_step(inp, 64, vis_len=vis_len, txt_len=txt_len)
+        assert np.all(r["out"][2] == 0) and np.all(np.isneginf(r["lse"][2]))   # nothing to attend to
+        assert_step_matches(inp, 64, vis_len=vis_len, txt_len=txt_len, label=f"ragged fill {fill}")
+
+
+@pytest.mark.parametrize("dtype,D,G", [(np.float16, 128, 7), (np.float16, 128, 12), (np.float16, 64, 4),
+                                      (np.float32, 128, 2), (np.float32, 64, 4)])
+def test_unused_cache_capacity_holding_nan_reaches_no_output(dtype, D, G):
+    """A preallocated KV cache is uninitialised past its lengths.  Every attention kernel (matrix cores with
+    head_dim 128 and 64, vector path) on ragged lengths that end inside a batch, a chunk and at 0, with NaN in
+    every K and V row past the lengths: the whole step, the gathered attention with slots past count, and the
+    attention on packed rows whose tail past count is NaN as well."""
+    import paper_2510_17777_amd as sv
+    Hkv, B, Nv, Nt, k = 2, 4, 2100, 330, 300
+    inp = rand_inputs(400 + D + G, B, Hkv * G, Hkv, D, Nv, Nt, dtype)
+    vis_len = np.array([Nv, 1333, 7, 0], np.int32)
+    txt_len = np.array([1, 330, 129, 64], np.int32)
+    poison_dead_rows(inp, vis_len, txt_len)
+    assert_step_matches(inp, k, vis_len=vis_len, txt_len=txt_len, label="nan padding")
+    r = run_step(inp, k, vis_len=vis_len, txt_len=txt_len)
+    d, buf = r["dev"], r["buf"]
+    tdt = torch.float16 if dtype == np.float16 else torch.float32
+    k_pack = torch.empty((B, Hkv, k, D), dtype=tdt, device="cuda:0")
+    v_pack = torch.empty_like(k_pack)
+    sv.sv_pack_selected(r["shape"], d["k_vis"], d["v_vis"], buf.idx, buf.count, k_pack, v_pack)
+    torch.cuda.synchronize()
+    cnt = r["count"]
+    for b in range(B):
+        for g in range(Hkv):
+            k_pack[b, g, int(cnt[b, g]):] = float("nan")      # the caller's packed region need not be cleared either
+            v_pack[b, g, int(cnt[b, g]):] = float("nan")
+    d_txt_len = torch.from_numpy(txt_len).to("cuda:0")
+    pshape = sv.make_shape(d["q"], k_pack, d["k_txt"], k, txt_len=d_txt_len)
+    pbuf = sv.DecodeBuffers(pshape, "cuda:0")
+    sv.sv_sparse_decode_attn(pshape, d["q"], k_pack, v_pack, d["k_txt"], d["v_txt"], None, buf.count,
+                             pbuf.out, pbuf.lse, pbuf.workspace)
+    torch.cuda.synchronize()
+    tol = out_tolerance(dtype)
+    oa, ol, _ = oracle.sparse_decode_attn(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"],
+                                          r["idx"], r["count"], txt_len=txt_len)
+    got, got_lse = pbuf.out.cpu().numpy(), pbuf.lse.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - oa).max() <= tol and np.abs(got_lse - ol).max() <= tol
 
 
 def test_identical_keys_give_mean_of_values_and_first_k_indices():
@@ -453,6 +504,7 @@ def test_attention_batches_per_wavefront_every_value_against_the_oracle():
     inp = rand_inputs(77, B, Hkv * G, Hkv, D, Nv, Nt, np.float16)
     vis_len = np.array([Nv, 1300, 640, 33], np.int32)      # kept: 1300, 1300, 640 (a chunk boundary for 5 batches), 33
     txt_len = np.array([Nt, 512, 1, 0], np.int32)
+    poison_dead_rows(inp, vis_len, txt_len)                # NaN: the kernel fetches clamped rows past the lengths
     sc = 1.0 / np.sqrt(D)
     try:
         ref = None
@@ -464,6 +516,7 @@ def test_attention_batches_per_wavefront_every_value_against_the_oracle():
                 oa, ol, _ = oracle.sparse_decode_attn(inp["q"], inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"],
                                                       r["idx"], r["count"], txt_len=txt_len, scale=sc)
             assert np.array_equal(r["idx"], ref["idx"]) and np.array_equal(r["count"], ref["count"]), nb
+            assert np.all(np.isfinite(r["out"])), nb
             assert np.abs(r["out"] - oa).max() <= 2e-3, (nb, np.abs(r["out"] - oa).max())
             fin = np.isfinite(ol)
             assert np.array_equal(np.isneginf(r["lse"]), ~fin), nb
@@ -877,7 +930,7 @@ def test_multi_turn_rounds_with_text_eviction_on_resident_buffers():
     its step -- and is then evicted by resetting txt_len on the device (no reallocation; the shapes of the decode
     steps are built once, only the retrieval's shape is rebuilt because its query strides describe the question).  Every
     retrieval and every decoded token is checked against the oracle run on fresh host arrays that hold exactly what
-    is live; evicted rows are overwritten with a sentinel to show they are never read again."""
+    is live; unused and evicted rows hold NaN to show that nothing of them reaches a result."""
     import paper_2510_17777_amd as sv
     rng = np.random.default_rng(9300)
     B, Hq, Hkv, D, Nv, cap, k = 2, 8, 2, 128, 3000, 96, 300
@@ -886,7 +939,8 @@ def test_multi_turn_rounds_with_text_eviction_on_resident_buffers():
     f = lambda *s: rng.standard_normal(s, dtype=np.float32).astype(np.float16)
     k_vis, v_vis = f(B, Hkv, Nv, D), f(B, Hkv, Nv, D)
     vis_len = np.array([Nv, 2500], np.int32)
-    k_txt, v_txt = np.full((B, Hkv, cap, D), 1e4, np.float16), np.full((B, Hkv, cap, D), 1e4, np.float16)
+    k_vis[1, :, 2500:], v_vis[1, :, 2500:] = np.nan, np.nan
+    k_txt, v_txt = np.full((B, Hkv, cap, D), np.nan, np.float16), np.full((B, Hkv, cap, D), np.nan, np.float16)
     k_txt[:, :, :prompt], v_txt[:, :, :prompt] = f(B, Hkv, prompt, D), f(B, Hkv, prompt, D)
     dev = "cuda:0"
     dkv, dvv, dkt, dvt = (torch.from_numpy(x).to(dev) for x in (k_vis, v_vis, k_txt, v_txt))
@@ -935,12 +989,13 @@ def test_multi_turn_rounds_with_text_eviction_on_resident_buffers():
             torch.cuda.synchronize()
             want_out, want_lse, _ = oracle.sparse_decode_attn(q, k_vis, v_vis, np.ascontiguousarray(k_txt[:, :, :n]),
                                                               np.ascontiguousarray(v_txt[:, :, :n]), idx, cnt)
+            assert np.all(np.isfinite(pbuf.out.cpu().numpy())), (rnd, t)
             assert np.abs(pbuf.out.cpu().numpy() - want_out).max() <= 2e-3, (rnd, t)
             assert np.abs(pbuf.lse.cpu().numpy() - want_lse).max() <= 2e-3, (rnd, t)
         # eviction: the round's question and answer leave the cache; their rows are poisoned to prove it
         d_txt_len.fill_(prompt)
-        k_txt[:, :, prompt:], v_txt[:, :, prompt:] = 1e4, 1e4
-        dkt[:, :, prompt:], dvt[:, :, prompt:] = 1e4, 1e4
+        k_txt[:, :, prompt:], v_txt[:, :, prompt:] = np.nan, np.nan
+        dkt[:, :, prompt:], dvt[:, :, prompt:] = float("nan"), float("nan")
 
 
 def test_pass_one_redoes_a_block_whose_rows_lie_far_below_their_wavefront_reference():
