@@ -242,6 +242,30 @@ sv_status sv_decode_step(const sv_shape *shape, const void *q,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sv_decode_step for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results (bit for bit) as sv_decode_step, without `workspace`: the step's scratch (scores when
+ * the caller passes none, split partial results, candidate records) lives in one array of
+ * SV_STATIC_SCRATCH_BYTES inside the library's code object, one copy per GPU, held from the moment the
+ * library is loaded on that GPU until the process ends.  The call allocates and frees nothing and
+ * calls no allocating routine; the first call on a device looks the array's address up once.
+ * A shape with sv_workspace_bytes(shape) > SV_STATIC_SCRATCH_BYTES is rejected with SV_ERR_WORKSPACE
+ * before anything is launched (32 MiB covers up to eight decoder layers of a 50 176-token video folded
+ * into the batch, all 28 layers of a 12 544-token video, or a batch of 16 sequences of 8 192 visual
+ * tokens; beyond that fold fewer layers per call, or use sv_decode_step with a workspace of your own).
+ * All calls on one GPU share that GPU's array: calls whose execution may overlap on one GPU (different
+ * streams without an ordering, several host threads) race on it and must be ordered by the caller.
+ * The array keeps what the last call left; nothing in it has to start at zero.  The device that is
+ * current when the call is made must be the device of `stream` and of every pointer.
+ */
+#define SV_STATIC_SCRATCH_BYTES (32u << 20)
+sv_status sv_decode_step_static(const sv_shape *shape, const void *q,
+                                const void *k_vis, const void *v_vis,
+                                const void *k_txt, const void *v_txt,
+                                float *scores, int32_t *idx, int32_t *count,
+                                float *out, float *lse, void *stream);
+
+/*
  * Measurement aid, not part of the decode path: copies `bytes` (a multiple of 16; both
  * DEVICE pointers 16-byte aligned, non-overlapping) with a plain kernel.  Hardware
  * traffic counters are calibrated against the known size of this copy.

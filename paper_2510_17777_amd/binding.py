@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.sv_sparse_decode_attn.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sv_decode_step.restype = ctypes.c_int
     lib.sv_decode_step.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sv_decode_step_static.restype = ctypes.c_int
+    lib.sv_decode_step_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.sv_mass_workspace_bytes.restype = sz
     lib.sv_mass_workspace_bytes.argtypes = [P, i32]
     lib.sv_score_visual_mass.restype = ctypes.c_int
@@ -241,6 +243,18 @@ def sv_decode_step(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, cou
         ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
         _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _ptr(workspace), nbytes,
         _stream(stream)), "sv_decode_step")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def sv_decode_step_static(shape: Shape, q, k_vis, v_vis, k_txt, v_txt, scores, idx, count, out, lse,
+                          stream=None) -> None:
+    """sv_decode_step without a workspace argument: the library's own per-GPU scratch array serves."""
+    _check_layout(shape, k_vis, v_vis, k_txt, v_txt)
+    _check(load_library().sv_decode_step_static(
+        ctypes.byref(shape.c), _ptr(q), _ptr(k_vis), _ptr(v_vis), _ptr(k_txt), _ptr(v_txt),
+        _ptr(scores), _ptr(idx), _ptr(count), _ptr(out), _ptr(lse), _stream(stream)), "sv_decode_step_static")
 
 
 def sv_score_visual_mass(shape: Shape, q_multi, k_vis, k_txt, scores, lse=None, workspace=None, stream=None):

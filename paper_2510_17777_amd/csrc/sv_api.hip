@@ -274,16 +274,79 @@ sv_status sv_sparse_decode_attn(const sv_shape* s, const void* q, const void* k_
     return from_hip(sv::launch_attend(a, static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+
+// Workspace of sv_decode_step_static: one array per device, inside the library's code object, so that
+// the call needs no allocation by anyone.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address that kernels and copies may use is looked up once per device.
+constexpr size_t kStaticScratchBytes = SV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of the current device's copy of `scratch`; looked up on the first call on that device.
+sv_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SV_ERR_LAUNCH;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SV_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread finds the same address
+    }
+    *out = p;
+    return SV_OK;
+}
+
+sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                           const void* k_txt, const void* v_txt, float* scores, int32_t* idx,
+                           int32_t* count, float* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+// Everything about a step's arguments that the host can check, short of the workspace.
+sv_status check_step_args(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis, const void* k_txt,
+                          const void* v_txt, const int32_t* idx, const int32_t* count, const float* out) {
+    const sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    if (st != SV_OK) return st;
+    if (kept_max(s) > 0 && (!idx || !count)) return SV_ERR_NULL;
+    return check_attn_pointers(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
+}
+
+}  // namespace
+
 sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
                          const void* k_txt, const void* v_txt, float* scores, int32_t* idx,
                          int32_t* count, float* out, float* lse, void* workspace,
                          size_t workspace_bytes, void* stream) {
-    sv_status st = check_shape(s, kNeedQ | kNeedVis | kNeedTxt);
+    return decode_step_impl(s, q, k_vis, v_vis, k_txt, v_txt, scores, idx, count, out, lse, workspace,
+                            workspace_bytes, stream);
+}
+
+sv_status sv_decode_step_static(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                                const void* k_txt, const void* v_txt, float* scores, int32_t* idx,
+                                int32_t* count, float* out, float* lse, void* stream) {
+    sv_status st = check_step_args(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
+    if (st != SV_OK) return st;
+    if (plan_workspace(s).total > kStaticScratchBytes) return SV_ERR_WORKSPACE;   // before anything touches the device
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != SV_OK) return st;
+    // Nothing in the workspace has to start at zero: partial results and candidate records are written
+    // before they are read, and the threshold words carry a per-call tag, so what the previous call
+    // (of any shape) left behind is never taken for this call's.
+    return decode_step_impl(s, q, k_vis, v_vis, k_txt, v_txt, scores, idx, count, out, lse, ws,
+                            kStaticScratchBytes, stream);
+}
+
+namespace {
+
+sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, const void* v_vis,
+                           const void* k_txt, const void* v_txt, float* scores, int32_t* idx,
+                           int32_t* count, float* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    sv_status st = check_step_args(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
     if (st != SV_OK) return st;
     const bool has_vis = kept_max(s) > 0;
-    if (has_vis && (!idx || !count)) return SV_ERR_NULL;
-    st = check_attn_pointers(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
-    if (st != SV_OK) return st;
     const Workspace w = plan_workspace(s);
     st = check_workspace(w, workspace, workspace_bytes);
     if (st != SV_OK) return st;
@@ -317,6 +380,8 @@ sv_status sv_decode_step(const sv_shape* s, const void* q, const void* k_vis, co
     const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
     return from_hip(sv::launch_attend(a, hs));
 }
+
+}  // namespace
 
 size_t sv_mass_workspace_bytes(const sv_shape* s, int32_t n_query_tokens) {
     if (check_shape(s, kAllowD96) != SV_OK || n_query_tokens < 1) return 0;

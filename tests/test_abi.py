@@ -231,6 +231,31 @@ def test_binding_refuses_value_tensors_laid_out_differently_from_the_keys():
         sv.sv_sparse_decode_attn(shape, q, k_vis, k_vis.clone(), k_txt, k_txt.clone(), **args)
 
 
+def test_static_scratch_entry_point_checks_arguments_and_size_on_the_host():
+    """sv_decode_step_static validates like sv_decode_step and rejects a shape whose scratch exceeds the
+    library's array before anything touches a device (so this runs without a GPU)."""
+    lib = sv.load_library()
+    s = good_shape()
+    sp = ctypes.byref(s)
+    assert lib.sv_workspace_bytes(sp) <= sv.STATIC_SCRATCH_BYTES
+    d = [FAKE] * 5
+    assert lib.sv_decode_step_static(None, *d, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_NULL
+    assert lib.sv_decode_step_static(sp, None, *d[1:], FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_NULL
+    assert lib.sv_decode_step_static(sp, *d, FAKE, None, FAKE, FAKE, FAKE, None) == E_NULL      # idx with k > 0
+    assert lib.sv_decode_step_static(sp, *d, FAKE, FAKE, FAKE, None, FAKE, None) == E_NULL      # out
+    assert lib.sv_decode_step_static(sp, FAKE + 8, *d[1:], FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_ALIGN
+    bad = good_shape(head_dim=100)
+    assert lib.sv_decode_step_static(ctypes.byref(bad), *d, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
+    # the long video with all 28 layers folded into the batch needs more than the array holds
+    big = good_shape(batch=28, n_vis_max=50176, n_txt_max=1024, k=2509)
+    assert lib.sv_workspace_bytes(ctypes.byref(big)) > sv.STATIC_SCRATCH_BYTES
+    assert lib.sv_decode_step_static(ctypes.byref(big), *d, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_WS
+    # what the header promises to fit
+    for kw in (dict(batch=8, n_vis_max=50176, n_txt_max=1024, k=2509), dict(batch=28, n_vis_max=12544, n_txt_max=512, k=1254),
+               dict(batch=16, n_vis_max=8192, n_txt_max=1024, k=512)):
+        assert 0 < lib.sv_workspace_bytes(ctypes.byref(good_shape(**kw))) <= sv.STATIC_SCRATCH_BYTES, kw
+
+
 def test_salience_entry_point_checks_its_arguments():
     lib = sv.load_library()
     s = good_shape(n_q_heads=16, n_kv_heads=16, head_dim=96, n_vis_max=5000)
