@@ -5,7 +5,10 @@ One "step" is one sv_decode_step over the whole workload: for the long-video con
 that is all 28 independent layers folded into the batch dimension (one launch per
 stage).  Inputs are synthetic, seeded, and resident in HBM before timing starts.
 
-Prints ONE JSON line.  Besides the step latency it carries
+Prints ONE JSON line and exits 1 if the GPU result does not match the oracle.  Besides the step latency it carries
+  modes         (layered workloads) beside the folded headline, what the same work costs when every layer is a
+                call of its own, as a decoder must issue it: 28 sv_decode_step calls in a row, and the paper's own
+                per-token loop -- one sv_sparse_decode_attn per layer on packed (or gathered) kept rows;
   roofline      the scoring kernel as sv_decode_step launches it (it moves ~88 % of the
                 step's algorithmic bytes): bytes of visual K per launch / its mean duration
                 measured with HIP events on the launch stream, against the 8 TB/s HBM peak;
@@ -30,18 +33,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "decode_step_cfg4_traffic_and_lds.txt")
 
 
 def measured_traffic(cfg: int):
-    """HBM bytes per launch of the scoring kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy); only that workload has one."""
-    if cfg != 4 or not os.path.exists(TRAFFIC_FILE):
-        return None
-    for line in open(TRAFFIC_FILE):
+    """HBM bytes per launch of the scoring kernel (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy).
+    NOT measured by the run that prints it: hardware counters need runs of their own under rocprofv3 --pmc, so the
+    figure is read from the committed summary of those runs, and the line names that file and the sources it was
+    taken at.  Returns (bytes or None, source description or None)."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_cfg{cfg}_traffic_and_lds.txt")
+    if not os.path.exists(path):
+        return None, None
+    val, src = None, ""
+    for line in open(path):
         if line.startswith("traffic_bytes_per_launch"):
-            return int(line.split("=")[1])
-    return None
+            val = int(line.split("=")[1])
+        if line.startswith("source_id"):
+            src = line.split("=")[1].strip()
+    rel = os.path.relpath(path, ROOT)
+    return val, f"{rel} (rocprofv3 --pmc runs of this command, sources {src or 'unknown'}; not measured in this run)"
 
 
 def time_variants(sv, torch, w, d, shape, buf, reps):
@@ -99,23 +108,6 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
                           buf.out, buf.lse, buf.workspace)
         torch.cuda.synchronize()
         del qm, mscores, mws
-    if w.layers > 1 and shape.vis_len is None and B % w.layers == 0:
-        # the step as a model would issue it: one sv_decode_step per layer, one after the other
-        per = B // w.layers
-        views = []
-        for l in range(w.layers):
-            sl = slice(l * per, (l + 1) * per)
-            ls = sv.make_shape(d["q"][sl], d["k_vis"][sl], d["k_txt"][sl], k)
-            views.append((ls, sl))
-        lbuf = sv.DecodeBuffers(views[0][0], dev, with_scores=False)
-
-        def sequential():
-            for ls, sl in views:
-                sv.sv_decode_step(ls, d["q"][sl], d["k_vis"][sl], d["v_vis"][sl], d["k_txt"][sl], d["v_txt"][sl], None,
-                                  lbuf.idx, lbuf.count, lbuf.out, lbuf.lse, lbuf.workspace)
-        out["step_sequential_per_layer_calls_us"] = timed(sequential)
-        out["step_sequential_calls"] = w.layers
-        del lbuf
     if shape.vis_len is None:   # dense baseline and sweep: uniform visual length only
         Nv = shape.n_vis_max
         dshape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], Nv, txt_len=shape.txt_len)
@@ -195,6 +187,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload id (4 = long video, the graded one)")
+    ap.add_argument("--seed", type=int, default=0, help="offset added to every input seed (another draw of the same workload)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="independent copies of the inputs the steps rotate over; 0 = 8 when the whole KV cache would "
+                         "otherwise sit in the 256 MB last-level cache (configs 1, 2, 5), else 1")
     ap.add_argument("--oracle-layers", type=int, default=28,
                     help="how many leading layers the CPU oracle is timed and compared on (0 = skip)")
     ap.add_argument("--gen-workers", type=int, default=min(16, len(os.sched_getaffinity(0))))
@@ -210,6 +206,122 @@ def parse_args():
     ap.add_argument("--set", action="append", default=[], metavar="KNOB=VALUE",
                     help="launch-shape knob for sweeps, e.g. --set attn_batches=4")
     return ap.parse_args()
+
+
+LLC_BYTES = 256 << 20     # last-level cache of the device
+
+
+def source_id() -> str:
+    """Hash of the kernel and C-ABI sources the loaded library was built from (names the build in the JSON line
+    and in the profile summaries, where a git revision is not available on the GPU machine)."""
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2510_17777_amd", "csrc", "*")) +
+                       [os.path.join(ROOT, "include", "sparsevila.h")]):
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:12]
+
+
+class Problem:
+    """One resident copy of the workload's tensors with its own output buffers."""
+
+    def __init__(self, sv, torch, sv_inputs, w, dev, workers, keep_scores):
+        t0 = time.time()
+        self.w = w
+        self.inp = sv_inputs.make_inputs(w, workers=workers)
+        self.gen_s = time.time() - t0
+        self.d = {n: torch.from_numpy(self.inp[n]).to(dev) for n in ("q", "k_vis", "v_vis", "k_txt", "v_txt")}
+        self.ragged = w.structure == "ragged"
+        self.vis_len = self.inp["vis_len"] if self.ragged else None
+        self.txt_len = self.inp["txt_len"] if self.ragged else None
+        self.shape = sv.make_shape(self.d["q"], self.d["k_vis"], self.d["k_txt"], w.k, vis_len=self.vis_len,
+                                   txt_len=self.txt_len)
+        self.buf = sv.DecodeBuffers(self.shape, dev, with_scores=keep_scores)
+        self.queries = [self.d["q"]]
+        for rnd in range(1, w.rounds):
+            self.queries.append(torch.from_numpy(sv_inputs.round_query(w, rnd)).to(dev))
+        self.sv = sv
+
+    def step(self, rnd: int = 0):
+        d, b = self.d, self.buf
+        self.sv.sv_decode_step(self.shape, self.queries[rnd % len(self.queries)], d["k_vis"], d["v_vis"], d["k_txt"],
+                               d["v_txt"], b.scores, b.idx, b.count, b.out, b.lse, b.workspace)
+
+
+def event_times_us(torch, fn, reps, warm=3):
+    """fn(i) called reps times, each call between two events on the current stream; microseconds per call."""
+    stream = torch.cuda.current_stream()
+    for i in range(warm):
+        fn(i)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for i, (a, b) in enumerate(evs):
+        a.record(stream)
+        fn(i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+
+
+def per_layer_modes(sv, torch, pr, reps):
+    """The step as a decoder issues it: its layers depend on each other, so every layer is a call of its own.
+    (a) 28 sv_decode_step calls, one after the other (retrieval at every step);
+    (b) the paper's own decode loop, section 3.2 / 4.1: retrieval and packing once per round, then per decoded token
+        and per layer one sv_sparse_decode_attn over the text rows and the packed kept rows (here: one token = the
+        28 per-layer calls in a row), and the same with the rows gathered through idx instead of packed."""
+    w, d, dev = pr.w, pr.d, pr.d["q"].device
+    L, per = w.layers, pr.shape.batch // w.layers
+    k, Hkv, D = w.k, w.n_kv_heads, w.head_dim
+    es = w.elem_size
+    layer_algo = sv_inputs_algorithmic_bytes(pr) // L
+    attn_bytes_layer = per * Hkv * D * es * 2 * (min(k, w.n_vis) + w.n_txt)
+    out = {}
+    sls = [slice(l * per, (l + 1) * per) for l in range(L)]
+    lshapes = [sv.make_shape(d["q"][sl], d["k_vis"][sl], d["k_txt"][sl], k) for sl in sls]
+    # outputs of layer l go to slice l of a second set of buffers, so the two modes can be compared
+    b2 = sv.DecodeBuffers(pr.shape, dev, with_scores=False)
+    lws = torch.empty((sv.workspace_bytes(lshapes[0]),), dtype=torch.uint8, device=dev)
+
+    def sequential(_i):
+        for ls, sl in zip(lshapes, sls):
+            sv.sv_decode_step(ls, d["q"][sl], d["k_vis"][sl], d["v_vis"][sl], d["k_txt"][sl], d["v_txt"][sl], None,
+                              b2.idx[sl], b2.count[sl], b2.out[sl], b2.lse[sl], lws)
+    t = event_times_us(torch, sequential, reps)
+    us = float(np.median(t))
+    out["sequential_per_layer_calls"] = {
+        "calls": L, "us": round(us, 1), "us_per_layer": round(us / L, 2),
+        "achieved_GBps": round(L * layer_algo / (us * 1e-6) / 1e9, 1),
+        "hbm_frac": round(L * layer_algo / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "idx_equal_to_folded": bool(torch.equal(b2.idx, pr.buf.idx) and torch.equal(b2.count, pr.buf.count)),
+        "out_max_abs_diff_to_folded": float((b2.out - pr.buf.out).abs().max())}
+
+    k_pack = torch.empty((pr.shape.batch, Hkv, k, D), dtype=d["k_vis"].dtype, device=dev)
+    v_pack = torch.empty_like(k_pack)
+    sv.sv_pack_selected(pr.shape, d["k_vis"], d["v_vis"], pr.buf.idx, pr.buf.count, k_pack, v_pack)
+    pshapes = [sv.make_shape(d["q"][sl], k_pack[sl], d["k_txt"][sl], k) for sl in sls]
+    pws = torch.empty((sv.workspace_bytes(pshapes[0]),), dtype=torch.uint8, device=dev)
+
+    def token_packed(_i):
+        for ps, sl in zip(pshapes, sls):
+            sv.sv_sparse_decode_attn(ps, d["q"][sl], k_pack[sl], v_pack[sl], d["k_txt"][sl], d["v_txt"][sl], None,
+                                     pr.buf.count[sl], b2.out[sl], b2.lse[sl], pws)
+
+    def token_gathered(_i):
+        for ls, sl in zip(lshapes, sls):
+            sv.sv_sparse_decode_attn(ls, d["q"][sl], d["k_vis"][sl], d["v_vis"][sl], d["k_txt"][sl], d["v_txt"][sl],
+                                     pr.buf.idx[sl], pr.buf.count[sl], b2.out[sl], b2.lse[sl], lws)
+    for name, fn in (("per_layer_attention_packed", token_packed), ("per_layer_attention_gathered", token_gathered)):
+        us = float(np.median(event_times_us(torch, fn, reps)))
+        out[name] = {"calls": L, "us_per_token_all_layers": round(us, 1), "us_per_layer": round(us / L, 2),
+                     "bytes_per_layer": attn_bytes_layer,
+                     "achieved_GBps": round(L * attn_bytes_layer / (us * 1e-6) / 1e9, 1),
+                     "hbm_frac": round(L * attn_bytes_layer / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "out_max_abs_diff_to_folded": float((b2.out - pr.buf.out).abs().max())}
+    return out
+
+
+def sv_inputs_algorithmic_bytes(pr) -> int:
+    import sv_inputs
+    return sv_inputs.algorithmic_bytes(pr.w, pr.inp["vis_len"], pr.inp["txt_len"])
 
 
 def main():
@@ -242,25 +354,20 @@ def main():
         print(json.dumps({"copy_calibration_bytes": n, "launches": 5}))
         return
 
-    w = sv_inputs.workload(args.config)
-    t0 = time.time()
-    inp = sv_inputs.make_inputs(w, workers=args.gen_workers)
-    t_gen = time.time() - t0
     dev = "cuda:0"
-    d = {n: torch.from_numpy(inp[n]).to(dev) for n in ("q", "k_vis", "v_vis", "k_txt", "v_txt")}
-    ragged = w.structure == "ragged"
-    vis_len = inp["vis_len"] if ragged else None
-    txt_len = inp["txt_len"] if ragged else None
-    shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], w.k, vis_len=vis_len, txt_len=txt_len)
-    buf = sv.DecodeBuffers(shape, dev, with_scores=True)
-    step_scores = buf.scores if args.keep_scores else None
-    queries = [d["q"]]
-    for rnd in range(1, w.rounds):
-        queries.append(torch.from_numpy(sv_inputs.round_query(w, rnd)).to(dev))
+    w = sv_inputs.workload(args.config, seed_offset=args.seed)
+    # A cache that fits the last-level cache would be served from it on every step after the first: such
+    # workloads rotate over independent copies (other seeds), so that every step reads its rows from HBM.
+    copies = args.copies if args.copies > 0 else (8 if sv_inputs.cache_bytes(w) <= 2 * LLC_BYTES else 1)
+    problems = [Problem(sv, torch, sv_inputs, sv_inputs.workload(args.config, seed_offset=args.seed + 7919 * c), dev,
+                        args.gen_workers, args.keep_scores) for c in range(copies)]
+    pr = problems[0]
+    inp, d, shape, buf = pr.inp, pr.d, pr.shape, pr.buf
+    t_gen = sum(p.gen_s for p in problems)
+    rounds = max(1, w.rounds)
 
     def step(i: int):
-        sv.sv_decode_step(shape, queries[i % len(queries)], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"],
-                          step_scores, buf.idx, buf.count, buf.out, buf.lse, buf.workspace)
+        problems[i % copies].step((i // copies) % rounds)
 
     for i in range(args.warmup):
         step(i)
@@ -274,43 +381,25 @@ def main():
 
     # Spread of single steps: the same steps again, each between two events on the launch stream.
     stream = torch.cuda.current_stream()
-    sevs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for i, (a, b) in enumerate(sevs):
-        a.record(stream)
-        step(i)
-        b.record(stream)
-    torch.cuda.synchronize()
-    step_ev_us = np.array([a.elapsed_time(b) * 1e3 for a, b in sevs])
+    step_ev_us = event_times_us(torch, step, args.steps, warm=0)
 
-    # The dominant kernel alone: the scoring launch exactly as the step issues it (the "step_stages"
-    # knob makes sv_decode_step return after it), bracketed by events on the stream it is launched on.
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(args.steps)]
-    sv.sv_set_tuning("step_stages", 1)
-    try:
-        for i in range(args.steps):
-            evs[i][0].record(stream)
-            step(i)
-            evs[i][1].record(stream)
-        torch.cuda.synchronize()
-    finally:
-        sv.sv_set_tuning("step_stages", 3)
-    score_us = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+    # The dominant kernel alone: the scoring launch exactly as the step issues it.  The test build of the library
+    # (the same kernel objects; its C-ABI layer knows the "step_stages" knob, the product's does not) makes
+    # sv_decode_step return after that launch; it is bracketed by events on the stream it is launched on.
+    with sv.test_hooks():
+        for item in args.set:
+            name, val = item.split("=")
+            sv.sv_set_tuning(name, int(val))
+        sv.sv_set_tuning("step_stages", 1)
+        score_us = event_times_us(torch, step, args.steps, warm=2)
 
     # What a plain read stream reaches on this device: the same visual-K bytes read once by a kernel
     # that does nothing else (context for the roofline fraction; the peak stays the published 8 TB/s).
     sink = torch.zeros(sv.READ_SINK_BYTES // 4, dtype=torch.int32, device=dev)
-    kv_flat = d["k_vis"].reshape(-1)
-    probe_bytes = kv_flat.numel() * kv_flat.element_size() // 16 * 16
-    pevs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-    for _ in range(2):
-        sv.sv_read_bytes(kv_flat, probe_bytes, sink)
-    for a, b in pevs:
-        a.record(stream)
-        sv.sv_read_bytes(kv_flat, probe_bytes, sink)
-        b.record(stream)
-    torch.cuda.synchronize()
-    probe_gbps = probe_bytes / (float(np.mean([a.elapsed_time(b) for a, b in pevs])) * 1e-3) / 1e9
+    flats = [p.d["k_vis"].reshape(-1) for p in problems]
+    probe_bytes = flats[0].numel() * flats[0].element_size() // 16 * 16
+    probe_us = event_times_us(torch, lambda i: sv.sv_read_bytes(flats[i % copies], probe_bytes, sink), 10, warm=2)
+    probe_gbps = probe_bytes / (float(probe_us.mean()) * 1e-6) / 1e9
 
     # Clocks while the device is busy with steps (best effort; the box decides power state and clocks).
     # Read from sysfs: starting another program from a process that holds the GPU is not an option.
@@ -331,14 +420,16 @@ def main():
         torch.cuda.synchronize()
         clocks = None
 
-    # Leave the buffers holding the result of a step with query 0 for the parity report.
-    step(0)
+    # Leave the buffers of copy 0 holding the result of a step with query 0 for the parity report.
+    pr.step(0)
     torch.cuda.synchronize()
 
-    algo_bytes = sv_inputs.algorithmic_bytes(w, inp["vis_len"], inp["txt_len"])
-    k_bytes = int(w.n_kv_heads * w.head_dim * w.elem_size * inp["vis_len"].astype(np.int64).sum())
+    algo_bytes = float(np.mean([sv_inputs_algorithmic_bytes(p) for p in problems]))
+    k_bytes = float(np.mean([w.n_kv_heads * w.head_dim * w.elem_size * p.inp["vis_len"].astype(np.int64).sum()
+                             for p in problems]))
     step_gbps = algo_bytes / (us_per_step * 1e-6) / 1e9
     score_gbps = k_bytes / (float(score_us.mean()) * 1e-6) / 1e9
+    traffic, traffic_src = measured_traffic(w.cfg)
 
     result = {
         "metric": "sparse_decode_step_latency", "value": round(us_per_step, 2), "unit": "us",
@@ -348,9 +439,14 @@ def main():
         "config": {"workload": f"cfg{w.cfg}_{w.name}", "batch": w.batch, "layers_folded": w.layers,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_visual": w.n_vis, "n_text": w.n_txt, "k": w.k, "mode": "folded_layers_one_call",
+                   "seed_offset": args.seed,
                    "score_rows_per_block": sv.sv_get_tuning("score_rows_per_block"),
                    "attn_batches": sv.sv_get_tuning("attn_batches") or "planned per call"},
-        "step_algorithmic_bytes": algo_bytes,
+        "source_id": source_id(),
+        "kv_cache_bytes": sv_inputs.cache_bytes(w),
+        "rotating_copies": copies,
+        "working_set_cache_resident": bool(copies * sv_inputs.cache_bytes(w) <= LLC_BYTES),
+        "step_algorithmic_bytes": int(algo_bytes),
         "step_achieved_GBps": round(step_gbps, 1),
         "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
         "step_event_us": {"median": round(float(np.median(step_ev_us)), 2),
@@ -358,13 +454,23 @@ def main():
                           "p90": round(float(np.percentile(step_ev_us, 90)), 2)},
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": round(score_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(w.cfg), "bytes_per_launch": k_bytes,
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "bytes_per_launch": int(k_bytes),
                      "mean_us": round(float(score_us.mean()), 2), "median_us": round(float(np.median(score_us)), 2),
                      "read_stream_probe_GBps": round(probe_gbps, 1),
                      "frac_of_read_stream_probe": round(score_gbps / probe_gbps, 4)},
         "clocks_under_load": clocks,
         "input_gen_s": round(t_gen, 1),
     }
+
+    if w.layers > 1 and not pr.ragged:
+        # side by side with the folded headline: what the same work costs when every layer is a call of its own
+        result["modes"] = {"folded_layers_one_call": {"calls": 1, "us": round(float(np.median(step_ev_us)), 1),
+                                                      "hbm_frac": round(algo_bytes / (float(np.median(step_ev_us)) * 1e-6) / 1e9
+                                                                        / HBM_PEAK_GBPS, 4)}}
+        result["modes"].update(per_layer_modes(sv, torch, pr, min(args.steps, 20)))
+        pr.step(0)
+        torch.cuda.synchronize()
 
     if args.variants:
         result["variants"] = time_variants(sv, torch, w, d, shape, buf, args.steps)
@@ -373,6 +479,7 @@ def main():
     if args.oracle_layers > 0:
         import oracle
         from oracle.compare import check_index_sets, out_tolerance
+        ragged = pr.ragged
         nb = min(args.oracle_layers * w.batch, w.B)
         sub = {n: inp[n][:nb] for n in ("q", "k_vis", "v_vis", "k_txt", "v_txt")}
         vl = inp["vis_len"][:nb] if ragged else None
@@ -397,6 +504,9 @@ def main():
                                 ok=bool(rep.ok and err <= out_tolerance(w.np_dtype)))
 
     print(json.dumps(result))
+    if "parity" in result and not result["parity"]["ok"]:
+        print("bench.py: the GPU result does not match the oracle (see \"parity\")", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -102,6 +102,12 @@ void sv_shape_set_contiguous(sv_shape *shape);
 size_t sv_workspace_bytes(const sv_shape *shape);
 
 /*
+ * Bytes sv_topk_select alone needs (never more than sv_workspace_bytes): 0 for rows of up to 16384
+ * scores and for an invalid shape.  A function of batch, n_kv_heads, n_vis_max and k only.
+ */
+size_t sv_select_workspace_bytes(const sv_shape *shape);
+
+/*
  * Step 1 -- query-aware relevance (section 3.2, "Query-Aware Token Selection":
  * the aggregate attention strength between the query and each visual entry of
  * the KV cache).  The paper gives no formula; the aggregate used here is the
@@ -119,11 +125,12 @@ sv_status sv_score_visual(const sv_shape *shape, const void *q, const void *k_vi
  * idx[b,g,0..count) = the k_b = min(k, vis_len[b]) indices j < vis_len[b] with
  * the largest scores[b,g,j]; equal scores are resolved toward the lower index
  * (+0 and -0 are equal); indices ascend; idx[b,g,count..k) = -1;
- * count[b,g] = k_b.  Only the visual fields, k, and -- for the layout of the
- * workspace -- dtype and head_dim of the shape are used.
+ * count[b,g] = k_b.  Only batch, n_kv_heads, n_vis_max, vis_len and k of the
+ * shape are used (the other fields must still describe a valid shape).
  * Integer-exact: the result is the unique set defined above for the given
  * float scores.  k == 0 is valid (nothing is written to idx).  Rows of up to
- * 16384 scores need no workspace (workspace may be NULL for such shapes).
+ * 16384 scores need no workspace (workspace may be NULL for such shapes); longer
+ * rows need sv_select_workspace_bytes(shape) bytes, 256-byte aligned.
  */
 sv_status sv_topk_select(const sv_shape *shape, const float *scores,
                          int32_t *idx, int32_t *count,
@@ -300,17 +307,26 @@ const char *sv_strerror(sv_status status);
  *                           few or too many candidates makes the row fall back to the full selection)
  *   "filter_samples"        rows of that sample: 256 or 512; 0 = by the size of the scoring launch (a launch of
  *                           few tiles waits for its samplers and takes 256).  Any value gives the same result
- *   "filter_test_mode"      0; 1 / 2 make every third tile of the scoring kernel ignore the threshold and hand
- *                           over none / all of its scores (tests of the selection's consistency check)
- *   "step_stages"           measurement aid: sv_decode_step returns after its first 1 (scoring launch) or 2
- *                           (scoring and selection) stages instead of all 3; the later outputs stay unwritten
- * Values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
- * Process-wide; not thread-safe against concurrent calls.  scores, idx and count never depend on
+ * Unknown names and values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
+ * Process-wide.  Every knob is one atomic word and a call reads each knob once, when it starts: setting
+ * a knob while calls are in flight on other threads is safe and affects calls that start later.
+ * No knob can leave an output unwritten or change what is computed.  scores, idx and count never depend on
  * the knobs; out and lse depend on them only through fp32 summation order in step 3 and, for
  * "attn_mfma", through the rounding of the softmax weights to fp16 on the matrix-core path.
  */
 sv_status sv_set_tuning(const char *name, int32_t value);
-int32_t sv_get_tuning(const char *name);
+int32_t sv_get_tuning(const char *name);   /* -1 for an unknown name */
+
+/*
+ * 0 in libsparsevila.so.  The repository's tests and benchmark also build the same sources with
+ * -DSV_TEST_HOOKS into libsparsevila_hooks.so (identical kernels), where this returns 1 and
+ * sv_set_tuning knows two more names that a product build must not have:
+ *   "filter_test_mode"  1 / 2 make every third tile of the scoring kernel ignore the sampled threshold and
+ *                       hand over none / all of its scores (tests of the selection's consistency check)
+ *   "step_stages"       sv_decode_step returns after its first 1 (scoring launch) or 2 (scoring and
+ *                       selection) stages, later outputs unwritten (timing of a stage as the step issues it)
+ */
+int32_t sv_has_test_hooks(void);
 
 #ifdef __cplusplus
 }

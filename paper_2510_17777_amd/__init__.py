@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     sv_score_visual, sv_topk_select, sv_sparse_decode_attn, sv_decode_step, sv_decode_step_static,
     STATIC_SCRATCH_BYTES,
     sv_pack_selected, sv_score_visual_mass, sv_salience_self, make_encoder_shape, sv_set_tuning, sv_get_tuning,
-    sv_strerror, sv_copy_bytes, sv_read_bytes, READ_SINK_BYTES, DecodeBuffers,
+    sv_strerror, test_hooks, sv_copy_bytes, sv_read_bytes, READ_SINK_BYTES, DecodeBuffers,
 )

@@ -6,6 +6,7 @@ the HIP kernels of libsparsevila.so.  PyTorch supplies device memory and streams
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 from dataclasses import dataclass
@@ -15,7 +16,9 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsparsevila.so")
+_LIB_HOOKS_PATH = os.path.join(_HERE, "libsparsevila_hooks.so")
 _lib: Optional[ctypes.CDLL] = None
+_lib_hooks: Optional[ctypes.CDLL] = None
 
 SV_F16, SV_F32 = 0, 1
 
@@ -51,16 +54,41 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
+    _lib = _open(_LIB_PATH)
+    return _lib
+
+
+@contextlib.contextmanager
+def test_hooks():
+    """Inside the block every function of this module calls libsparsevila_hooks.so: the same kernel objects
+    linked with a build of the C-ABI layer that knows two more knobs ("filter_test_mode", "step_stages"; see
+    sv_has_test_hooks in the header).  For the repository's tests and benchmark only; the knobs are reset on exit."""
+    global _lib, _lib_hooks
+    if _lib_hooks is None:
+        _lib_hooks = _open(_LIB_HOOKS_PATH)
+        assert _lib_hooks.sv_has_test_hooks() == 1
+    saved, _lib = _lib, _lib_hooks
+    try:
+        yield _lib_hooks
+    finally:
+        _lib_hooks.sv_set_tuning(b"filter_test_mode", 0)
+        _lib_hooks.sv_set_tuning(b"step_stages", 3)
+        _lib = saved
+
+
+def _open(path: str) -> ctypes.CDLL:
+    if not os.path.exists(path):
         raise RuntimeError(
-            f"{_LIB_PATH} is missing: build it with `python -m paper_2510_17777_amd.build` "
+            f"{path} is missing: build it with `python -m paper_2510_17777_amd.build` "
             "(hipcc, gfx950).  There is no CPU fallback for the sparse decode path.")
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     P, vp, i32, sz = ctypes.POINTER(SvShape), ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.sv_shape_set_contiguous.restype = None
     lib.sv_shape_set_contiguous.argtypes = [P]
     lib.sv_workspace_bytes.restype = sz
     lib.sv_workspace_bytes.argtypes = [P]
+    lib.sv_select_workspace_bytes.restype = sz
+    lib.sv_select_workspace_bytes.argtypes = [P]
     lib.sv_score_visual.restype = ctypes.c_int
     lib.sv_score_visual.argtypes = [P, vp, vp, vp, vp]
     lib.sv_topk_select.restype = ctypes.c_int
@@ -91,7 +119,8 @@ def load_library() -> ctypes.CDLL:
     lib.sv_set_tuning.argtypes = [ctypes.c_char_p, i32]
     lib.sv_get_tuning.restype = i32
     lib.sv_get_tuning.argtypes = [ctypes.c_char_p]
-    _lib = lib
+    lib.sv_has_test_hooks.restype = i32
+    lib.sv_has_test_hooks.argtypes = []
     return lib
 
 

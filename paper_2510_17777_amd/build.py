@@ -1,4 +1,4 @@
-"""Builds libsparsevila.so (HIP, gfx950 only) in-tree next to this file."""
+"""Builds libsparsevila.so (HIP, gfx950 only) and its test build libsparsevila_hooks.so in-tree next to this file."""
 from __future__ import annotations
 
 import os
@@ -11,6 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparsevila.so")
+LIB_HOOKS = os.path.join(HERE, "libsparsevila_hooks.so")   # same objects, sv_api.hip compiled with -DSV_TEST_HOOKS
+HOOKED_SOURCE = "sv_api.hip"
 SOURCES = ["sv_api.hip", "sv_score.hip", "sv_select.hip", "sv_attend.hip", "sv_attend_mfma.hip", "sv_attend_flash.hip", "sv_pack.hip", "sv_mass.hip", "sv_salience.hip", "sv_util.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -24,9 +26,9 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, hooks: bool = False) -> str:
+    obj = os.path.join(OBJ_DIR, src.replace(".hip", "_hooks.o" if hooks else ".o"))
+    cmd = [HIPCC, *FLAGS, *(["-DSV_TEST_HOOKS"] if hooks else []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -58,14 +60,21 @@ def _compile(src: str) -> str:
 def build(verbose: bool = False) -> str:
     """Compiles every source and links the shared library; always rebuilds."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    if verbose:
-        print(f"built {LIB}")
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = ex.map(_compile, SOURCES)
+        api_hooks = ex.submit(_compile, HOOKED_SOURCE, True)
+        objs = list(objs)
+        api_hooks = api_hooks.result()
+    # The test build differs from the product in one host-side object (two more knob names in sv_api.hip): every
+    # kernel object is shared, so what the hooks time and test is the product's device code.
+    hooked = [api_hooks if o.endswith(HOOKED_SOURCE.replace(".hip", ".o")) else o for o in objs]
+    for lib, parts in ((LIB, objs), (LIB_HOOKS, hooked)):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *parts]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

@@ -16,19 +16,54 @@ constexpr int kMinChunk = 64;      // smallest attention chunk; sizes the worksp
 constexpr int kMaxChunk = 1024;
 constexpr int kMaxGridYZ = 65535;
 
-struct Tuning {
-    int32_t score_rows_per_block = 0;   // 0 = default
-    int32_t attn_chunk = 0;
-    int32_t score_stream_loads = -1;    // -1 = default
-    int32_t attn_mfma = -1;             // -1 = default
-    int32_t attn_batches = 0;           // 0 = planned per launch
-    int32_t select_filter = -1;         // -1 = default
-    int32_t filter_rank = 0;            // 0 = derived from k / n
-    int32_t filter_test_mode = 0;
-    int32_t filter_samples = 0;         // 0 = by the size of the launch; 256 or 512
-    int32_t step_stages = 3;            // measurement aid: sv_decode_step stops after this many stages
+// Launch-shape knobs.  Each is one atomic word, read once per call into a plain snapshot, so a call sees
+// one consistent value of every knob and a concurrent sv_set_tuning cannot tear anything.
+enum Knob : int {
+    kScoreRowsPerBlock, kAttnChunk, kScoreStreamLoads, kAttnMfma, kAttnBatches, kSelectFilter, kFilterRank,
+    kFilterSamples,
+#ifdef SV_TEST_HOOKS
+    kFilterTestMode, kStepStages,   // exist only in the test build of the library (libsparsevila_hooks.so)
+#endif
+    kNumKnobs
 };
-Tuning g_tuning;
+struct KnobSpec { const char* name; int32_t init; };
+constexpr KnobSpec kKnobSpecs[kNumKnobs] = {
+    {"score_rows_per_block", 0},   // 0 = default
+    {"attn_chunk", 0},
+    {"score_stream_loads", -1},    // -1 = default
+    {"attn_mfma", -1},
+    {"attn_batches", 0},           // 0 = planned per launch
+    {"select_filter", -1},
+    {"filter_rank", 0},            // 0 = derived from k / n
+    {"filter_samples", 0},         // 0 = by the size of the launch; 256 or 512
+#ifdef SV_TEST_HOOKS
+    {"filter_test_mode", 0},
+    {"step_stages", 3},            // sv_decode_step stops after this many stages
+#endif
+};
+struct Knobs {
+    std::atomic<int32_t> v[kNumKnobs];
+    Knobs() { for (int i = 0; i < kNumKnobs; ++i) v[i].store(kKnobSpecs[i].init, std::memory_order_relaxed); }
+};
+Knobs g_knobs;
+
+struct Tuning {   // one call's view of the knobs
+    int32_t score_rows_per_block, attn_chunk, score_stream_loads, attn_mfma, attn_batches, select_filter, filter_rank,
+        filter_samples, filter_test_mode, step_stages;
+};
+inline Tuning tuning_snapshot() {
+    auto get = [](int k) { return g_knobs.v[k].load(std::memory_order_relaxed); };
+    Tuning t{};
+    t.score_rows_per_block = get(kScoreRowsPerBlock); t.attn_chunk = get(kAttnChunk);
+    t.score_stream_loads = get(kScoreStreamLoads); t.attn_mfma = get(kAttnMfma); t.attn_batches = get(kAttnBatches);
+    t.select_filter = get(kSelectFilter); t.filter_rank = get(kFilterRank); t.filter_samples = get(kFilterSamples);
+#ifdef SV_TEST_HOOKS
+    t.filter_test_mode = get(kFilterTestMode); t.step_stages = get(kStepStages);
+#else
+    t.filter_test_mode = 0; t.step_stages = 3;
+#endif
+    return t;
+}
 std::atomic<uint32_t> g_epoch{0x5eed0001u};   // tags the threshold words of one sv_decode_step call
 
 constexpr int kDefaultScoreRows = 256;
@@ -112,6 +147,28 @@ Workspace plan_workspace(const sv_shape* s) {
     return w;
 }
 
+// sv_topk_select carves the workspace on its own -- [selection scratch][candidate records] from offset 0 -- as a
+// function of batch, n_kv_heads, n_vis_max and k alone: the call reads nothing else of the shape.  The records of
+// given scores are laid out for the finest tiling any scoring kernel uses (that of fp32 rows of 128 dims).
+constexpr int kSelectDtype = SV_F32, kSelectDim = 128;
+struct SelectOnlyWorkspace { size_t sel_bytes, filt_off, filt_bytes, total; };
+
+SelectOnlyWorkspace plan_select_workspace(const sv_shape* s) {
+    SelectOnlyWorkspace w{};
+    w.sel_bytes = align_up(sv::select_workspace_bytes(s->batch, s->n_kv_heads, s->n_vis_max));
+    w.filt_off = w.sel_bytes;
+    if (w.sel_bytes > 0 && sv::filtered_select_applies(kSelectDtype, kSelectDim, s->n_vis_max, s->k))
+        w.filt_bytes = align_up(sv::filtered_workspace_bytes(kSelectDtype, kSelectDim, s->batch, s->n_kv_heads, s->n_vis_max));
+    w.total = w.filt_off + w.filt_bytes;
+    return w;
+}
+
+// What sv_workspace_bytes reports: enough for each of the three calls.
+size_t workspace_total(const sv_shape* s) {
+    const size_t step = plan_workspace(s).total, sel = plan_select_workspace(s).total;
+    return step > sel ? step : sel;
+}
+
 sv_status check_workspace(const Workspace& w, const void* ws, size_t bytes) {
     if (!ws) return SV_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(ws) % kAlign) return SV_ERR_WORKSPACE;
@@ -119,7 +176,7 @@ sv_status check_workspace(const Workspace& w, const void* ws, size_t bytes) {
     return SV_OK;
 }
 
-sv::ScoreArgs make_score_args(const sv_shape* s, const void* q, const void* k_vis, float* scores) {
+sv::ScoreArgs make_score_args(const sv_shape* s, const Tuning& tune, const void* q, const void* k_vis, float* scores) {
     sv::ScoreArgs a{};
     a.q = q; a.k_vis = k_vis; a.scores = scores; a.vis_len = s->vis_len;
     a.B = s->batch; a.Hkv = s->n_kv_heads; a.G = s->n_q_heads / s->n_kv_heads;
@@ -127,8 +184,8 @@ sv::ScoreArgs make_score_args(const sv_shape* s, const void* q, const void* k_vi
     a.scale = effective_scale(s);
     a.q_sb = s->q_stride_b; a.q_sh = s->q_stride_h;
     a.k_sb = s->kv_vis_stride_b; a.k_sh = s->kv_vis_stride_h; a.k_sn = s->kv_vis_stride_n;
-    a.rows_per_block = g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block : kDefaultScoreRows;
-    a.stream_loads = g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
+    a.rows_per_block = tune.score_rows_per_block > 0 ? tune.score_rows_per_block : kDefaultScoreRows;
+    a.stream_loads = tune.score_stream_loads >= 0 ? tune.score_stream_loads : kDefaultStreamLoads;
     a.write_scores = 1;
     return a;
 }
@@ -142,7 +199,7 @@ sv::SelectArgs make_select_args(const sv_shape* s, const Workspace& w, void* ws,
     return a;
 }
 
-sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, const void* q,
+sv::AttnArgs make_attn_args(const sv_shape* s, const Tuning& tune, const Workspace& w, void* ws, const void* q,
                             const void* k_vis, const void* v_vis, const void* k_txt, const void* v_txt,
                             const int32_t* idx, const int32_t* count, float* out, float* lse) {
     sv::AttnArgs a{};
@@ -158,8 +215,8 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     a.q_sb = s->q_stride_b; a.q_sh = s->q_stride_h;
     a.vis_sb = s->kv_vis_stride_b; a.vis_sh = s->kv_vis_stride_h; a.vis_sn = s->kv_vis_stride_n;
     a.txt_sb = s->kv_txt_stride_b; a.txt_sh = s->kv_txt_stride_h; a.txt_sn = s->kv_txt_stride_n;
-    a.chunk = g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
-    a.use_mfma = (s->dtype == SV_F16) && (g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma);
+    a.chunk = tune.attn_chunk > 0 ? tune.attn_chunk : kDefaultAttnChunk;
+    a.use_mfma = (s->dtype == SV_F16) && (tune.attn_mfma >= 0 ? tune.attn_mfma : kDefaultAttnMfma);
     if (a.use_mfma) a.chunk = sv::attn_mfma_chunk();   // the attn_chunk knob shapes the vector path only
     a.chunk_vis = a.chunk;
     const int64_t t_max = (int64_t)s->n_txt_max + kept_max(s);
@@ -167,7 +224,7 @@ sv::AttnArgs make_attn_args(const sv_shape* s, const Workspace& w, void* ws, con
     a.split_base = -1;
     if (a.use_mfma && s->head_dim == 128) {   // that kernel gives text and visual tokens chunks of their own
         const int hblk = a.G > 8 ? (a.G + 7) / 8 : 1;
-        sv::attn_flash_plan((int64_t)a.B * a.Hkv * hblk, s->n_txt_max, kept_max(s), g_tuning.attn_batches, &a.chunk,
+        sv::attn_flash_plan((int64_t)a.B * a.Hkv * hblk, s->n_txt_max, kept_max(s), tune.attn_batches, &a.chunk,
                             &a.chunk_vis);
         a.split_base = (s->n_txt_max + a.chunk - 1) / a.chunk;
         a.n_chunks = a.split_base + (kept_max(s) + a.chunk_vis - 1) / a.chunk_vis;
@@ -210,7 +267,12 @@ void sv_shape_set_contiguous(sv_shape* s) {
 
 size_t sv_workspace_bytes(const sv_shape* s) {
     if (check_shape(s, 0) != SV_OK) return 0;
-    return plan_workspace(s).total;
+    return workspace_total(s);
+}
+
+size_t sv_select_workspace_bytes(const sv_shape* s) {
+    if (check_shape(s, 0) != SV_OK) return 0;
+    return plan_select_workspace(s).total;
 }
 
 sv_status sv_score_visual(const sv_shape* s, const void* q, const void* k_vis, float* scores, void* stream) {
@@ -219,7 +281,7 @@ sv_status sv_score_visual(const sv_shape* s, const void* q, const void* k_vis, f
     if (s->n_vis_max == 0) return SV_OK;
     if (!q || !k_vis || !scores) return SV_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_vis)) return SV_ERR_ALIGN;
-    return from_hip(sv::launch_score(make_score_args(s, q, k_vis, scores), static_cast<hipStream_t>(stream)));
+    return from_hip(sv::launch_score(make_score_args(s, tuning_snapshot(), q, k_vis, scores), static_cast<hipStream_t>(stream)));
 }
 
 sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, int32_t* count,
@@ -229,29 +291,31 @@ sv_status sv_topk_select(const sv_shape* s, const float* scores, int32_t* idx, i
     if (!count) return SV_ERR_NULL;
     if (s->k > 0 && !idx) return SV_ERR_NULL;
     if (s->n_vis_max > 0 && !scores) return SV_ERR_NULL;
-    const Workspace w = plan_workspace(s);
-    if (w.sel_bytes > 0) {   // short rows are selected entirely on chip and need no workspace
-        st = check_workspace(w, workspace, workspace_bytes);
-        if (st != SV_OK) return st;
+    const SelectOnlyWorkspace w = plan_select_workspace(s);
+    if (w.total > 0) {   // short rows are selected entirely on chip and need no workspace
+        if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign || workspace_bytes < w.total)
+            return SV_ERR_WORKSPACE;
     }
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const sv::SelectArgs sel = make_select_args(s, w, workspace, scores, idx, count);
-    const bool filter = w.filt_bytes > 0 && w.sel_bytes > 0 &&
-                        (g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter) != 0;
+    const Tuning tune = tuning_snapshot();
+    sv::SelectArgs sel{};
+    sel.scores = scores; sel.idx = idx; sel.count = count; sel.vis_len = s->vis_len;
+    sel.ws = w.total > 0 ? workspace : nullptr;
+    sel.B = s->batch; sel.Hkv = s->n_kv_heads; sel.n_vis_max = s->n_vis_max; sel.k = s->k;
+    const bool filter = w.filt_bytes > 0 && (tune.select_filter >= 0 ? tune.select_filter : kDefaultSelectFilter) != 0;
     if (filter) {   // long rows: one pass over the scores hands the on-chip selection its candidates
         sv::ScoreArgs sa{};
         sa.scores = const_cast<float*>(scores);   // read only: write_scores = 1 keeps the selection's fallback off it
         sa.vis_len = s->vis_len;
-        sa.B = s->batch; sa.Hkv = s->n_kv_heads; sa.G = s->n_q_heads / s->n_kv_heads;
-        sa.D = s->head_dim; sa.n_vis_max = s->n_vis_max; sa.dtype = s->dtype;
+        sa.B = s->batch; sa.Hkv = s->n_kv_heads; sa.G = 1;
+        sa.D = kSelectDim; sa.n_vis_max = s->n_vis_max; sa.dtype = kSelectDtype;
         sa.write_scores = 1;
-        sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, s->dtype, s->head_dim,
+        sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, kSelectDtype, kSelectDim,
                                              s->batch, s->n_kv_heads, s->n_vis_max, s->k,
-                                             g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block
-                                                                               : kDefaultScoreRows);
-        sa.filt.rank_override = g_tuning.filter_rank;
-        sa.filt.test_mode = g_tuning.filter_test_mode;
-        if (g_tuning.filter_samples > 0) sa.filt.n_samples = g_tuning.filter_samples;
+                                             tune.score_rows_per_block > 0 ? tune.score_rows_per_block : kDefaultScoreRows);
+        sa.filt.rank_override = tune.filter_rank;
+        sa.filt.test_mode = tune.filter_test_mode;
+        if (tune.filter_samples > 0) sa.filt.n_samples = tune.filter_samples;
         sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
         if (sv::launch_scores_filter(sa, hs) != hipSuccess) return SV_ERR_LAUNCH;
         return from_hip(sv::launch_select_filtered(sel, sa, hs));
@@ -270,7 +334,7 @@ sv_status sv_sparse_decode_attn(const sv_shape* s, const void* q, const void* k_
     const Workspace w = plan_workspace(s);
     st = check_workspace(w, workspace, workspace_bytes);
     if (st != SV_OK) return st;
-    const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
+    const sv::AttnArgs a = make_attn_args(s, tuning_snapshot(), w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
     return from_hip(sv::launch_attend(a, static_cast<hipStream_t>(stream)));
 }
 
@@ -327,7 +391,7 @@ sv_status sv_decode_step_static(const sv_shape* s, const void* q, const void* k_
                                 int32_t* count, float* out, float* lse, void* stream) {
     sv_status st = check_step_args(s, q, k_vis, v_vis, k_txt, v_txt, idx, count, out);
     if (st != SV_OK) return st;
-    if (plan_workspace(s).total > kStaticScratchBytes) return SV_ERR_WORKSPACE;   // before anything touches the device
+    if (workspace_total(s) > kStaticScratchBytes) return SV_ERR_WORKSPACE;   // before anything touches the device
     void* ws = nullptr;
     st = static_scratch(&ws);
     if (st != SV_OK) return st;
@@ -351,23 +415,24 @@ sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, 
     st = check_workspace(w, workspace, workspace_bytes);
     if (st != SV_OK) return st;
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    const Tuning tune = tuning_snapshot();
     if (has_vis) {
         float* sc = scores ? scores : reinterpret_cast<float*>(static_cast<char*>(workspace) + w.scores_off);
-        sv::ScoreArgs sa = make_score_args(s, q, k_vis, sc);
+        sv::ScoreArgs sa = make_score_args(s, tune, q, k_vis, sc);
         const bool filter = w.filt_bytes > 0 &&
-                            (g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter) != 0;
+                            (tune.select_filter >= 0 ? tune.select_filter : kDefaultSelectFilter) != 0;
         if (filter) {   // long rows: sample a threshold, let the scoring kernel emit the candidates above it
             sa.filt = sv::carve_filter_workspace(static_cast<char*>(workspace) + w.filt_off, s->dtype, s->head_dim,
                                                  s->batch, s->n_kv_heads, s->n_vis_max, s->k, sa.rows_per_block);
-            sa.filt.rank_override = g_tuning.filter_rank;
-            sa.filt.test_mode = g_tuning.filter_test_mode;
-            if (g_tuning.filter_samples > 0) sa.filt.n_samples = g_tuning.filter_samples;
+            sa.filt.rank_override = tune.filter_rank;
+            sa.filt.test_mode = tune.filter_test_mode;
+            if (tune.filter_samples > 0) sa.filt.n_samples = tune.filter_samples;
             sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
             sa.write_scores = scores != nullptr;   // nobody asked for the scores: do not spend HBM writes on them
         }
         hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
-        if (g_tuning.step_stages < 2) return SV_OK;
+        if (tune.step_stages < 2) return SV_OK;
         const sv::SelectArgs sel = make_select_args(s, w, workspace, sc, idx, count);
         e = filter ? sv::launch_select_filtered(sel, sa, hs) : sv::launch_select(sel, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
@@ -376,8 +441,8 @@ sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, 
         hipError_t e = sv::launch_select(make_select_args(s, w, workspace, scores, idx, count), hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
     }
-    if (g_tuning.step_stages < 3) return SV_OK;
-    const sv::AttnArgs a = make_attn_args(s, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
+    if (tune.step_stages < 3) return SV_OK;
+    const sv::AttnArgs a = make_attn_args(s, tune, w, workspace, q, k_vis, v_vis, k_txt, v_txt, idx, count, out, lse);
     return from_hip(sv::launch_attend(a, hs));
 }
 
@@ -525,75 +590,49 @@ const char* sv_strerror(sv_status status) {
 
 sv_status sv_set_tuning(const char* name, int32_t value) {
     if (!name) return SV_ERR_NULL;
-    if (!std::strcmp(name, "score_rows_per_block")) {
-        if (value != 0 && (value < 64 || value > 65536)) return SV_ERR_SHAPE;
-        g_tuning.score_rows_per_block = value;
-        return SV_OK;
+    int k = 0;
+    while (k < kNumKnobs && std::strcmp(name, kKnobSpecs[k].name)) ++k;
+    bool ok = false;
+    switch (k) {
+        case kScoreRowsPerBlock: ok = value == 0 || (value >= 64 && value <= 65536); break;
+        case kAttnChunk: ok = value == 0 || (value >= kMinChunk && value <= kMaxChunk && value % 64 == 0); break;
+        case kScoreStreamLoads: case kAttnMfma: case kSelectFilter: ok = value >= -1 && value <= 1; break;
+        case kAttnBatches: ok = value >= 0 && value <= 8; break;
+        case kFilterRank: ok = value >= 0 && value <= 448; break;
+        case kFilterSamples: ok = value == 0 || value == 256 || value == 512; break;
+#ifdef SV_TEST_HOOKS
+        case kFilterTestMode: ok = value >= 0 && value <= 2; break;
+        case kStepStages: ok = value >= 1 && value <= 3; break;
+#endif
+        default: break;   // unknown name
     }
-    if (!std::strcmp(name, "attn_chunk")) {
-        if (value != 0 && (value < kMinChunk || value > kMaxChunk || value % 64)) return SV_ERR_SHAPE;
-        g_tuning.attn_chunk = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "score_stream_loads")) {
-        if (value < -1 || value > 1) return SV_ERR_SHAPE;
-        g_tuning.score_stream_loads = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "attn_mfma")) {
-        if (value < -1 || value > 1) return SV_ERR_SHAPE;
-        g_tuning.attn_mfma = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "attn_batches")) {
-        if (value < 0 || value > 8) return SV_ERR_SHAPE;
-        g_tuning.attn_batches = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "select_filter")) {
-        if (value < -1 || value > 1) return SV_ERR_SHAPE;
-        g_tuning.select_filter = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "filter_rank")) {
-        if (value < 0 || value > 448) return SV_ERR_SHAPE;
-        g_tuning.filter_rank = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "filter_test_mode")) {
-        if (value < 0 || value > 2) return SV_ERR_SHAPE;
-        g_tuning.filter_test_mode = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "filter_samples")) {
-        if (value != 0 && value != 256 && value != 512) return SV_ERR_SHAPE;
-        g_tuning.filter_samples = value;
-        return SV_OK;
-    }
-    if (!std::strcmp(name, "step_stages")) {
-        if (value < 1 || value > 3) return SV_ERR_SHAPE;
-        g_tuning.step_stages = value;
-        return SV_OK;
-    }
-    return SV_ERR_SHAPE;
+    if (!ok) return SV_ERR_SHAPE;
+    g_knobs.v[k].store(value, std::memory_order_relaxed);
+    return SV_OK;
 }
 
 int32_t sv_get_tuning(const char* name) {
     if (!name) return -1;
-    if (!std::strcmp(name, "score_rows_per_block"))
-        return g_tuning.score_rows_per_block > 0 ? g_tuning.score_rows_per_block : kDefaultScoreRows;
-    if (!std::strcmp(name, "attn_chunk")) return g_tuning.attn_chunk > 0 ? g_tuning.attn_chunk : kDefaultAttnChunk;
-    if (!std::strcmp(name, "score_stream_loads"))
-        return g_tuning.score_stream_loads >= 0 ? g_tuning.score_stream_loads : kDefaultStreamLoads;
-    if (!std::strcmp(name, "attn_mfma")) return g_tuning.attn_mfma >= 0 ? g_tuning.attn_mfma : kDefaultAttnMfma;
-    if (!std::strcmp(name, "attn_batches")) return g_tuning.attn_batches;
-    if (!std::strcmp(name, "select_filter"))
-        return g_tuning.select_filter >= 0 ? g_tuning.select_filter : kDefaultSelectFilter;
-    if (!std::strcmp(name, "filter_rank")) return g_tuning.filter_rank;
-    if (!std::strcmp(name, "filter_test_mode")) return g_tuning.filter_test_mode;
-    if (!std::strcmp(name, "filter_samples")) return g_tuning.filter_samples;
-    if (!std::strcmp(name, "step_stages")) return g_tuning.step_stages;
-    return -1;
+    int k = 0;
+    while (k < kNumKnobs && std::strcmp(name, kKnobSpecs[k].name)) ++k;
+    if (k == kNumKnobs) return -1;
+    const int32_t v = g_knobs.v[k].load(std::memory_order_relaxed);
+    switch (k) {   // knobs with a "default" value report what that default is
+        case kScoreRowsPerBlock: return v > 0 ? v : kDefaultScoreRows;
+        case kAttnChunk: return v > 0 ? v : kDefaultAttnChunk;
+        case kScoreStreamLoads: return v >= 0 ? v : kDefaultStreamLoads;
+        case kAttnMfma: return v >= 0 ? v : kDefaultAttnMfma;
+        case kSelectFilter: return v >= 0 ? v : kDefaultSelectFilter;
+        default: return v;
+    }
+}
+
+int32_t sv_has_test_hooks(void) {
+#ifdef SV_TEST_HOOKS
+    return 1;
+#else
+    return 0;
+#endif
 }
 
 }  // extern "C"

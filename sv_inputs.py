@@ -55,6 +55,7 @@ class Workload:
     frame_len: int = 196
     vis_len_min: int = 0  # ragged only
     rounds: int = 1
+    seed_offset: int = 0  # added to every seed: other draws of the same workload (bench --seed, rotating copies)
 
     @property
     def B(self) -> int:
@@ -86,7 +87,7 @@ def workload(cfg: int, **overrides) -> Workload:
 
 
 def _layer_rng(w: Workload, layer: int) -> np.random.Generator:
-    return np.random.default_rng(BASE_SEED + 1000 * w.cfg + layer)
+    return np.random.default_rng(BASE_SEED + w.seed_offset + 1000 * w.cfg + layer)
 
 
 def _normal(rng, shape):
@@ -158,8 +159,13 @@ def make_inputs(w: Workload, layers: Optional[range] = None, workers: int = 1) -
 
 def round_query(w: Workload, rnd: int) -> np.ndarray:
     """Fresh query of conversation round rnd >= 1 (round 0 uses make_inputs' q)."""
-    rng = np.random.default_rng(BASE_SEED + 1000 * w.cfg + 500 + rnd)
+    rng = np.random.default_rng(BASE_SEED + w.seed_offset + 1000 * w.cfg + 500 + rnd)
     return _normal(rng, (w.B, w.n_q_heads, w.head_dim)).astype(w.np_dtype)
+
+
+def cache_bytes(w: Workload) -> int:
+    """Bytes of the whole KV cache of the workload (visual and text, K and V, at capacity)."""
+    return int(2 * w.B * w.n_kv_heads * (w.n_vis + w.n_txt) * w.head_dim * w.elem_size)
 
 
 def algorithmic_bytes(w: Workload, vis_len: np.ndarray, txt_len: np.ndarray) -> int:

@@ -184,6 +184,78 @@ def test_strerror_and_tuning_knobs():
     sv.sv_set_tuning("attn_batches", 0)
 
 
+def test_product_library_has_no_test_hooks_and_the_test_build_exports_the_same_abi():
+    """libsparsevila.so knows no knob that can leave an output unwritten or falsify a kernel's behaviour; the
+    test build (same kernel objects, -DSV_TEST_HOOKS in the C-ABI layer) adds exactly those two names."""
+    lib = sv.load_library()
+    assert lib.sv_has_test_hooks() == 0
+    for name in (b"filter_test_mode", b"step_stages"):
+        assert lib.sv_set_tuning(name, 1) == E_SHAPE
+        assert lib.sv_get_tuning(name) == -1
+    with sv.test_hooks() as hooks:
+        assert hooks is not lib and hooks.sv_has_test_hooks() == 1
+        assert sv.load_library() is hooks                      # inside the block the binding calls the test build
+        for name in declared_functions():
+            assert hasattr(hooks, name), name
+        assert hooks.sv_set_tuning(b"step_stages", 1) == OK and hooks.sv_get_tuning(b"step_stages") == 1
+        assert hooks.sv_set_tuning(b"step_stages", 0) == E_SHAPE and hooks.sv_set_tuning(b"step_stages", 4) == E_SHAPE
+        assert hooks.sv_set_tuning(b"filter_test_mode", 2) == OK
+        assert hooks.sv_set_tuning(b"filter_test_mode", 3) == E_SHAPE
+        assert lib.sv_get_tuning(b"step_stages") == -1         # the product's state is its own
+    assert sv.load_library() is lib
+    assert hooks.sv_get_tuning(b"step_stages") == 3 and hooks.sv_get_tuning(b"filter_test_mode") == 0   # reset on exit
+
+
+def test_knobs_are_atomic_words_that_concurrent_setters_cannot_tear():
+    """Each knob is one atomic word: threads hammering sv_set_tuning with valid values while others read leave
+    every read a value that some thread wrote."""
+    import threading
+    lib = sv.load_library()
+    seen, stop = set(), threading.Event()
+
+    def setter(v):
+        while not stop.is_set():
+            assert lib.sv_set_tuning(b"attn_batches", v) == OK
+
+    def reader():
+        for _ in range(20000):
+            seen.add(lib.sv_get_tuning(b"attn_batches"))
+
+    threads = [threading.Thread(target=setter, args=(v,)) for v in (1, 8)] + [threading.Thread(target=reader)]
+    for t in threads:
+        t.start()
+    threads[-1].join()
+    stop.set()
+    for t in threads[:-1]:
+        t.join()
+    lib.sv_set_tuning(b"attn_batches", 0)
+    assert seen <= {0, 1, 8}
+
+
+def test_select_workspace_depends_on_the_fields_the_selection_reads_only():
+    """sv_topk_select reads batch, n_kv_heads, n_vis_max, vis_len and k: the workspace it asks for must not change
+    with dtype, head_dim, the query heads or the text fields, and sv_workspace_bytes covers it."""
+    lib = sv.load_library()
+
+    def need(**kw):
+        s = good_shape(**dict(dict(batch=2, n_kv_heads=2, n_q_heads=2, n_vis_max=60000, k=3000), **kw))
+        sp = ctypes.byref(s)
+        n = lib.sv_select_workspace_bytes(sp)
+        assert 0 < n <= lib.sv_workspace_bytes(sp) and n % 256 == 0
+        assert lib.sv_topk_select(sp, FAKE, FAKE, FAKE, None, 0, None) == E_WS          # long rows need one
+        assert lib.sv_topk_select(sp, FAKE, FAKE, FAKE, FAKE, n - 256, None) == E_WS    # one granule short
+        assert lib.sv_topk_select(sp, FAKE, FAKE, FAKE, FAKE + 16, n, None) == E_WS     # misaligned
+        return n
+
+    base = need()
+    for kw in (dict(dtype=1), dict(head_dim=64), dict(n_q_heads=14), dict(n_txt_max=4096), dict(dtype=1, head_dim=64)):
+        assert need(**kw) == base, kw
+    assert need(n_vis_max=120000) > base and need(batch=4) > base
+    short = good_shape(n_vis_max=16384, k=100)
+    assert lib.sv_select_workspace_bytes(ctypes.byref(short)) == 0                       # selected on chip
+    assert lib.sv_select_workspace_bytes(ctypes.byref(good_shape(head_dim=100))) == 0    # invalid shape
+
+
 def test_measurement_aids_check_their_arguments():
     lib = sv.load_library()
     lib.sv_read_bytes.restype = ctypes.c_int

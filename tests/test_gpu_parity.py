@@ -217,6 +217,8 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     inp["k_vis"][1, 1, :] = np.round(inp["k_vis"][1, 1, :])                 # coarse keys: many equal scores
     vis_len = np.array([Nv, Nv - 13, Nv // 3], np.int32)
     base = None
+    hooks = sv.test_hooks()     # the test build of the library: same kernel objects, plus the "filter_test_mode" knob
+    hooks.__enter__()
     try:
         for filt, rank, rows, mode, samples in [(1, 0, 0, 0, 0), (0, 0, 0, 0, 0), (1, 1, 0, 0, 0), (1, 440, 0, 0, 0),
                                                 (1, 0, 128, 0, 0), (1, 0, 1024, 0, 0), (1, 0, 0, 1, 0), (1, 0, 0, 2, 0),
@@ -245,6 +247,11 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
         sv.sv_set_tuning("filter_rank", 0)
         sv.sv_set_tuning("score_rows_per_block", 0)
         sv.sv_set_tuning("filter_test_mode", 0)
+        hooks.__exit__(None, None, None)
+    # the product library, default knobs: bit for bit what the test build gave, and the whole rule set
+    r = run_step(inp, k, vis_len=vis_len, dev=base["dev"])
+    for key in ("scores", "idx", "count", "out", "lse"):
+        assert np.array_equal(r[key], base[key]), key
     assert_step_matches(inp, k, vis_len=vis_len, label="filtered")
 
 
