@@ -288,8 +288,9 @@ sv_status sv_copy_bytes(void *dst, const void *src, size_t bytes, void *stream);
 #define SV_READ_SINK_BYTES 4096
 sv_status sv_read_bytes(const void *src, size_t bytes, uint32_t *sink, void *stream);
 
-/* Static, human-readable name of a status code. */
-const char *sv_strerror(sv_status status);
+/* Static, human-readable name of a status code; takes an int so that any value may be asked about
+ * ("unknown status" for one that is no sv_status). */
+const char *sv_strerror(int status);
 
 /*
  * Launch-shape knobs for measurement sweeps (not needed for correct use):

@@ -30,10 +30,19 @@ _LIB = os.path.join(_HERE, "libsv_oracle.so")
 _lib: Optional[ctypes.CDLL] = None
 
 
+# SV_ORACLE_SANITIZE=1: the same source built with AddressSanitizer and UndefinedBehaviorSanitizer into a library of
+# its own (the process must then run with gcc's libasan preloaded; see tests/run_sanitizers.sh).
+_SANITIZE = os.environ.get("SV_ORACLE_SANITIZE", "0") not in ("", "0")
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libsv_oracle_asan.so")
+
+
 def build(force: bool = False) -> str:
     """Compile sv_oracle.c with gcc (OpenMP over independent (batch, head) units)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=undefined"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c99", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

@@ -15,7 +15,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsparsevila.so")
+# SPARSEVILA_LIBRARY names another build of the same library to load instead (e.g. the host-sanitized one).
+_LIB_PATH = os.environ.get("SPARSEVILA_LIBRARY") or os.path.join(_HERE, "libsparsevila.so")
 _LIB_HOOKS_PATH = os.path.join(_HERE, "libsparsevila_hooks.so")
 _lib: Optional[ctypes.CDLL] = None
 _lib_hooks: Optional[ctypes.CDLL] = None

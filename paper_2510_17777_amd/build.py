@@ -26,9 +26,17 @@ FLAGS = [
 ]
 
 
-def _compile(src: str, hooks: bool = False) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", "_hooks.o" if hooks else ".o"))
-    cmd = [HIPCC, *FLAGS, *(["-DSV_TEST_HOOKS"] if hooks else []), "-c", os.path.join(CSRC, src), "-o", obj]
+# Host-side sanitizers (AddressSanitizer + UndefinedBehaviorSanitizer on the C-ABI layer and the launchers; device
+# code is compiled as always).  Used by build_host_sanitized() only.
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+LIB_ASAN = os.path.join(HERE, "libsparsevila_asan.so")
+
+
+def _compile(src: str, hooks: bool = False, sanitize: bool = False) -> str:
+    obj = os.path.join(OBJ_DIR, src.replace(".hip", "_asan.o" if sanitize else "_hooks.o" if hooks else ".o"))
+    cmd = [HIPCC, *FLAGS, *(["-DSV_TEST_HOOKS"] if hooks else []), *(HOST_SANITIZE if sanitize else []),
+           "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -78,5 +86,25 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(verbose: bool = False) -> str:
+    """libsparsevila_asan.so: every source with AddressSanitizer and UndefinedBehaviorSanitizer on its HOST code.
+    For the CPU-only argument-checking tests (tests/run_sanitizers.sh); load it with SPARSEVILA_LIBRARY=<path> and
+    clang's libclang_rt.asan preloaded.  Not built by build()."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(lambda s: _compile(s, sanitize=True), SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+           "-shared-libsan", "-o", LIB_ASAN, *objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {LIB_ASAN}")
+    return LIB_ASAN
+
+
 if __name__ == "__main__":
-    build(verbose=True)
+    if "--host-sanitize" in sys.argv[1:]:
+        build_host_sanitized(verbose=True)
+    else:
+        build(verbose=True)

@@ -575,7 +575,7 @@ sv_status sv_read_bytes(const void* src, size_t bytes, uint32_t* sink, void* str
     return from_hip(sv::launch_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
 }
 
-const char* sv_strerror(sv_status status) {
+const char* sv_strerror(int status) {
     switch (status) {
         case SV_OK: return "ok";
         case SV_ERR_NULL: return "a required pointer is NULL";

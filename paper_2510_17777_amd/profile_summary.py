@@ -137,6 +137,8 @@ def main():
     if ks:
         o.append("by the profiler's begin/end stamps of the same launches (%s, %d work-items): avg %.1f us -> %.1f GB/s = %.1f %% of 8 TB/s."
                  % (ks[0], ks[1], st[ks][1], rf["bytes_per_launch"] / st[ks][1] / 1e3, rf["bytes_per_launch"] / st[ks][1] / 1e3 / 80.0))
+    o.append("(event-timed figures of a run under the tracer carry its cost per launch, a few microseconds: the step and mode")
+    o.append(" times of an untraced run are lower; the begin/end stamps of the kernels above are not affected.)")
     for name, m in bj.get("modes", {}).items():
         o.append("mode %-32s %s" % (name, json.dumps(m)))
     os.makedirs(args.out, exist_ok=True)
