@@ -36,6 +36,7 @@
 #include "sv_score_device.h"
 
 #include <atomic>
+#include <type_traits>
 #include <cfloat>
 #include <cmath>
 
@@ -270,18 +271,47 @@ struct SingleShared {
 // ITEMS*1024 of them readable, map is ignored -- and are read with 128-bit loads, two pairs at a time.
 // With have_range the caller vouches that lo_hint <= every score and supplies an upper value for the
 // binning (scores above it share the top bin); the workgroup then skips its own min/max pass.
+// The ITEMS consecutive scores of lane `tid` of a row with n_cap readable scores at s, requested without
+// knowing how many of them are live (0 past the capacity): a caller that fetches them before the row's length has
+// arrived saves one trip through memory.
+template <int ITEMS>
+__device__ __forceinline__ void load_lane_items(const float* __restrict__ s, int n_cap, int tid, float (&vals)[ITEMS]) {
+    const int j0 = tid * ITEMS;
+    const int readable = min(max(n_cap - j0, 0), ITEMS);
+    if ((reinterpret_cast<uintptr_t>(s) & 15u) == 0) {   // block-uniform: 128-bit loads inside the row
+#pragma unroll
+        for (int i = 0; i < ITEMS; i += 4) {
+            if (i + 4 <= readable) {
+                const float4 v = *reinterpret_cast<const float4*>(s + j0 + i);
+                vals[i] = v.x; vals[i + 1] = v.y; vals[i + 2] = v.z; vals[i + 3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = i; e < i + 4; ++e) vals[e] = e < readable ? s[j0 + e] : 0.f;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) vals[i] = i < readable ? s[j0 + i] : 0.f;
+    }
+}
+
+// pre: the lane's scores as load_lane_items fetched them (nullptr: fetched here, once n is known).
 template <int ITEMS, bool kVec>
 __device__ __forceinline__ void select_block(SingleShared& sh, const float* __restrict__ s, int32_t* __restrict__ out,
                                              int n, int kb, int tid, int lane, int wave,
                                              const int32_t* map = nullptr, bool have_range = false,
-                                             float lo_hint = 0.f, float hi_hint = 0.f) {
+                                             float lo_hint = 0.f, float hi_hint = 0.f,
+                                             const float (*pre)[ITEMS] = nullptr) {
     constexpr int NT = kSingleThreads, NW = NT / kWave;
     static_assert(!kVec || ITEMS % 2 == 0, "vector reads take two pairs");
     const int j0 = tid * ITEMS;
     const int my_items = min(max(n - j0, 0), ITEMS);
     float vals[ITEMS];
     int32_t pair_name[kVec ? ITEMS : 1];
-    if (kVec) {
+    if (pre) {   // compile-time known at every call site
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) vals[i] = i < my_items ? (*pre)[i] : 0.f;
+    } else if (kVec) {
 #pragma unroll
         for (int i = 0; i < ITEMS; i += 2) {
             const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint2*>(s) + j0 + i);
@@ -407,14 +437,27 @@ __global__ __launch_bounds__(kSingleThreads) void select_single_kernel(const Sel
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int64_t unit = (int64_t)b * a.Hkv + g;
-    const int n = live_rows(a.vis_len, b, a.n_vis_max);
-    const int kb = a.k < n ? a.k : n;
-    if (emit_trivial<kSingleThreads>(a, unit, n, kb, 0, 1, tid)) return;
     const float* s = a.scores + unit * a.n_vis_max;
     int32_t* out = a.idx + unit * a.k;
-    if (n <= 4 * kSingleThreads) select_block<4, false>(sh, s, out, n, kb, tid, lane, wave);         // block-uniform
-    else if (n <= 8 * kSingleThreads) select_block<8, false>(sh, s, out, n, kb, tid, lane, wave);
-    else select_block<kSingleMaxN / kSingleThreads, false>(sh, s, out, n, kb, tid, lane, wave);
+    // Scores per lane by the row's CAPACITY, so that they can be requested before the row's length has arrived
+    // (rows past the length are masked afterwards): one trip through memory instead of two.
+    if (a.k == 0 || !a.scores) {   // nothing to keep (a text-only step passes no scores): count and padding only
+        const int n = live_rows(a.vis_len, b, a.n_vis_max);
+        emit_trivial<kSingleThreads>(a, unit, n, 0, 0, 1, tid);
+        return;
+    }
+    auto run = [&](auto items_tag) {
+        constexpr int ITEMS = decltype(items_tag)::value;
+        float pre[ITEMS];
+        load_lane_items<ITEMS>(s, a.n_vis_max, tid, pre);
+        const int n = live_rows(a.vis_len, b, a.n_vis_max);
+        const int kb = a.k < n ? a.k : n;
+        if (emit_trivial<kSingleThreads>(a, unit, n, kb, 0, 1, tid)) return;
+        select_block<ITEMS, false>(sh, s, out, n, kb, tid, lane, wave, nullptr, false, 0.f, 0.f, &pre);
+    };
+    if (a.n_vis_max <= 4 * kSingleThreads) run(std::integral_constant<int, 4>{});         // block-uniform
+    else if (a.n_vis_max <= 8 * kSingleThreads) run(std::integral_constant<int, 8>{});
+    else run(std::integral_constant<int, kSingleMaxN / kSingleThreads>{});
 }
 
 // ------------------------------------------------------------------ candidate-filtered shape
