@@ -90,8 +90,8 @@ __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x
 // redoes the block on the exact path (a reference per row with a running maximum).  So an element costs a
 // multiply-add, an exponential and an add, as in pass 2, with no maximum, no vote and no branch, and the loop holds
 // no reference registers: with 16 of them per lane, or with the references set by a variant of the stage code inside
-// the loop, or with a second variant of the stage for the ragged last stage of a row, the kernel needed more than
-// the 168 registers that three wavefronts per SIMD leave.
+// the loop, the kernel needed more than the 168 registers that three wavefronts per SIMD leave.  The ragged last
+// stage of a key block runs the same code (rowstat_fast_stage masks its dead columns through the reference).
 // rows_live: rows of this workgroup below it exist (the others are zero rows and must not set the reference).
 template <int KB, int NTL>
 __device__ __forceinline__ float rowstat_init_ref(const KeyStage<KB>& st, int lane, int wave, int rot, int rows_live,
@@ -110,10 +110,13 @@ __device__ __forceinline__ float rowstat_init_ref(const KeyStage<KB>& st, int la
     return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, wave_max(m))));
 }
 
-// A stage of 64 live keys: the matrix instructions of the next key tile go between the vector instructions of this one.
+// A stage of which the first live_cols (1..64, wave-uniform) key columns are live: the matrix instructions of the next
+// key tile go between the vector instructions of this one.  A dead column (the ragged end of a key block; its key is
+// a copy of the last live one) takes -inf in place of the reference in the multiply-add, so its term is exactly 0 at
+// no cost per element: one compare and one select per key tile.
 template <int KB, int NTL>
 __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int lane, const half8_t (&qa)[kTilesPerWave][KB],
-                                                   float c2, float ref, float (&l)[kTilesPerWave][4]) {
+                                                   float c2, float ref, int live_cols, float (&l)[kTilesPerWave][4]) {
     half8_t kf[2][KB];
     float4_t sv[2][kTilesPerWave];
     read_key_tile<KB>(st, 0, lane, kf[0]);
@@ -130,6 +133,7 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
 #pragma unroll
             for (int t = 0; t < NTL; ++t) sv[nxt][t] = {0.f, 0.f, 0.f, 0.f};
         }
+        const float nref = kt * 16 + (lane & 15) < live_cols ? -ref : -INFINITY;
         float y[n_e1], pr[n_e1];
 #pragma unroll
         for (int step = 0; step < n_e + 2; ++step) {
@@ -140,7 +144,7 @@ __device__ __forceinline__ void rowstat_fast_stage(const KeyStage<KB>& st, int l
                     sv[nxt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t][kb], kf[nxt][kb], sv[nxt][t], 0, 0, 0);
                 }
             }
-            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, -ref);
+            if (step < n_e) y[step] = fmaf(sv[cur][step / 4][step % 4], c2, nref);
             if (step >= 1 && step - 1 < n_e) pr[step - 1] = __builtin_amdgcn_exp2f(y[step - 1]);
             if (step >= 2) l[(step - 2) / 4][(step - 2) % 4] += pr[step - 2];
             SV_STAGE_FENCE();

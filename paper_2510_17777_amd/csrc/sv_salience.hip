@@ -93,8 +93,7 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) st.w[wave][kb][lane] = kfetch[kb];
     };
-    // the ragged last stage of the keys (or a block shorter than one stage) and every tile of an exact sweep: a
-    // reference per row kept as the exact running maximum, dead columns masked
+    // every tile of an exact sweep: a reference per row kept as the exact running maximum, dead columns masked
     auto masked_tile = [&](int k0, const KeyStage<KB>& st, int kt) {
         half8_t kf[KB];
         read_key_tile<KB>(st, kt, lane, kf);
@@ -115,9 +114,9 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
             }
         }
     };
-    // One sweep over the key block.  On the fast path the full stages run in a loop of their own -- references from
-    // the first 16 keys, then multiply-add, exponential, add per element -- and the ragged last stage follows on the
-    // masked path; the exact sweep (blocks whose fast sums left the trusted range) takes the masked path for every
+    // One sweep over the key block.  On the fast path every stage, the ragged last one included, runs in one loop --
+    // references from the first 16 keys, then multiply-add, exponential, add per element, dead columns masked through
+    // the reference --; the exact sweep (blocks whose fast sums left the trusted range) takes the masked path for every
     // tile.  The loops are separate and instantiated once per count of live row tiles, chosen outside them:
     // a stage loop that can take either path, or a switch inside it, costs the registers that decide between two and
     // three wavefronts per SIMD.  No branch around the fetch and the store of the next stage: past the end they are
@@ -155,22 +154,19 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
     auto run_fast = [&](auto ntl_c) __attribute__((always_inline)) {
         constexpr int NTL = decltype(ntl_c)::value;
         start();
-        int cur = 0, s0 = key0;
-        if (s0 + kStageKeys <= k_end) {
-            const float ref_w = rowstat_init_ref<KB, NTL>(stage[0], lane, wave, rot, min(n - row0, kRowsPerGroup), qa, c2);   // wave-uniform
-            for (; s0 + kStageKeys <= k_end; s0 += kStageKeys) {
-                fetch(s0 + kStageKeys);
-                rowstat_fast_stage<KB, NTL>(stage[cur], lane, qa, c2, ref_w, l);
-                put(stage[cur ^ 1]);
-                __syncthreads();
-                cur ^= 1;
-            }
-#pragma unroll
-            for (int t = 0; t < NTL; ++t)   // from here on every row carries its own reference
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) ref[t][rr] = ref_w;
+        int cur = 0;
+        const float ref_w = rowstat_init_ref<KB, NTL>(stage[0], lane, wave, rot, min(n - row0, kRowsPerGroup), qa, c2);   // wave-uniform
+        for (int s0 = key0; s0 < k_end; s0 += kStageKeys) {   // the ragged last stage included: its dead columns add 0
+            fetch(s0 + kStageKeys);
+            rowstat_fast_stage<KB, NTL>(stage[cur], lane, qa, c2, ref_w, min(k_end - s0, kStageKeys), l);
+            put(stage[cur ^ 1]);
+            __syncthreads();
+            cur ^= 1;
         }
-        if (s0 < k_end) masked_stage(s0, stage[cur]);   // the ragged last stage: already stored by the loop above
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)   // from here on every row carries its own reference
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) ref[t][rr] = ref_w;
     };
     auto sweep_fast = [&]() __attribute__((always_inline)) {
         switch (ntl) {   // wave-uniform
@@ -184,13 +180,14 @@ __global__ __launch_bounds__(kMassThreads) __attribute__((amdgpu_waves_per_eu(SV
     sweep_fast();
     // did the sum of a live row leave the range in which it is trusted (inf, NaN, huge or tiny: logits far from the
     // wavefront's reference)?
+    const bool sees_a_key = row < k_end - key0;   // a block of fewer than 16 keys leaves lanes without a live column: sum 0
     bool bad = false;
 #pragma unroll
     for (int t = 0; t < kTilesPerWave; ++t)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
             const bool live_row = t < ntl && row0 + row_tile_of(wave, rot, t) * 16 + 4 * quad + rr < n;
-            bad |= live_row && !(l[t][rr] < kSumLimit && l[t][rr] >= 1.f / kSumLimit);
+            bad |= live_row && sees_a_key && !(l[t][rr] < kSumLimit && l[t][rr] >= 1.f / kSumLimit);
         }
     if (block_any(bad, &s_flag)) run_exact();   // block-uniform
     // merge the 16 key columns of a row, store per key block (natural-log units from here on)
