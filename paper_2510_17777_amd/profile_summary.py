@@ -16,6 +16,19 @@ then, anywhere the CSVs are:
   python -m paper_2510_17777_amd.profile_summary --config N --dir DIR --out profiles [--head GIT_REVISION]
 
 writes profiles/decode_step_cfgN_kernel_trace.txt and profiles/decode_step_cfgN_traffic_and_lds.txt.
+
+The kernels of `bench.py --variants` (attention-mass retrieval, encoder salience, packing; VBENCH =
+`python3 <repo>/bench.py --variants --oracle-layers 0`) have summaries of their own:
+
+  kernel trace   rocprofv3 --kernel-trace --stats -d DIR/vtrace -o v --output-format csv -- VBENCH > DIR/vbench.json
+  SQ counters    rocprofv3 --pmc SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_WAIT_INST_LDS SQ_ACTIVE_INST_LDS -d DIR/vpmc1 -o m --output-format csv -- VBENCH --steps 5 --warmup 1
+                 rocprofv3 --pmc SQ_WAIT_INST_ANY SQ_WAIT_ANY SQ_ACTIVE_INST_ANY SQ_INSTS_VALU_TRANS_F32 SQ_LDS_BANK_CONFLICT SQ_INSTS_LDS SQ_INSTS_SALU SQ_LDS_IDX_ACTIVE -d DIR/vpmc2 -o m --output-format csv -- VBENCH --steps 5 --warmup 1
+                 rocprofv3 --pmc SQ_VALU_MFMA_COEXEC_CYCLES SQ_BUSY_CU_CYCLES -d DIR/vpmc3 -o m --output-format csv -- VBENCH --steps 5 --warmup 1
+
+  python -m paper_2510_17777_amd.profile_summary --variants --dir DIR --out profiles [--head GIT_REVISION]
+
+writes profiles/variants_cfg4_kernel_trace.txt, profiles/mass_retrieval_cfg4_sq_counters.txt and
+profiles/salience_encoder_layers_sq_counters.txt.
 The counters FETCH_SIZE / WRITE_SIZE are in KiB per dispatch; each is scaled by what the same counter reads
 for the library's plain copy kernel of 1 GiB (the factor is printed in the summary).
 """
@@ -101,13 +114,118 @@ def describe(w) -> str:
             f"D={w.head_dim}, {w.dtype}, {w.n_vis} visual + {w.n_txt} text tokens, k={w.k})")
 
 
+SQ_COUNTERS = ["SQ_BUSY_CYCLES", "SQ_BUSY_CU_CYCLES", "SQ_WAVE_CYCLES", "SQ_ACTIVE_INST_ANY", "SQ_ACTIVE_INST_VALU",
+               "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_VALU_MFMA_COEXEC_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA",
+               "SQ_INSTS_VALU_TRANS_F32", "SQ_INSTS_LDS", "SQ_INSTS_SALU", "SQ_WAIT_ANY", "SQ_WAIT_INST_ANY",
+               "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_LDS", "SQ_LDS_IDX_ACTIVE", "SQ_LDS_BANK_CONFLICT"]
+SQ_COMMANDS = """Commands (one counter group per run, from /tmp on the GPU box, TMPDIR=/tmp):
+  rocprofv3 --pmc SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_ACTIVE_INST_VALU SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_WAIT_INST_LDS SQ_ACTIVE_INST_LDS \\
+      -d out -o m --output-format csv -- python3 bench.py --variants --oracle-layers 0 --steps 5 --warmup 1
+  rocprofv3 --pmc SQ_WAIT_INST_ANY SQ_WAIT_ANY SQ_ACTIVE_INST_ANY SQ_INSTS_VALU_TRANS_F32 SQ_LDS_BANK_CONFLICT SQ_INSTS_LDS SQ_INSTS_SALU SQ_LDS_IDX_ACTIVE \\
+      -d out -o m --output-format csv -- python3 bench.py --variants --oracle-layers 0 --steps 5 --warmup 1
+  rocprofv3 --pmc SQ_VALU_MFMA_COEXEC_CYCLES SQ_BUSY_CU_CYCLES \\
+      -d out -o m --output-format csv -- python3 bench.py --variants --oracle-layers 0 --steps 5 --warmup 1
+Values: mean per dispatch, summed over the chip (256 compute units, 1024 SIMDs).
+"""
+
+
+def _sq_table(C, keys, heads):
+    o = ["%-28s" % "counter" + "".join("%26s" % h for h in heads)]
+    for c in SQ_COUNTERS:
+        o.append("%-28s" % c + "".join("%26.4g" % C[k].get(c, float("nan")) for k in keys))
+    return "\n".join(o)
+
+
+def _sq_reading(d, label):
+    """What the counters of one kernel say about the two pipes: SQ_ACTIVE_INST_VALU counts issue slots of 4 cycles
+    (1 per ordinary vector or matrix instruction, 2 per exponential); a matrix instruction keeps its pipe busy 16."""
+    cu = d["SQ_BUSY_CU_CYCLES"] / 256
+    el = d["SQ_INSTS_VALU_TRANS_F32"] / 1024
+    mf, va, co = d["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024, d["SQ_ACTIVE_INST_VALU"] * 4 / 1024, d["SQ_VALU_MFMA_COEXEC_CYCLES"] / 1024
+    return ("  %s: %.0f k cycles per compute unit; per SIMD the matrix pipe is busy %.0f k cycles (%.0f %%), vector issue %.0f k cycles\n"
+            "      (%.0f %%), both at once %.0f k cycles: %.1f cycles per (row, key) element and lane; matrix %.1f + vector %.1f if the two pipes never\n"
+            "      overlapped, %.1f if they overlapped fully."
+            % (label, cu / 1e3, mf / 1e3, 100 * mf / cu, va / 1e3, 100 * va / cu, co / 1e3, cu / el, mf / el, va / el, max(mf, va) / el))
+
+
+def variants_main(args):
+    D = args.dir
+    bj = json.loads([ln for ln in open(os.path.join(D, "vbench.json")) if ln.startswith("{")][-1])
+    v = bj["variants"]
+    src = bj.get("source_id", "unknown")
+    head = f"git {args.head}, " if args.head else ""
+    mine = ("mass_", "salience_", "pack_kernel", "scores_filter_kernel")
+    st = collections.OrderedDict((k, x) for k, x in kernel_stats(os.path.join(D, "vtrace")).items() if k[0].startswith(mine))
+    o = ["Kernel-trace summary of the variants measured beside the decode step (bench.py --variants), long-video workload",
+         "(cfg4: 28 layers folded, 28q/4kv heads, D=128, fp16, 50176 visual + 1024 text tokens, k=2509), one MI355X.",
+         f"source_id = {src}   ({head}hash of csrc/ and include/ as bench.py prints it)", "",
+         "Command (from /tmp on the GPU box, TMPDIR=/tmp):",
+         "  rocprofv3 --kernel-trace --stats -d out -o v --output-format csv -- python3 bench.py --variants --oracle-layers 0",
+         "(the variants call sv_score_visual_mass with a 32-token question, sv_topk_select on its masses (scores_filter_kernel,",
+         " then select_filtered_kernel), sv_pack_selected, sv_sparse_decode_attn gathered / packed / dense and over a keep-ratio",
+         " sweep, and sv_salience_self on three encoder-shaped layers -- 256 frames x 729 tokens, one sequence of 16384 tokens and",
+         " one of 100000 tokens, 16 heads, head dim padded to 96; rows are per (kernel, grid size in work-items), which keeps the",
+         " three salience shapes apart; the attention and scoring kernels are listed in the decode-step summaries.)", "",
+         "%-30s %10s %6s %10s %10s %10s" % ("kernel", "work-items", "calls", "avg_us", "min_us", "max_us")]
+    for (k, grid), (calls, avg, pct, lo, hi) in st.items():
+        o.append("%-30s %10d %6d %10.1f %10.1f %10.1f" % (k, grid, calls, avg, lo, hi))
+    o += ["", "bench.py --variants of the same run (medians of event-timed calls, under the tracer): retrieval by attention mass,",
+          "32-token question: %.0f us = %.0f TFLOP/s of QK^T on the matrix cores, %.0f G exponentials/s; sv_topk_select on the masses %.1f us;"
+          % (v["retrieval_mass_32tok_us"], v["retrieval_mass_TFLOPs"], v["retrieval_mass_Gexp_per_s"], v["select_after_mass_us"]),
+          "sv_pack_selected %.1f us; attention gathered %.1f us, packed %.1f us, dense %.1f us.  sv_salience_self:"
+          % (v["pack_us"], v["attn_gathered_us"], v["attn_packed_us"], v["attn_dense_us"])]
+    for e in v["encoder_salience"]:
+        o.append("  %-40s %8.1f us = %.0f TFLOP/s of QK^T, %.0f G exponentials/s, %.3f of the vector-issue bound"
+                 % (e["workload"], e["us"], e["QK_TFLOPs"], e["Gexp_per_s"], e["frac_of_vector_issue_peak"]))
+    os.makedirs(args.out, exist_ok=True)
+    open(os.path.join(args.out, "variants_cfg4_kernel_trace.txt"), "w").write("\n".join(o) + "\n")
+    print("\n".join(o))
+
+    C = {}
+    for sub in ("vpmc1", "vpmc2", "vpmc3"):
+        for key, d in counters(os.path.join(D, sub)).items():
+            if "rowstat" in key[0] or "colsum" in key[0]:
+                C.setdefault(key, {}).update(d)
+    m_row, m_col = largest_grid(C, "mass_rowstat"), largest_grid(C, "mass_colsum")
+    o = ["SQ counters of the attention-mass retrieval kernels (sv_score_visual_mass, 32-token question), long-video workload",
+         "(cfg4: 28 layers folded, 28q/4kv heads -> 224 query rows per kv head, D=128, fp16, 50176 visual + 1024 text keys), one MI355X.",
+         f"source_id = {src}   ({head}hash of csrc/ and include/ as bench.py prints it)", "", SQ_COMMANDS,
+         _sq_table(C, [m_row, m_col], ["mass_rowstat_kernel<128>", "mass_colsum_kernel<128>"]), "",
+         "Reading (SQ_ACTIVE_INST_VALU counts issue slots of 4 cycles: 1 per ordinary vector or matrix instruction, 2 per",
+         "exponential; a matrix instruction keeps the matrix pipe busy for 16 cycles; both kernels at 3 wavefronts per SIMD):",
+         _sq_reading(C[m_row], "rowstat"), _sq_reading(C[m_col], "colsum")]
+    open(os.path.join(args.out, "mass_retrieval_cfg4_sq_counters.txt"), "w").write("\n".join(o) + "\n")
+    print("\n".join(o[-3:]))
+
+    sal = sorted((k for k in C if k[0].startswith("salience")), key=lambda k: (k[1], k[0]))
+    # shapes by grid size: A = one sequence of 16384 tokens (3072 workgroups), B = 256 frames of 729 tokens (12288)
+    want = {"A": 3072 * 256, "B": 12288 * 256}
+    pick = [(tag, kern, next((k for k in sal if k[0] == kern and k[1] == grid), None))
+            for tag, grid in want.items() for kern in ("salience_rowstat_kernel", "salience_colsum_kernel")]
+    pick = [(tag, kern, k) for tag, kern, k in pick if k is not None]
+    o = ["SQ counters of the query-agnostic salience kernels (sv_salience_self) on two of the encoder-shaped layers that",
+         "bench.py --variants runs (synthetic q, k; 16 heads, head dim zero-padded to 96, fp16), one MI355X:",
+         "  A: one sequence of 16384 tokens (grid of 786432 work-items = 3072 workgroups in both passes)",
+         "  B: 256 frames of 729 tokens     (grid of 3145728 work-items = 12288 workgroups)",
+         f"source_id = {src}   ({head}hash of csrc/ and include/ as bench.py prints it)", "", SQ_COMMANDS,
+         _sq_table(C, [k for _, _, k in pick], ["%s %s<96>" % (tag, kern.split("_")[1]) for tag, kern, _ in pick]), "",
+         "Reading (issue slots of 4 cycles: 1 per ordinary vector or matrix instruction, 2 per exponential; at head dim 96 an",
+         "element takes three matrix instructions of 16 cycles per 4 elements, 12 cycles per element; 3 wavefronts per SIMD):"]
+    o += [_sq_reading(C[k], "%s %s" % (tag, kern.split("_")[1])) for tag, kern, k in pick]
+    open(os.path.join(args.out, "salience_encoder_layers_sq_counters.txt"), "w").write("\n".join(o) + "\n")
+    print("\n".join(o[-4:]))
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--config", type=int, required=True)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--variants", action="store_true", help="summarise the runs of bench.py --variants instead")
     ap.add_argument("--dir", required=True, help="directory holding trace/ fetch/ write/ lds/ cal_f/ cal_w/ and bench.json")
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
     ap.add_argument("--head", default="", help="git revision of the sources the runs were made with")
     args = ap.parse_args()
+    if args.variants:
+        return variants_main(args)
     import sv_inputs
     w = sv_inputs.workload(args.config)
     D = args.dir
