@@ -337,6 +337,49 @@ def test_step_captured_in_a_hip_graph_replays_exactly_with_fresh_queries():
         assert np.array_equal(got["idx"], want_idx) and np.array_equal(got["count"], want_cnt), trial
 
 
+def test_per_layer_attention_calls_captured_in_a_hip_graph_replay_exactly():
+    """The decode loop of one token as a caller under graph capture issues it: one sv_sparse_decode_attn per layer on
+    packed rows, all captured into one graph.  Replayed several times with fresh queries written into the captured
+    buffer, eager calls and synchronisations in between: every replay equals the eager calls bit for bit and the
+    oracle's attention over the kept rows within the bar."""
+    import paper_2510_17777_amd as sv
+    L, Hkv, G, D, Nv, Nt, k = 3, 2, 7, 128, 6000, 300, 640
+    inp = rand_inputs(123, L, Hkv * G, Hkv, D, Nv, Nt, np.float16)
+    r = run_step(inp, k)
+    d, buf = r["dev"], r["buf"]
+    k_pack = torch.empty((L, Hkv, k, D), dtype=torch.float16, device="cuda:0")
+    v_pack = torch.empty_like(k_pack)
+    sv.sv_pack_selected(r["shape"], d["k_vis"], d["v_vis"], buf.idx, buf.count, k_pack, v_pack)
+    sls = [slice(l, l + 1) for l in range(L)]
+    shapes = [sv.make_shape(d["q"][sl], k_pack[sl], d["k_txt"][sl], k) for sl in sls]
+    ws = torch.empty((sv.workspace_bytes(shapes[0]),), dtype=torch.uint8, device="cuda:0")
+    out_g, lse_g = torch.empty_like(buf.out), torch.empty_like(buf.lse)
+    out_e, lse_e = torch.empty_like(buf.out), torch.empty_like(buf.lse)
+
+    def token(out, lse):
+        for shp, sl in zip(shapes, sls):
+            sv.sv_sparse_decode_attn(shp, d["q"][sl], k_pack[sl], v_pack[sl], d["k_txt"][sl], d["v_txt"][sl], None,
+                                     buf.count[sl], out[sl], lse[sl], ws)
+    token(out_g, lse_g)            # outside the capture first: one-time host set-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        token(out_g, lse_g)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    for trial in range(4):
+        q = rng.standard_normal(inp["q"].shape, dtype=np.float32).astype(np.float16)
+        d["q"].copy_(torch.from_numpy(q))
+        out_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        token(out_e, lse_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(lse_g, lse_e), trial
+        oa, ol, _ = oracle.sparse_decode_attn(q, inp["k_vis"], inp["v_vis"], inp["k_txt"], inp["v_txt"], r["idx"], r["count"])
+        assert np.abs(out_g.cpu().numpy() - oa).max() <= 2e-3 and np.abs(lse_g.cpu().numpy() - ol).max() <= 2e-3, trial
+
+
 @pytest.mark.parametrize("case", range(40))
 def test_seeded_random_shapes_match_the_oracle(case):
     """Shapes nobody chose by hand: batch, heads, group size, head_dim, dtype, lengths (ragged or not), k and
