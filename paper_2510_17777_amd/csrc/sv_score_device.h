@@ -25,10 +25,21 @@ __device__ __forceinline__ void summed_query(const ScoreArgs& a, int b, int g, i
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qs[i] = 0.f;
     const T* qp = static_cast<const T*>(a.q) + (int64_t)b * a.q_sb + (int64_t)g * a.G * a.q_sh + c * EPL;
-    for (int h = 0; h < a.G; ++h) {
-        const Chunk<T> qc = load_chunk(qp + (int64_t)h * a.q_sh);
+    // Eight rows are requested at once (on clamped row numbers) and then added in row order: a loop of load, wait,
+    // add per head is G trips through the cache in front of every tile -- 3.6 us of a 13.6 us scoring launch over one
+    // layer of a long video, measured.  The order of the additions, and with it every bit of the sum, is unchanged.
+    constexpr int kRowsInFlight = 8;
+    for (int h0 = 0; h0 < a.G; h0 += kRowsInFlight) {
+        Chunk<T> qc[kRowsInFlight];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) qs[i] += qc.at(i);
+        for (int j = 0; j < kRowsInFlight; ++j) qc[j] = load_chunk(qp + (int64_t)min(h0 + j, a.G - 1) * a.q_sh);
+#pragma unroll
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            if (h0 + j < a.G) {
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) qs[i] += qc[j].at(i);
+            }
+        }
     }
 }
 
