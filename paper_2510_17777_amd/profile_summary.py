@@ -2,7 +2,7 @@
 
 The summaries are what the roofline figures of bench.py are checked against, so they must be
 reproducible from the repository alone.  Every run below starts from /tmp on the GPU machine
-(`cd /tmp && export TMPDIR=/tmp`), BENCH = `python3 <repo>/bench.py --config N --oracle-layers 0`:
+(`cd /tmp && export TMPDIR=/tmp`), BENCH = `python3 <repo>/bench.py --config N --oracle-layers 0 --no-other-configs`:
 
   kernel trace   rocprofv3 --kernel-trace --stats -d DIR/trace -o t --output-format csv -- BENCH --steps 20 --warmup 3 > DIR/bench.json
   HBM reads      rocprofv3 --pmc FETCH_SIZE -d DIR/fetch -o f --output-format csv -- BENCH --steps 3 --warmup 1
@@ -232,7 +232,7 @@ def main():
     bj = json.loads([ln for ln in open(os.path.join(D, "bench.json")) if ln.startswith("{")][-1])
     src = bj.get("source_id", "unknown")
     head = f"git {args.head}, " if args.head else ""
-    bench = f"python3 bench.py --config {w.cfg} --oracle-layers 0"
+    bench = f"python3 bench.py --config {w.cfg} --oracle-layers 0 --no-other-configs"
 
     st = kernel_stats(os.path.join(D, "trace"))
     o = [f"Kernel-trace summary of the sparse decode step, {describe(w)}, one MI355X.",
