@@ -55,6 +55,52 @@ def measured_traffic(cfg: int):
     return val, f"{rel} (rocprofv3 --pmc runs of this command, sources {src or 'unknown'}; not measured in this run)"
 
 
+MFMA_FP16_PEAK_TFLOPS = 2500.0     # dense fp16 matrix-core peak of the device
+
+
+def read_clocks_MHz():
+    """Current shader and memory clock levels from sysfs (best effort; None where unreadable).  Read while work is
+    queued on the device: starting another program from a process that holds the GPU is not an option."""
+    clocks = {}
+    try:
+        for name in ("sclk", "mclk"):
+            for path in sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{name}")):
+                cur = [ln for ln in open(path).read().splitlines() if ln.rstrip().endswith("*")]
+                if cur:
+                    clocks[f"{name}_MHz"] = int("".join(ch for ch in cur[0].split(":")[1] if ch.isdigit()))
+                    break
+    except Exception:   # noqa: BLE001 - files may be missing or unreadable
+        return None
+    return clocks or None
+
+
+def sclk_under(torch, fn, seconds=0.15):
+    """Shader clock (MHz) read while calls of fn are queued for about `seconds`; None if unreadable."""
+    fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    fn()
+    torch.cuda.synchronize()
+    one = max(time.perf_counter() - t0, 1e-6)
+    for _ in range(max(2, int(seconds / one))):
+        fn()
+    c = read_clocks_MHz()
+    torch.cuda.synchronize()
+    return None if not c else c.get("sclk_MHz")
+
+
+def issue_bound_fractions(rate_element_passes, sclk_MHz):
+    """An (query, key, head) element-pass of the attention-mass kernels is a matrix instruction, a multiply-add, an
+    exponential (two slots) and an add: five 4-cycle issue slots for 64 lanes per SIMD.  Fraction of that bound at the
+    nominal 2.4 GHz and at the clock the device held under this very load."""
+    out = {"frac_of_vector_issue_peak": round(rate_element_passes / VALU_ISSUE_PEAK_ELEMENT_PASSES, 3)}
+    if sclk_MHz:
+        out["sclk_MHz_under_this_load"] = sclk_MHz
+        out["frac_of_vector_issue_bound_at_that_clock"] = round(
+            rate_element_passes / (VALU_ISSUE_PEAK_ELEMENT_PASSES * sclk_MHz / 2400.0), 3)
+    return out
+
+
 def time_variants(sv, torch, w, d, shape, buf, reps):
     """Event-timed variants around the step (all on the workload's own tensors, idx/count as the step left them):
     gathered attention per decoded token, packing + attention on the packed rows (the paper's once-per-round
@@ -103,7 +149,11 @@ def time_variants(sv, torch, w, d, shape, buf, reps):
         keys = int(shape.n_vis_max if shape.vis_len is None else shape.vis_len.sum().item() / B)
         flop = 2.0 * 2 * B * Hkv * rows * (keys + shape.n_txt_max) * D      # two passes of QK^T
         out["retrieval_mass_TFLOPs"] = round(flop / (out["retrieval_mass_32tok_us"] * 1e-6) / 1e12, 1)
-        out["retrieval_mass_Gexp_per_s"] = round(2.0 * B * Hkv * rows * keys / (out["retrieval_mass_32tok_us"] * 1e-6) / 1e9, 1)
+        out["retrieval_mass_frac_of_fp16_mfma_peak"] = round(out["retrieval_mass_TFLOPs"] / MFMA_FP16_PEAK_TFLOPS, 3)
+        rate = 2.0 * B * Hkv * rows * keys / (out["retrieval_mass_32tok_us"] * 1e-6)
+        out["retrieval_mass_Gexp_per_s"] = round(rate / 1e9, 1)
+        out["retrieval_mass_bounds"] = issue_bound_fractions(
+            rate, sclk_under(torch, lambda: sv.sv_score_visual_mass(mshape, qm, d["k_vis"], d["k_txt"], mscores, None, mws)))
         out["select_after_mass_us"] = timed(lambda: sv.sv_topk_select(shape, mscores, buf.idx, buf.count, buf.workspace))
         # leave idx/count as the step produced them for whatever follows
         sv.sv_decode_step(shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], None, buf.idx, buf.count,
@@ -173,10 +223,12 @@ def time_encoder_salience(sv, torch, reps):
         us = float(np.median([a.elapsed_time(b) * 1e3 for a, b in evs]))
         elements = float(B) * H * N * N
         rate = 2.0 * elements / (us * 1e-6)          # element-passes per second (two passes)
+        tflops = 2 * 2 * elements * D / (us * 1e-6) / 1e12
+        sclk = sclk_under(torch, lambda: sv.sv_salience_self(shape, q, k, sal, None, ws)) if N < 50000 else None
         out.append({"workload": name, "tokens": N, "batch": B, "heads": H, "head_dim": d_head, "padded_head_dim": D,
-                    "us": round(us, 1), "QK_TFLOPs": round(2 * 2 * elements * D / (us * 1e-6) / 1e12, 1),
-                    "Gexp_per_s": round(rate / 1e9, 1),
-                    "frac_of_vector_issue_peak": round(rate / VALU_ISSUE_PEAK_ELEMENT_PASSES, 3),
+                    "us": round(us, 1), "QK_TFLOPs": round(tflops, 1),
+                    "frac_of_fp16_mfma_peak": round(tflops / MFMA_FP16_PEAK_TFLOPS, 3),
+                    "Gexp_per_s": round(rate / 1e9, 1), **issue_bound_fractions(rate, sclk),
                     "salience_sums_to_one_max_dev": float((sal.double().sum(dim=1) - 1.0).abs().max()),
                     "workspace_MB": round(ws.numel() / 1e6, 1)})
         del q, k, sal, ws
@@ -478,22 +530,10 @@ def main():
 
     # Clocks while the device is busy with steps (best effort; the box decides power state and clocks).
     # Read from sysfs: starting another program from a process that holds the GPU is not an option.
-    clocks = None
-    try:
-        for i in range(max(200, int(0.2 / (us_per_step * 1e-6)))):
-            step(i)
-        clocks = {}
-        for name in ("sclk", "mclk"):
-            for path in sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{name}")):
-                cur = [ln for ln in open(path).read().splitlines() if ln.rstrip().endswith("*")]
-                if cur:
-                    clocks[f"{name}_MHz"] = int("".join(ch for ch in cur[0].split(":")[1] if ch.isdigit()))
-                    break
-        torch.cuda.synchronize()
-        clocks = clocks or None
-    except Exception:   # noqa: BLE001 - files may be missing or unreadable
-        torch.cuda.synchronize()
-        clocks = None
+    for i in range(max(200, int(0.2 / (us_per_step * 1e-6)))):
+        step(i)
+    clocks = read_clocks_MHz()
+    torch.cuda.synchronize()
 
     # Leave the buffers of copy 0 holding the result of a step with query 0 for the parity report.
     pr.step(0)
