@@ -282,6 +282,59 @@ def test_rows_of_hundreds_of_thousands_of_tokens(B, Hkv, G, D, dtype, Nv, Nt, k,
     assert_step_matches(inp, k, vis_len=vis_len, label=f"long rows Nv={Nv} k={k}")
 
 
+def test_caches_of_more_than_two_to_the_31_elements():
+    """96 long-video layers folded into one call: the visual K and V tensors hold 2.47 G elements each (4.9 GB), so
+    element offsets of the later batch entries do not fit 32 bits.  Inputs are drawn on the device; the batch entry
+    that straddles offset 2^31, its neighbour and the last one are copied back and checked in full against the
+    oracle, the first against it as well, and all against the same call on that entry alone (bit for bit)."""
+    import paper_2510_17777_amd as sv
+    B, Hkv, G, D, Nv, Nt, k = 96, 4, 7, 128, 50176, 256, 500
+    per_b = Hkv * Nv * D
+    assert B * per_b > 2 ** 31 and (2 ** 31) // per_b == 83
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(4242)
+    rnd = lambda *shape: torch.randn(shape, device=dev, dtype=torch.float16, generator=g)
+    d = dict(q=rnd(B, Hkv * G, D), k_vis=rnd(B, Hkv, Nv, D), v_vis=rnd(B, Hkv, Nv, D), k_txt=rnd(B, Hkv, Nt, D),
+             v_txt=rnd(B, Hkv, Nt, D))
+    shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], k)
+    buf = sv.DecodeBuffers(shape, dev, with_scores=True)
+    buf.idx.fill_(-7); buf.out.fill_(float("nan"))
+    sv.sv_decode_step(shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], buf.scores, buf.idx, buf.count,
+                      buf.out, buf.lse, buf.workspace)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(buf.out).all()) and bool((buf.count == k).all())
+    for b in (0, 83, 84, 95):
+        sl = slice(b, b + 1)
+        one = {n: t[sl].contiguous() for n, t in d.items()}
+        s1 = sv.make_shape(one["q"], one["k_vis"], one["k_txt"], k)
+        b1 = sv.DecodeBuffers(s1, dev, with_scores=True)
+        sv.sv_decode_step(s1, one["q"], one["k_vis"], one["v_vis"], one["k_txt"], one["v_txt"], b1.scores, b1.idx, b1.count,
+                          b1.out, b1.lse, b1.workspace)
+        torch.cuda.synchronize()
+        assert torch.equal(b1.scores[0], buf.scores[b]) and torch.equal(b1.idx[0], buf.idx[b]), b
+        assert float((b1.out[0] - buf.out[b]).abs().max()) <= 2e-3, b     # the attention plan differs with the batch
+        host = {n: t.cpu().numpy() for n, t in one.items()}
+        o = oracle.decode_step(host["q"], host["k_vis"], host["v_vis"], host["k_txt"], host["v_txt"], k)
+        idx, cnt = buf.idx[sl].cpu().numpy(), buf.count[sl].cpu().numpy()
+        assert check_index_sets(o["scores"], k, None, idx, cnt).ok, b
+        oa, ol, _ = oracle.sparse_decode_attn(host["q"], host["k_vis"], host["v_vis"], host["k_txt"], host["v_txt"], idx, cnt)
+        assert np.abs(buf.out[sl].cpu().numpy() - oa).max() <= 2e-3 and np.abs(buf.lse[sl].cpu().numpy() - ol).max() <= 2e-3, b
+
+
+@pytest.mark.parametrize("B,Hkv,G,D,dtype", [(65535, 1, 2, 64, np.float16), (30000, 2, 1, 128, np.float32)])
+def test_very_large_batches_of_small_sequences(B, Hkv, G, D, dtype):
+    """The batch is a grid dimension of every kernel: its largest value (65535) and tens of thousands of tiny
+    sequences with ragged lengths, whole rule set."""
+    Nv, Nt, k = 80, 12, 9
+    inp = rand_inputs(777 + D, B, Hkv * G, Hkv, D, Nv, Nt, dtype)
+    rng = np.random.default_rng(778)
+    vis_len = rng.integers(0, Nv, size=B, endpoint=True).astype(np.int32)
+    txt_len = rng.integers(0, Nt, size=B, endpoint=True).astype(np.int32)
+    rep = assert_step_matches(inp, k, vis_len=vis_len, txt_len=txt_len, label=f"B={B}")
+    assert rep.problems == B * Hkv
+
+
 def test_filtered_selection_degenerate_rows():
     """All keys equal (every row is a candidate: more than fit on chip -> whole-row fallback), rows
     shorter than k, shorter than the sample, and empty rows, on a shape that takes the filtered path."""
