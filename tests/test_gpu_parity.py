@@ -322,6 +322,51 @@ def test_caches_of_more_than_two_to_the_31_elements():
         assert np.abs(buf.out[sl].cpu().numpy() - oa).max() <= 2e-3 and np.abs(buf.lse[sl].cpu().numpy() - ol).max() <= 2e-3, b
 
 
+def test_two_host_threads_on_two_streams_with_workspaces_of_their_own():
+    """The library keeps no state between calls beyond atomic words (a call counter, the knobs, one-time kernel
+    attributes): two host threads that each drive a stream of their own, with buffers and a workspace of their own,
+    must both get exactly what a single thread gets -- on shapes that take the candidate filter (threshold words and
+    a generation word in each workspace) and on short rows."""
+    import threading
+    import paper_2510_17777_amd as sv
+    jobs = []
+    for seed, (B, Hkv, G, D, Nv, Nt, k) in enumerate([(2, 2, 7, 128, 20000, 200, 900), (3, 2, 4, 128, 3000, 64, 200)]):
+        inp = rand_inputs(600 + seed, B, Hkv * G, Hkv, D, Nv, Nt, np.float16)
+        ref = run_step(inp, k)
+        jobs.append((inp, k, ref))
+    results, errors = {}, []
+
+    def worker(slot):
+        try:
+            inp, k, ref = jobs[slot]
+            stream = torch.cuda.Stream()                       # default priority
+            with torch.cuda.stream(stream):
+                d = ref["dev"]
+                shape = sv.make_shape(d["q"], d["k_vis"], d["k_txt"], k)
+                buf = sv.DecodeBuffers(shape, "cuda:0")
+                outs = []
+                for _ in range(25):
+                    buf.out.fill_(float("nan"))
+                    sv.sv_decode_step(shape, d["q"], d["k_vis"], d["v_vis"], d["k_txt"], d["v_txt"], buf.scores, buf.idx,
+                                      buf.count, buf.out, buf.lse, buf.workspace, stream=stream)
+                    outs.append((buf.idx.clone(), buf.count.clone(), buf.out.clone(), buf.lse.clone()))
+                stream.synchronize()
+            results[slot] = outs
+        except Exception as e:   # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for slot, (inp, k, ref) in enumerate(jobs):
+        for idx, cnt, out, lse in results[slot]:
+            assert np.array_equal(idx.cpu().numpy(), ref["idx"]) and np.array_equal(cnt.cpu().numpy(), ref["count"]), slot
+            assert np.array_equal(out.cpu().numpy(), ref["out"]) and np.array_equal(lse.cpu().numpy(), ref["lse"]), slot
+
+
 @pytest.mark.parametrize("B,Hkv,G,D,dtype", [(65535, 1, 2, 64, np.float16), (30000, 2, 1, 128, np.float32)])
 def test_very_large_batches_of_small_sequences(B, Hkv, G, D, dtype):
     """The batch is a grid dimension of every kernel: its largest value (65535) and tens of thousands of tiny
