@@ -12,7 +12,7 @@ export UBSAN_OPTIONS=print_stacktrace=1:halt_on_error=1
 
 echo "== oracle under gcc ASan + UBSan"
 SV_ORACLE_SANITIZE=1 LD_PRELOAD="$(gcc -print-file-name=libasan.so)" \
-    python -m pytest tests/test_oracle_pins.py tests/test_compare_rules.py tests/test_inputs.py -q -x -p no:cacheprovider
+    python -m pytest tests/test_oracle_pins.py tests/test_oracle_properties.py tests/test_compare_rules.py tests/test_inputs.py -q -x -p no:cacheprovider
 
 echo "== host code of libsparsevila under clang ASan + UBSan"
 python -m paper_2510_17777_amd.build --host-sanitize
