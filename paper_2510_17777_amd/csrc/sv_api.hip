@@ -429,6 +429,9 @@ sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, 
             if (tune.filter_samples > 0) sa.filt.n_samples = tune.filter_samples;
             sa.filt.epoch = g_epoch.fetch_add(1u, std::memory_order_relaxed);
             sa.write_scores = scores != nullptr;   // nobody asked for the scores: do not spend HBM writes on them
+            // Scratch for a spread sample (2 KB per (b, g)): the head of the workspace's score region, which this launch
+            // does not write (the scores go to the caller's buffer or nowhere; a row the selection re-scores comes later).
+            sa.filt.samples = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + w.scores_off);
         }
         hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;

@@ -30,7 +30,11 @@ struct FilterArgs {
     uint32_t* gen;          // [1] bumped by every filtered selection: added to epoch on the device, so that replays
                             // of a captured call (same arguments, same epoch) still tag their hint words apart
     int32_t test_mode;      // 0; tests: every third tile ignores the hint (1: keeps nothing, 2: keeps all)
-    int32_t n_samples;      // rows a sampler scores: 512, or 256 in a launch so small that it waits for its samplers
+    int32_t n_samples;      // rows sampled per (b, g): 512, or 256 in a launch so small that it waits for its samplers
+    uint64_t* samples;      // [units][256] {epoch << 32 | score bits}: the sample scores of a spread sample; may be nullptr
+    int32_t spread;         // set by the launcher: sampler workgroups per (b, g).  1: one workgroup scores the whole sample
+                            // in rounds of dependent loads; > 1 (256 samples, `samples` given): each scores its share in
+                            // ONE round and publishes the scores, the first of them ranks all 256 and publishes t_lo
 };
 
 struct ScoreArgs {

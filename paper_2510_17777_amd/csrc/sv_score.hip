@@ -160,6 +160,83 @@ __device__ __forceinline__ void sample_threshold(const ScoreArgs& a, int b, int 
     if (tid == 0) publish_hint(a, unit, t_lo);
 }
 
+// Rows of the sample one round of loads of a sampler workgroup covers (U loads per lane, as in sample_threshold).
+template <typename T, int D>
+constexpr int sampler_round_rows() {
+    return kScoreWaves * (kScoreUnroll / 2) * (kWave / (D / Chunk<T>::kElems));
+}
+
+// SPREAD sampling, for launches so small that all their tiles are resident at once and have streamed their rows before
+// one sampler workgroup has walked through its chain of dependent trips (lengths, query, four rounds of sample rows,
+// rank search: 9 us, where the tiles of one layer of a long video are done after 6).  The 256 sample rows of a (b, g)
+// are dealt over `spread` sampler workgroups; each scores its share in ONE round of loads and publishes the scores as
+// tagged words {epoch, score}; workgroup 0 of the (b, g) then fetches all 256 words (a bounded wait for the others,
+// which run beside it), ranks them and publishes t_lo as sample_threshold does.  If the words never all carry this
+// call's tag it publishes "every row is a candidate", which the selection's checks cover like any other threshold.
+template <typename T, int D>
+__device__ __forceinline__ void sample_threshold_spread(const ScoreArgs& a, int b, int g, int part, float* samp) {
+    constexpr int EPL = Chunk<T>::kElems;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = kWave / LPR;
+    constexpr int U = kScoreUnroll / 2;
+    constexpr int ns = kSample / 2, WPL = ns / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int c = lane % LPR, grp = lane / LPR;
+    const int64_t unit = (int64_t)b * a.Hkv + g;
+    const int n = live_rows_of(a, b);
+    const int kb = a.filt.k < n ? a.filt.k : n;
+    if (kb == 0 || kb == n) {   // the selection handles these rows without candidates
+        if (part == 0 && tid == 0) publish_hint(a, unit, INFINITY);
+        return;
+    }
+    const int rank = a.filt.rank_override > 0 ? a.filt.rank_override : sample_rank(n, kb, ns);
+    if (rank > ns - ns / 8) {   // the sample cannot separate the top kb: every row is a candidate
+        if (part == 0 && tid == 0) publish_hint(a, unit, -INFINITY);
+        return;
+    }
+    const T* kbase = static_cast<const T*>(a.k_vis) + (int64_t)b * a.k_sb + (int64_t)g * a.k_sh + c * EPL;
+    const int i0 = part * sampler_round_rows<T, D>() + wave * U * RPW + grp;   // this lane group's first sample
+    Chunk<T> kc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) kc[u] = load_chunk(kbase + (int64_t)sample_row_of(i0 + u * RPW, n, unit, ns) * a.k_sn);
+    float qs[EPL];
+    summed_query<T>(a, b, g, c, qs);   // after the rows were requested: the two share a trip
+    const uint32_t epoch = launch_epoch(a);
+    uint64_t* words = a.filt.samples + unit * ns;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float sc = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) sc = fmaf(kc[u].at(i), qs[i], sc);
+        sc = group_sum<LPR>(sc) * a.scale;
+        if (c == 0)
+            __hip_atomic_store(words + i0 + u * RPW, ((uint64_t)epoch << 32) | (uint64_t)__float_as_uint(sc),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (part != 0 || wave != 0) return;   // no barrier below: one wavefront of one workgroup ranks
+    float t_lo = -INFINITY;
+    for (int poll = 0; poll < kHintPolls; ++poll) {
+        uint64_t w[WPL];
+#pragma unroll
+        for (int i = 0; i < WPL; ++i) w[i] = __hip_atomic_load(words + lane + i * kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool mine = true;
+#pragma unroll
+        for (int i = 0; i < WPL; ++i) mine = mine && (uint32_t)(w[i] >> 32) == epoch;
+        if (__ballot(!mine) == 0ull) {   // wave-uniform: all 256 words are this call's
+#pragma unroll
+            for (int i = 0; i < WPL; ++i) samp[lane + i * kWave] = __uint_as_float((uint32_t)w[i]);
+#pragma unroll
+            for (int i = WPL; i < kSample / kWave; ++i) samp[lane + i * kWave] = -INFINITY;   // the rank search reads kSample slots
+            __builtin_amdgcn_wave_barrier();   // LDS traffic of one wavefront stays in program order
+            t_lo = rank_statistic(samp, rank, lane);
+            if (t_lo != t_lo) t_lo = -INFINITY;   // stale words that happen to carry the tag may hold anything
+            break;
+        }
+        __builtin_amdgcn_s_sleep(16);
+    }
+    if (lane == 0) publish_hint(a, unit, t_lo);
+}
+
 // End of a tile, one wavefront: waits (bounded) for the row's threshold and stores the tile's record.
 // s_val holds the tile's scores (-inf past the live rows), s_pair is scratch for the pairs.
 __device__ __forceinline__ void emit_tile_record(const ScoreArgs& a, int64_t unit, int tile, int row_begin, int row_end,
@@ -236,11 +313,13 @@ void score_kernel(const ScoreArgs a) {
     if (kFilter) {   // linear grid: samplers first, then the tiles of unit 0, unit 1, ...
         const int units = a.B * a.Hkv;
         int id = (int)blockIdx.x;
-        if (id < units) {
-            sample_threshold<T, D>(a, id / a.Hkv, id % a.Hkv, s_val);
+        if (id < units * a.filt.spread) {   // samplers: a.filt.spread workgroups per (b, g)
+            const int u = id / a.filt.spread;
+            if (a.filt.spread > 1) sample_threshold_spread<T, D>(a, u / a.Hkv, u % a.Hkv, id - u * a.filt.spread, s_val);
+            else sample_threshold<T, D>(a, u / a.Hkv, u % a.Hkv, s_val);
             return;
         }
-        id -= units;
+        id -= units * a.filt.spread;
         const int unit = id / a.filt.n_tiles;
         tile = id - unit * a.filt.n_tiles;
         b = unit / a.Hkv;
@@ -370,7 +449,9 @@ hipError_t launch_typed(const ScoreArgs& a, hipStream_t stream) {
     if (tiles == 0 || a.B == 0) return hipSuccess;
     dim3 block(kScoreThreads);
     if (a.filt.tiles) {
-        const uint64_t blocks = (uint64_t)a.B * a.Hkv * (1u + tiles);
+        // a sample of 256 rows (a launch so small that it waits for its samplers) is spread over several sampler workgroups
+        k.filt.spread = (a.filt.n_samples == kSample / 2 && a.filt.samples) ? (kSample / 2) / sampler_round_rows<T, D>() : 1;
+        const uint64_t blocks = (uint64_t)a.B * a.Hkv * ((unsigned)k.filt.spread + tiles);
         if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
         dim3 grid((unsigned)blocks);
         if (a.stream_loads) hipLaunchKernelGGL((score_kernel<T, D, true, true>), grid, block, 0, stream, k);
@@ -389,6 +470,7 @@ hipError_t launch_scores_filter(const ScoreArgs& a, hipStream_t stream) {
     if (!a.filt.tiles || a.filt.tile_rows <= 0) return hipErrorInvalidValue;
     ScoreArgs k = a;
     k.rows_per_block = a.filt.tile_rows;
+    k.filt.spread = 1;   // given scores are sampled in one trip by one workgroup
     const int per_group = kScoreWaves * kFilterTilesPerWave;
     const int groups = (a.filt.n_tiles + per_group - 1) / per_group;   // workgroups per row
     const uint64_t blocks = (uint64_t)a.B * a.Hkv * (1u + (uint64_t)groups);

@@ -1022,6 +1022,8 @@ FilterArgs carve_filter_workspace(void* base, int dtype, int D, int B, int Hkv, 
     FilterArgs f{};
     f.hint = reinterpret_cast<uint64_t*>(p + l.hint);
     f.gen = reinterpret_cast<uint32_t*>(p + l.gen);
+    f.samples = nullptr;   // the caller may point it at units * 2 KB of scratch that the scoring launch may use
+    f.spread = 1;
     f.tiles = reinterpret_cast<uint4*>(p + l.tiles);
     f.overflow = reinterpret_cast<uint2*>(p + l.overflow);
     f.tile_rows = filter_tile_rows(dtype, D, requested_tile_rows, n_vis_max, kFiltMaxTiles);
