@@ -308,6 +308,8 @@ const char *sv_strerror(int status);
  *                           few or too many candidates makes the row fall back to the full selection)
  *   "filter_samples"        rows of that sample: 256 or 512; 0 = by the size of the scoring launch (a launch of
  *                           few tiles waits for its samplers and takes 256).  Any value gives the same result
+ *   "filter_spread"         1 (default) = a sample of 256 rows is dealt over four sampler workgroups that score it in one
+ *                           round of loads; 0 = one sampler workgroup per (b, g) scores it in rounds.  Same result
  * Unknown names and values outside a knob's range are rejected with SV_ERR_SHAPE and change nothing.
  * Process-wide.  Every knob is one atomic word and a call reads each knob once, when it starts: setting
  * a knob while calls are in flight on other threads is safe and affects calls that start later.

@@ -20,7 +20,7 @@ constexpr int kMaxGridYZ = 65535;
 // one consistent value of every knob and a concurrent sv_set_tuning cannot tear anything.
 enum Knob : int {
     kScoreRowsPerBlock, kAttnChunk, kScoreStreamLoads, kAttnMfma, kAttnBatches, kSelectFilter, kFilterRank,
-    kFilterSamples,
+    kFilterSamples, kFilterSpread,
 #ifdef SV_TEST_HOOKS
     kFilterTestMode, kStepStages,   // exist only in the test build of the library (libsparsevila_hooks.so)
 #endif
@@ -36,6 +36,7 @@ constexpr KnobSpec kKnobSpecs[kNumKnobs] = {
     {"select_filter", -1},
     {"filter_rank", 0},            // 0 = derived from k / n
     {"filter_samples", 0},         // 0 = by the size of the launch; 256 or 512
+    {"filter_spread", 1},          // 1 = a 256-row sample is spread over several sampler workgroups
 #ifdef SV_TEST_HOOKS
     {"filter_test_mode", 0},
     {"step_stages", 3},            // sv_decode_step stops after this many stages
@@ -49,7 +50,7 @@ Knobs g_knobs;
 
 struct Tuning {   // one call's view of the knobs
     int32_t score_rows_per_block, attn_chunk, score_stream_loads, attn_mfma, attn_batches, select_filter, filter_rank,
-        filter_samples, filter_test_mode, step_stages;
+        filter_samples, filter_spread, filter_test_mode, step_stages;
 };
 inline Tuning tuning_snapshot() {
     auto get = [](int k) { return g_knobs.v[k].load(std::memory_order_relaxed); };
@@ -57,6 +58,7 @@ inline Tuning tuning_snapshot() {
     t.score_rows_per_block = get(kScoreRowsPerBlock); t.attn_chunk = get(kAttnChunk);
     t.score_stream_loads = get(kScoreStreamLoads); t.attn_mfma = get(kAttnMfma); t.attn_batches = get(kAttnBatches);
     t.select_filter = get(kSelectFilter); t.filter_rank = get(kFilterRank); t.filter_samples = get(kFilterSamples);
+    t.filter_spread = get(kFilterSpread);
 #ifdef SV_TEST_HOOKS
     t.filter_test_mode = get(kFilterTestMode); t.step_stages = get(kStepStages);
 #else
@@ -431,7 +433,8 @@ sv_status decode_step_impl(const sv_shape* s, const void* q, const void* k_vis, 
             sa.write_scores = scores != nullptr;   // nobody asked for the scores: do not spend HBM writes on them
             // Scratch for a spread sample (2 KB per (b, g)): the head of the workspace's score region, which this launch
             // does not write (the scores go to the caller's buffer or nowhere; a row the selection re-scores comes later).
-            sa.filt.samples = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + w.scores_off);
+            sa.filt.samples = tune.filter_spread
+                                  ? reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + w.scores_off) : nullptr;
         }
         hipError_t e = sv::launch_score(sa, hs);
         if (e != hipSuccess) return SV_ERR_LAUNCH;
@@ -603,6 +606,7 @@ sv_status sv_set_tuning(const char* name, int32_t value) {
         case kAttnBatches: ok = value >= 0 && value <= 8; break;
         case kFilterRank: ok = value >= 0 && value <= 448; break;
         case kFilterSamples: ok = value == 0 || value == 256 || value == 512; break;
+        case kFilterSpread: ok = value == 0 || value == 1; break;
 #ifdef SV_TEST_HOOKS
         case kFilterTestMode: ok = value >= 0 && value <= 2; break;
         case kStepStages: ok = value >= 1 && value <= 3; break;

@@ -221,28 +221,32 @@ def test_filtered_selection_equals_full_selection(dtype, D, G, Nv, k):
     hooks = sv.test_hooks()     # the test build of the library: same kernel objects, plus the "filter_test_mode" knob
     hooks.__enter__()
     try:
-        for filt, rank, rows, mode, samples in [(1, 0, 0, 0, 0), (0, 0, 0, 0, 0), (1, 1, 0, 0, 0), (1, 440, 0, 0, 0),
-                                                (1, 0, 128, 0, 0), (1, 0, 1024, 0, 0), (1, 0, 0, 1, 0), (1, 0, 0, 2, 0),
-                                                (1, 300, 128, 2, 0), (1, 0, 0, 0, 256), (1, 0, 0, 0, 512),
-                                                (1, 1, 0, 0, 256), (1, 200, 64, 1, 256), (1, 230, 0, 0, 256)]:
+        # the last field: 1 = a 256-row sample is spread over four sampler workgroups (the default), 0 = one workgroup
+        for filt, rank, rows, mode, samples, spread in [
+                (1, 0, 0, 0, 0, 1), (0, 0, 0, 0, 0, 1), (1, 1, 0, 0, 0, 1), (1, 440, 0, 0, 0, 1), (1, 0, 128, 0, 0, 1),
+                (1, 0, 1024, 0, 0, 1), (1, 0, 0, 1, 0, 1), (1, 0, 0, 2, 0, 1), (1, 300, 128, 2, 0, 1), (1, 0, 0, 0, 256, 1),
+                (1, 0, 0, 0, 512, 1), (1, 1, 0, 0, 256, 1), (1, 200, 64, 1, 256, 1), (1, 230, 0, 0, 256, 1),
+                (1, 0, 0, 0, 0, 0), (1, 1, 0, 0, 256, 0), (1, 230, 0, 2, 256, 0), (1, 0, 128, 1, 0, 0)]:
+            sv.sv_set_tuning("filter_spread", spread)
             sv.sv_set_tuning("select_filter", filt)
             sv.sv_set_tuning("filter_rank", rank)
             sv.sv_set_tuning("score_rows_per_block", rows)
             sv.sv_set_tuning("filter_test_mode", mode)
             sv.sv_set_tuning("filter_samples", samples)   # 0: by the size of the launch (256 rows for these shapes)
             r = run_step(inp, k, vis_len=vis_len, dev=None if base is None else base["dev"])
-            assert _exact_sets(r, k, vis_len), (filt, rank, rows, mode, samples)
+            assert _exact_sets(r, k, vis_len), (filt, rank, rows, mode, samples, spread)
             if base is None:
                 base = r
             else:
                 for key in ("scores", "idx", "count", "out", "lse"):
-                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode, samples)
+                    assert np.array_equal(r[key], base[key]), (key, filt, rank, rows, mode, samples, spread)
             # without a scores buffer the scoring launch stores no scores at all; a row whose candidates
             # do not suffice is then re-scored by the selection itself
             r2 = run_step(inp, k, vis_len=vis_len, dev=base["dev"], with_scores=False)
             for key in ("idx", "count", "out", "lse"):
-                assert np.array_equal(r2[key], base[key]), (key, filt, rank, rows, mode, samples, "no scores buffer")
+                assert np.array_equal(r2[key], base[key]), (key, filt, rank, rows, mode, samples, spread, "no scores buffer")
     finally:
+        sv.sv_set_tuning("filter_spread", 1)
         sv.sv_set_tuning("select_filter", -1)
         sv.sv_set_tuning("filter_samples", 0)
         sv.sv_set_tuning("filter_rank", 0)
